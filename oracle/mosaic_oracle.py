@@ -1,0 +1,242 @@
+"""CPU oracle for projection-level importance scoring and mask construction.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition of what the
+HIP path must compute.  Only tests, the smoke check and the benchmark's
+cpu_baseline leg may import it; the product path never does, and this file
+imports nothing from the product package.
+
+Everything is written out in float64 NumPy, step by step, in the order and
+notation of the paper (Mosaic, arXiv 2504.06323):
+
+  * activation column norms      -- the l2 norm term of Eq. 5 / Eq. 3, gathered
+                                    over all calibration samples (Algorithm 1,
+                                    the loop over S that fills A)
+  * weight metric  omega         -- Eq. 5
+  * projection outliers O, C, R  -- Eq. 6 and the three assignments of
+                                    Algorithm 1 that follow the weight metric
+  * normalize(R_LLM) + planner   -- Algorithm 1's return value and the
+                                    Projection Planner of Section 3.3
+  * unstructured masking         -- Section 4.1.3, category 1
+  * structured removal           -- Section 4.1.3, categories 2 and 3, Fig. 4
+
+Readings taken where the paper is silent (each is listed in the design notes):
+per-input-channel norms of the tensor a projection multiplies; plain l2 norm
+with no division by the token count; one omega per parameter; strict ">" in
+Eq. 6; per-output-row selection of the k smallest omega with the lower column
+index pruned first among equals; structured group magnitude = squared l2 norm
+of the already-masked gate row + up row + down column.
+
+Parity status of each function:
+  column_sumsq / column_norms      pinned (closed forms, library norm)
+  weight_metric                    pinned (hand example, magnitude special case)
+  outlier_stats / count_above      pinned (hand example, brute force, strictness)
+  plan_sparsity                    PARITY UNPINNED against the paper: the paper gives no
+                                   formula for normalize() or for the planner's scaling;
+                                   pinned only by the invariants it states (mean = p,
+                                   more outliers => pruned less, equal ranks => uniform p)
+  select_smallest_per_row          pinned (brute-force sort, library top-k special case)
+  group_magnitude / struct_rank    PARITY UNPINNED against the paper (no formula given for
+                                   "lowest-magnitude" groups); pinned by brute force and
+                                   by the dense-equivalence invariant
+  struct_compact                   pinned (dense-equivalence of the MLP, exact gather)
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+def _f64(a) -> np.ndarray:
+    return np.asarray(a, dtype=np.float64)
+
+
+# --------------------------------------------------------------------------- norms
+
+def column_sumsq(x) -> np.ndarray:
+    """sumsq[j] = sum over tokens t of X[t, j]^2  (the square of Eq. 5's norm term)."""
+    x = _f64(x)
+    return (x * x).sum(axis=0)
+
+
+def column_norms(x) -> np.ndarray:
+    """||X[:, j]||_2 per input channel j, over every calibration token (Eq. 5, Alg. 1)."""
+    return np.sqrt(column_sumsq(x))
+
+
+# --------------------------------------------------------------------------- Eq. 5
+
+def weight_metric(w, norms) -> np.ndarray:
+    """omega[i, j] = ||A_j||_2 * |theta[i, j]|  (Eq. 5); the norm is broadcast over output rows."""
+    w = _f64(w)
+    norms = _f64(norms)
+    assert w.ndim == 2 and norms.shape == (w.shape[1],)
+    return np.abs(w) * norms[None, :]
+
+
+# --------------------------------------------------------------------------- Eq. 6
+
+def outlier_stats(omega, alpha: float):
+    """Algorithm 1, the four steps after the weight metric.
+
+    Returns (C, O, R, mean): parameter count, number of outliers
+    #{omega_i > alpha * mean(omega)} with a strict comparison (Eq. 6),
+    the projection rank R = O / C * 100, and the mean itself.
+    """
+    flat = _f64(omega).reshape(-1)          # flatten
+    c = flat.size                           # C = numel
+    mean = flat.sum() / c
+    o = int(np.count_nonzero(flat > alpha * mean))
+    return c, o, 100.0 * o / c, mean
+
+
+def count_above(scores, tau) -> int:
+    """#{scores > tau} evaluated in the dtype the scores already have.
+
+    Used for the bit-exact protocol: the kernel's own score bits and its own
+    float32 threshold go in, so the integer decision is taken in the kernel's
+    precision on both sides.
+    """
+    scores = np.asarray(scores)
+    tau = scores.dtype.type(tau)
+    return int(np.count_nonzero(scores > tau))
+
+
+def threshold_f32(alpha: float, score_sum: float, numel: int) -> np.float32:
+    """tau = alpha * mean, formed in float64 and rounded once to float32."""
+    return np.float32(np.float64(alpha) * np.float64(score_sum) / np.float64(numel))
+
+
+# --------------------------------------------------------------------------- planner
+
+def plan_sparsity(ratios, p: float, lam: float, scope: str = "global", cols=None):
+    """normalize(R_LLM) and the Projection Planner: ranks -> per-projection sparsity targets.
+
+    ratios is the N x M table R_LLM.  Within a comparison scope (all N*M
+    entries, or one projection category m across the N layers) the ranks are
+    min-max normalised to [0, 1] and spread about the scope mean:
+
+        r_hat = (R - R_min) / (R_max - R_min)
+        s     = p + 2 * lam * (mean(r_hat) - r_hat)
+
+    so that the unweighted mean of s equals p (Eq. 1 and Eq. 2), projections
+    with more outliers get a smaller target, and equal ranks give s == p
+    everywhere (global pruning).  If cols is given (N x M input widths) each
+    target is clamped to [0, 1 - 1/cols].  Returns (s, clamped_flag).
+    """
+    r = _f64(ratios)
+    assert r.ndim == 2
+    s = np.empty_like(r)
+
+    def spread(block):
+        lo, hi = block.min(), block.max()
+        if hi == lo:
+            return np.full_like(block, p)
+        r_hat = (block - lo) / (hi - lo)
+        return p + 2.0 * lam * (r_hat.mean() - r_hat)
+
+    if scope == "global":
+        s[:, :] = spread(r)
+    elif scope == "category":
+        for m in range(r.shape[1]):
+            s[:, m] = spread(r[:, m])
+    else:
+        raise ValueError(scope)
+
+    clamped = False
+    if cols is not None:
+        upper = 1.0 - 1.0 / _f64(cols)
+        t = np.minimum(np.maximum(s, 0.0), upper)
+        clamped = bool(np.any(t != s))
+        s = t
+    return s, clamped
+
+
+def zeros_per_row(sparsity: float, cols: int) -> int:
+    """k = floor(s * cols) in float64."""
+    return int(np.floor(np.float64(sparsity) * np.float64(cols)))
+
+
+# --------------------------------------------------------------------------- unstructured
+
+def select_smallest_per_row(omega, k: int) -> np.ndarray:
+    """Boolean [rows, cols], True = pruned: in every output row the k smallest omega.
+
+    A full stable ascending sort of each row by omega; among equal omega the
+    lower column comes first, which makes the result unique.  Works on any
+    real dtype (float64 oracle scores, or the kernel's float32 score bits).
+    """
+    omega = np.asarray(omega)
+    rows, cols = omega.shape
+    assert 0 <= k <= cols
+    pruned = np.zeros((rows, cols), dtype=bool)
+    if k == 0:
+        return pruned
+    order = np.argsort(omega, axis=1, kind="stable")
+    np.put_along_axis(pruned, order[:, :k], True, axis=1)
+    return pruned
+
+
+def apply_mask(w, pruned) -> np.ndarray:
+    """Unstructured pruning: pruned parameters are set to zero, survivors untouched."""
+    out = np.array(w, copy=True)
+    out[np.asarray(pruned, dtype=bool)] = 0
+    return out
+
+
+def pack_keep_bits(pruned) -> np.ndarray:
+    """uint32 [rows, ceil(cols/32)]; bit b of word q is 1 iff column 32*q + b is kept."""
+    pruned = np.asarray(pruned, dtype=bool)
+    rows, cols = pruned.shape
+    words = (cols + 31) // 32
+    keep = np.zeros((rows, words * 32), dtype=np.uint64)
+    keep[:, :cols] = ~pruned
+    weights = (np.uint64(1) << np.arange(32, dtype=np.uint64))
+    return (keep.reshape(rows, words, 32) * weights).sum(axis=2).astype(np.uint32)
+
+
+# --------------------------------------------------------------------------- structured
+
+def group_magnitude(gate, up, down) -> np.ndarray:
+    """g[c] = ||gate[c, :]||^2 + ||up[c, :]||^2 + ||down[:, c]||^2 on the (masked) weights.
+
+    Channel c of the MLP intermediate dimension couples one row of gate, one
+    row of up and one column of down; they are scored and removed as a group.
+    """
+    gate, up, down = _f64(gate), _f64(up), _f64(down)
+    inter = gate.shape[0]
+    assert up.shape == gate.shape and down.shape == (gate.shape[1], inter)
+    return (gate * gate).sum(axis=1) + (up * up).sum(axis=1) + (down * down).sum(axis=0)
+
+
+def struct_rank(g, r: int) -> np.ndarray:
+    """Indices (ascending) of the channels kept after removing the r lowest-magnitude groups.
+
+    Stable ascending sort by g, lower channel index first among equals.
+    """
+    g = np.asarray(g)
+    n = g.shape[0]
+    assert 0 <= r < n
+    order = np.argsort(g, kind="stable")
+    return np.sort(order[r:]).astype(np.int32)
+
+
+def struct_compact(gate, up, down, kept_idx):
+    """Physically remove the dropped channels: gate[kept, :], up[kept, :], down[:, kept]."""
+    kept_idx = np.asarray(kept_idx)
+    return (np.asarray(gate)[kept_idx, :].copy(),
+            np.asarray(up)[kept_idx, :].copy(),
+            np.asarray(down)[:, kept_idx].copy())
+
+
+# --------------------------------------------------------------------------- whole path
+
+def rank_projection(x, w, alpha: float):
+    """Ranking Controller work for one projection: norms, omega, (C, O, R, mean)."""
+    norms = column_norms(x)
+    omega = weight_metric(w, norms)
+    return (norms, omega) + outlier_stats(omega, alpha)
+
+
+def prune_projection(w, omega, k: int):
+    """Pruning Controller, unstructured category, one projection."""
+    pruned = select_smallest_per_row(omega, k)
+    return apply_mask(w, pruned), pruned
