@@ -1,0 +1,174 @@
+/*
+ * mosaic_prune.h -- C ABI of the MI355X (gfx950) projection-pruning hot path.
+ *
+ * The calls follow the problem statement of "Mosaic: Composite Projection
+ * Pruning for Resource-efficient LLMs" (arXiv 2504.06323): the Parameter
+ * Ranking Controller (Algorithm 1, Eq. 5, Eq. 6) and the unstructured /
+ * structured / composite categories of the Parameter Pruning Controller
+ * (Section 3.3, Section 4.1.3).
+ *
+ * Conventions shared by every entry point
+ *   - Plain C, no exceptions.  Every call returns a prune_status (0 = ok,
+ *     negative = error and nothing was launched).
+ *   - Matrices are row-major.  A projection weight W is [rows = output
+ *     features, cols = input features] with leading dimension ld_w (elements);
+ *     its input activation X is [n_tokens, n_channels = cols] with ld_x.
+ *   - Unless marked "host", a pointer is a DEVICE pointer owned by the caller.
+ *     The library allocates nothing, frees nothing and keeps no state between
+ *     calls.  Scratch memory is passed in as (ws, ws_bytes); its minimum size
+ *     comes from prune_workspace_bytes() and it needs no initialisation.
+ *     ws must be 16-byte aligned.
+ *   - stream is a hipStream_t passed as void* (NULL = the default stream).
+ *     All device work is enqueued asynchronously on it; nothing synchronises.
+ *   - dtype is a prune_dtype: PRUNE_F32 (float) or PRUNE_BF16 (bfloat16 stored
+ *     as 16-bit words).  bf16 is widened exactly to float before any arithmetic.
+ *   - Results are deterministic: running a call twice on the same inputs gives
+ *     bit-identical outputs (fixed reduction orders; only integer atomics).
+ *   - Any shape is accepted.  Rows whose base address and width allow 128-bit
+ *     accesses (pointer 16-byte aligned, cols and ld multiples of 8) take the
+ *     vectorised kernels; everything else takes slower scalar kernels with the
+ *     same results.
+ */
+#ifndef MOSAIC_PRUNE_H
+#define MOSAIC_PRUNE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PRUNE_OK = 0,
+    PRUNE_ERR_NULL = -1,      /* a required pointer is NULL */
+    PRUNE_ERR_SHAPE = -2,     /* non-positive extent, or ld smaller than the row width */
+    PRUNE_ERR_DTYPE = -3,     /* dtype is not a prune_dtype */
+    PRUNE_ERR_ALIGNMENT = -4, /* ws not 16-byte aligned, or a pointer not aligned to its element size */
+    PRUNE_ERR_WORKSPACE = -5, /* ws_bytes smaller than prune_workspace_bytes() */
+    PRUNE_ERR_RANGE = -6,     /* scalar argument outside its documented range */
+    PRUNE_ERR_DEVICE = -7     /* the HIP runtime refused a launch */
+} prune_status;
+
+typedef enum { PRUNE_F32 = 0, PRUNE_BF16 = 1 } prune_dtype;
+
+typedef enum {
+    PRUNE_OP_STATS = 0,   /* rows = n_tokens, cols = n_channels */
+    PRUNE_OP_SCORE = 1,   /* rows, cols of W */
+    PRUNE_OP_OUTLIER = 2, /* needs no workspace (returns 0) */
+    PRUNE_OP_SELECT = 3,  /* rows, cols of W */
+    PRUNE_OP_STRUCT = 4   /* rows = inter, cols = hidden */
+} prune_op;
+
+typedef enum { PRUNE_SCOPE_GLOBAL = 0, PRUNE_SCOPE_CATEGORY = 1 } prune_scope;
+
+/* host, pure.  Library version as major * 10000 + minor * 100 + patch. */
+int prune_version(void);
+
+/* host, pure.  Static string naming a prune_status. */
+const char *prune_status_string(int status);
+
+/* host, pure.  Minimum ws_bytes for one call of `op` on a problem of the given
+ * extents (see prune_op for what rows/cols mean).  Returns 0 for bad arguments. */
+size_t prune_workspace_bytes(int op, int64_t rows, int64_t cols);
+
+/*
+ * Activation statistics (Algorithm 1, the loop that gathers A over the
+ * calibration samples; the l2-norm term of Eq. 5).
+ *   sumsq[j] += sum over t < n_tokens of x[t * ld_x + j]^2      for j < n_channels
+ * x       [n_tokens, n_channels] of dtype, read once.
+ * sumsq   [n_channels] float, in/out: the caller zeroes it before the first
+ *         chunk of a tensor and may call repeatedly with further token chunks.
+ * Squares and sums are formed in float (fixed order), the cross-block
+ * reduction in double.  n_tokens == 0 is a valid no-op.
+ */
+int prune_stats_accumulate(const void *x, int dtype, int64_t n_tokens, int64_t n_channels, int64_t ld_x,
+                           float *sumsq, void *ws, size_t ws_bytes, void *stream);
+
+/* norms[j] = sqrt(sumsq[j]) (correctly rounded float sqrt).  In place allowed. */
+int prune_stats_finalize(const float *sumsq, int64_t n_channels, float *norms, void *stream);
+
+/*
+ * Weight metric (Eq. 5; Algorithm 1, "Weight metric" step).
+ *   omega[i, j] = float(|w[i, j]|) * norms[j]        one IEEE float multiply
+ *   *score_sum  = sum over i, j of omega[i, j]       accumulated in double, fixed order
+ * w          [rows, cols] of dtype, read once.
+ * norms      [cols] float, as produced by prune_stats_finalize.
+ * scores     optional [rows, cols] float, contiguous (ld = cols): receives omega.
+ *            NULL in the hot mode (nothing but the sum is written).
+ * score_sum  one double on the device.
+ */
+int prune_score(const void *w, int dtype, int64_t rows, int64_t cols, int64_t ld_w, const float *norms,
+                float *scores, double *score_sum, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Projection outliers (Eq. 6; Algorithm 1, the C / O steps).
+ *   tau    = float(alpha * *score_sum / (rows * cols))   formed in double, rounded once
+ *   *count = #{ (i, j) : omega[i, j] > tau }              strict, float compare
+ * The projection rank is R = 100 * count / (rows * cols), formed by the caller.
+ * omega is recomputed from (w, norms) exactly as in prune_score, or read from
+ * `scores` when that is non-NULL (then w and norms may be NULL).
+ * alpha >= 0.  count: one unsigned 64-bit on the device.  tau: optional float
+ * on the device receiving the threshold that was used.
+ */
+int prune_outlier_ratio(const void *w, int dtype, int64_t rows, int64_t cols, int64_t ld_w,
+                        const float *norms, const float *scores, float alpha, const double *score_sum,
+                        unsigned long long *count, float *tau, void *stream);
+
+/*
+ * host only, touches no device (Algorithm 1's normalize(R_LLM) and the
+ * Projection Planner of Section 3.3; Eq. 1, Eq. 2).
+ * Turns the n_layers x n_proj table of outlier counts into sparsity targets:
+ *   R = 100 * counts / numels;  within a scope (all entries, or one projection
+ *   category across layers) r_hat = (R - min) / (max - min) and
+ *   s = p + 2 * lambda * (mean(r_hat) - r_hat);  s = p when max == min.
+ * The unweighted mean of s is p, more outliers give a smaller s.  If cols is
+ * non-NULL each s is clamped to [0, 1 - 1 / cols] and *clamped_out (optional)
+ * is set to 1 when any clamp changed a value; zeros_per_row_out (optional,
+ * needs cols) receives k = floor(s * cols), the per-row count handed to
+ * prune_select_mask.  All arrays are host arrays of n_layers * n_proj entries,
+ * row-major.  p in [0, 1), lambda >= 0.
+ */
+int prune_plan_sparsity(const unsigned long long *counts, const unsigned long long *numels, const int64_t *cols,
+                        int n_layers, int n_proj, double p, double lambda, int scope, double *sparsity_out,
+                        uint32_t *zeros_per_row_out, int *clamped_out);
+
+/*
+ * Unstructured projection pruning (Section 4.1.3, category 1: pruned
+ * parameters are set to zero).  In every row the k entries with the smallest
+ * omega are zeroed; among equal omega the lower column goes first, so the
+ * result is unique.  omega is recomputed from (w, norms) as in prune_score, or
+ * read from `scores` (contiguous [rows, cols], non-negative) when non-NULL.
+ *   w_out[i, j] = pruned(i, j) ? 0 : w[i, j]          same dtype and ld as w
+ * w_out may equal w (in place) or be a separate buffer; partial overlap is
+ * not allowed.  mask_bits is optional: uint32 [rows, ceil(cols / 32)], bit b of
+ * word q of a row is 1 iff column 32 * q + b is kept; bits past cols are 0.
+ * 0 <= k <= cols; k == 0 copies w to w_out.
+ */
+int prune_select_mask(const void *w, void *w_out, int dtype, int64_t rows, int64_t cols, int64_t ld_w,
+                      const float *norms, const float *scores, uint32_t k, uint32_t *mask_bits, void *ws,
+                      size_t ws_bytes, void *stream);
+
+/*
+ * Structured removal of MLP intermediate channels (Section 4.1.3, categories
+ * 2 and 3; Fig. 4: the nodes between projections are pruned as a group).
+ * Run on the already masked weights for the composite category.
+ *   group_mag[c] = sum_j gate[c, j]^2 + sum_j up[c, j]^2 + sum_i down[i, c]^2
+ * the r channels with the smallest group_mag (lower c first among equals) are
+ * removed; kept_idx receives the remaining inter - r channel indices in
+ * ascending order, and, when the three *_out pointers are non-NULL,
+ *   gate_out = gate[kept, :]  [inter - r, hidden]
+ *   up_out   = up[kept, :]    [inter - r, hidden]
+ *   down_out = down[:, kept]  [hidden, inter - r]
+ * gate, up are [inter, hidden], down is [hidden, inter]; all inputs and
+ * outputs are contiguous.  Pass all three outputs or none (rank only).
+ * 0 <= r < inter.  Outputs must not overlap inputs.
+ */
+int prune_struct_compact(const void *gate, const void *up, const void *down, int dtype, int64_t inter,
+                         int64_t hidden, uint32_t r, float *group_mag, int32_t *kept_idx, void *gate_out,
+                         void *up_out, void *down_out, void *ws, size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOSAIC_PRUNE_H */

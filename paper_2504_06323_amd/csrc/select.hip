@@ -1,0 +1,228 @@
+// Unstructured projection pruning (Section 4.1.3, category 1): in every output
+// row the k entries with the smallest weight metric (Eq. 5) are set to zero,
+// lower column first among equal metrics.
+//
+// One block per row.  The row is loaded once with 128-bit loads and stays in
+// registers in its storage format; the metric keys live in registers too, the
+// radix search runs over them with its histogram in LDS, and the row is written
+// back once (plus one keep-bit per element).  HBM traffic is one read and one
+// write of the projection.
+#include "select.hpp"
+
+namespace mp {
+
+namespace {
+
+template <typename T, int BLOCK, int NCHUNK, bool FROM_SCORES>
+__global__ __launch_bounds__(BLOCK) void select_rows_vec(const T *w, T *w_out, int64_t cols, int64_t ld,
+                                                         const float *__restrict__ norms,
+                                                         const float *__restrict__ scores, uint32_t k, int idx_bits,
+                                                         uint8_t *__restrict__ mask_bytes, int64_t mask_row_bytes) {
+    __shared__ SelectSmem<BLOCK> sm;
+    const int64_t row = blockIdx.x;
+    const int tid = threadIdx.x;
+
+    Packet<T, 8> pk[NCHUNK];
+    uint32_t key[NCHUNK][8];
+#pragma unroll
+    for (int c = 0; c < NCHUNK; ++c) {
+        const int64_t col0 = (static_cast<int64_t>(c) * BLOCK + tid) * 8;
+        if (col0 < cols) {
+            pk[c].load(w + row * ld + col0);
+            float om[8];
+            if (FROM_SCORES) {
+                load_floats(scores + row * cols + col0, om);
+            } else {
+                float v[8], nrm[8];
+                pk[c].to_float(v);
+                load_floats(norms + col0, nrm);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) om[e] = metric(v[e], nrm[e]);
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) key[c][e] = key_of(om[e]);
+        }
+    }
+
+    uint64_t bound = ~uint64_t(0);  // k == cols: everything goes
+    if (k < cols) {
+        bound = block_select_bound<BLOCK>(
+            [&](auto f) {
+#pragma unroll
+                for (int c = 0; c < NCHUNK; ++c) {
+                    const int64_t col0 = (static_cast<int64_t>(c) * BLOCK + tid) * 8;
+                    if (col0 < cols) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) f(key[c][e], static_cast<uint32_t>(col0 + e));
+                    }
+                }
+            },
+            k, idx_bits, sm);
+    }
+
+#pragma unroll
+    for (int c = 0; c < NCHUNK; ++c) {
+        const int64_t col0 = (static_cast<int64_t>(c) * BLOCK + tid) * 8;
+        if (col0 < cols) {
+            uint32_t keep = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                keep |= (composite(key[c][e], static_cast<uint32_t>(col0 + e), idx_bits) > bound ? 1u : 0u) << e;
+            pk[c].apply_keep(keep);
+            pk[c].store(w_out + row * ld + col0);
+            if (mask_bytes) {
+                uint8_t *mrow = mask_bytes + row * mask_row_bytes;
+                mrow[col0 >> 3] = static_cast<uint8_t>(keep);
+                if (col0 + 8 == cols)  // owner of the last packet clears the padding of the last word
+                    for (int64_t b = (cols >> 3); b < mask_row_bytes; ++b) mrow[b] = 0;
+            }
+        }
+    }
+}
+
+// any width / pitch / alignment; keys are recomputed from memory on every digit pass
+template <typename T, int BLOCK, bool FROM_SCORES>
+__global__ __launch_bounds__(BLOCK) void select_rows_generic(const T *w, T *w_out, int64_t cols, int64_t ld,
+                                                             const float *__restrict__ norms,
+                                                             const float *__restrict__ scores, uint32_t k,
+                                                             int idx_bits, uint32_t *__restrict__ mask_words,
+                                                             int64_t words_per_row) {
+    __shared__ SelectSmem<BLOCK> sm;
+    const int64_t row = blockIdx.x;
+    const int tid = threadIdx.x;
+    const T *wr = w + row * ld;
+    auto key_at = [&](int64_t j) -> uint32_t {
+        const float om = FROM_SCORES ? scores[row * cols + j] : metric(widen(wr[j]), norms[j]);
+        return key_of(om);
+    };
+    uint64_t bound = ~uint64_t(0);
+    if (k < cols) {
+        bound = block_select_bound<BLOCK>(
+            [&](auto f) {
+                for (int64_t j = tid; j < cols; j += BLOCK) f(key_at(j), static_cast<uint32_t>(j));
+            },
+            k, idx_bits, sm);
+    }
+    T *orow = w_out + row * ld;
+    for (int64_t q = tid; q < words_per_row; q += BLOCK) {
+        uint32_t word = 0;
+        for (int b = 0; b < 32; ++b) {
+            const int64_t j = q * 32 + b;
+            if (j < cols) {
+                const bool keep = composite(key_at(j), static_cast<uint32_t>(j), idx_bits) > bound;
+                const T v = wr[j];
+                orow[j] = keep ? v : T(0);
+                word |= (keep ? 1u : 0u) << b;
+            }
+        }
+        if (mask_words) mask_words[row * words_per_row + q] = word;
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void copy_rows(const T *__restrict__ src, T *__restrict__ dst, int64_t rows,
+                                                 int64_t cols, int64_t ld) {
+    const int64_t n = rows * cols;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < n;
+         i += static_cast<int64_t>(gridDim.x) * 256) {
+        const int64_t r = i / cols, c = i - r * cols;
+        dst[r * ld + c] = src[r * ld + c];
+    }
+}
+
+// keep-bits all ones over the live columns, zero in the padding of the last word
+__global__ __launch_bounds__(256) void fill_keep_all(uint32_t *__restrict__ mask_words, int64_t rows, int64_t cols,
+                                                     int64_t words_per_row) {
+    const int64_t n = rows * words_per_row;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < n;
+         i += static_cast<int64_t>(gridDim.x) * 256) {
+        const int64_t q = i % words_per_row;
+        const int64_t live = cols - q * 32;
+        mask_words[i] = live >= 32 ? 0xffffffffu : ((1u << live) - 1u);
+    }
+}
+
+template <typename T, bool FROM_SCORES>
+int launch_select(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld, const float *norms,
+                  const float *scores, uint32_t k, uint32_t *mask_bits, hipStream_t stream) {
+    const int idx_bits = index_bits_for(cols);
+    const int64_t words = ceil_div(cols, 32);
+    const dim3 grid(static_cast<unsigned>(rows));
+    bool vec = packet_ok(w, cols, ld) && aligned_to(w_out, 16) && cols <= 16384;
+    if (FROM_SCORES ? !aligned_to(scores, 16) : !aligned_to(norms, 16)) vec = false;
+    if (!vec) {
+        hipLaunchKernelGGL((select_rows_generic<T, 256, FROM_SCORES>), grid, dim3(256), 0, stream, w, w_out, cols,
+                           ld, norms, scores, k, idx_bits, mask_bits, words);
+        return launch_status();
+    }
+    uint8_t *mb = reinterpret_cast<uint8_t *>(mask_bits);
+    const int64_t mrb = words * 4;
+#define MP_SELECT_CASE(BLOCK, NCHUNK)                                                                              \
+    hipLaunchKernelGGL((select_rows_vec<T, BLOCK, NCHUNK, FROM_SCORES>), grid, dim3(BLOCK), 0, stream, w, w_out,   \
+                       cols, ld, norms, scores, k, idx_bits, mb, mrb)
+    if (cols <= 512) MP_SELECT_CASE(64, 1);
+    else if (cols <= 1024) MP_SELECT_CASE(64, 2);
+    else if (cols <= 2048) MP_SELECT_CASE(256, 1);
+    else if (cols <= 4096) MP_SELECT_CASE(256, 2);
+    else if (cols <= 6144) MP_SELECT_CASE(256, 3);
+    else if (cols <= 8192) MP_SELECT_CASE(256, 4);
+    else if (cols <= 10240) MP_SELECT_CASE(256, 5);
+    else if (cols <= 12288) MP_SELECT_CASE(256, 6);
+    else if (cols <= 14336) MP_SELECT_CASE(256, 7);
+    else MP_SELECT_CASE(256, 8);
+#undef MP_SELECT_CASE
+    return launch_status();
+}
+
+template <typename T>
+int select_dispatch(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld, const float *norms,
+                    const float *scores, uint32_t k, uint32_t *mask_bits, hipStream_t stream) {
+    if (k == 0) {  // nothing to prune: copy through, every bit kept
+        if (w_out != w) {
+            hipLaunchKernelGGL(copy_rows<T>, dim3(2048), dim3(256), 0, stream, w, w_out, rows, cols, ld);
+            if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
+        }
+        if (mask_bits) {
+            hipLaunchKernelGGL(fill_keep_all, dim3(1024), dim3(256), 0, stream, mask_bits, rows, cols,
+                               ceil_div(cols, 32));
+            return launch_status();
+        }
+        return PRUNE_OK;
+    }
+    return scores ? launch_select<T, true>(w, w_out, rows, cols, ld, norms, scores, k, mask_bits, stream)
+                  : launch_select<T, false>(w, w_out, rows, cols, ld, norms, scores, k, mask_bits, stream);
+}
+
+}  // namespace
+
+size_t select_workspace_bytes(int64_t, int64_t) { return 0; }  // the row lives in registers and LDS
+
+}  // namespace mp
+
+extern "C" int prune_select_mask(const void *w, void *w_out, int dtype, int64_t rows, int64_t cols, int64_t ld_w,
+                                 const float *norms, const float *scores, uint32_t k, uint32_t *mask_bits, void *ws,
+                                 size_t ws_bytes, void *stream_) {
+    using namespace mp;
+    (void)ws;
+    (void)ws_bytes;
+    if (!valid_dtype(dtype)) return PRUNE_ERR_DTYPE;
+    if (rows <= 0 || cols <= 0 || ld_w < cols || cols > (int64_t(1) << 32) || rows > 0x7fffffff)
+        return PRUNE_ERR_SHAPE;
+    if (!w || !w_out || (!scores && !norms)) return PRUNE_ERR_NULL;
+    if (static_cast<int64_t>(k) > cols) return PRUNE_ERR_RANGE;
+    const size_t es = elem_size(dtype);
+    if (!aligned_to(w, es) || !aligned_to(w_out, es) || (norms && !aligned_to(norms, 4)) ||
+        (scores && !aligned_to(scores, 4)) || (mask_bits && !aligned_to(mask_bits, 4)))
+        return PRUNE_ERR_ALIGNMENT;
+    if (w_out != w) {  // separate output must not partially overlap the input
+        const uintptr_t a = reinterpret_cast<uintptr_t>(w), b = reinterpret_cast<uintptr_t>(w_out);
+        const uintptr_t span = static_cast<uintptr_t>((rows - 1) * ld_w + cols) * es;
+        if ((a < b && a + span > b) || (b < a && b + span > a)) return PRUNE_ERR_RANGE;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (dtype == PRUNE_BF16)
+        return select_dispatch(static_cast<const bf16_t *>(w), static_cast<bf16_t *>(w_out), rows, cols, ld_w, norms,
+                               scores, k, mask_bits, stream);
+    return select_dispatch(static_cast<const float *>(w), static_cast<float *>(w_out), rows, cols, ld_w, norms, scores,
+                           k, mask_bits, stream);
+}

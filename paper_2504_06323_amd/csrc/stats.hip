@@ -1,0 +1,195 @@
+// Activation statistics: per-input-channel sum of squares over the calibration
+// tokens (the l2-norm term of Eq. 5, gathered over all samples as in
+// Algorithm 1), and its square root.
+//
+// HBM-bound streaming reduction.  Each thread owns 8 adjacent channels (one
+// 128-bit load per row for bf16) and walks down a stripe of rows keeping 8
+// private float accumulators, so nothing crosses lanes while streaming.  A
+// block covers 2048 adjacent channels (4 KB of every row it touches); the grid
+// is (channel tiles) x (row stripes) with thousands of blocks.  Each block
+// writes one row of partials; a second small kernel adds the stripes in a fixed
+// order in double and folds them into the caller's running sums.
+#include "common.hpp"
+
+namespace mp {
+
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kTargetBlocks = 4096;  // blocks aimed for on the packet path (16 per CU)
+constexpr int kMinRowsPerBlock = 32;
+constexpr int kMaxStripes = 4096;
+
+template <typename T, int UNROLL>
+__global__ __launch_bounds__(kBlock) void colsumsq_partial_vec(const T *__restrict__ x, int64_t n_rows,
+                                                               int64_t n_cols, int64_t ld, int64_t rows_per_block,
+                                                               float *__restrict__ partials) {
+    const int64_t c0 = (static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x) * 8;
+    if (c0 >= n_cols) return;  // n_cols is a multiple of 8 on this path; no barriers below
+    const int64_t t0 = static_cast<int64_t>(blockIdx.y) * rows_per_block;
+    int64_t t1 = t0 + rows_per_block;
+    if (t1 > n_rows) t1 = n_rows;
+
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+
+    const T *p = x + t0 * ld + c0;
+    int64_t t = t0;
+    for (; t + UNROLL <= t1; t += UNROLL) {
+        Packet<T, 8> pk[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) pk[u].template load<true>(p + u * ld);
+        float s[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) s[e] = 0.f;
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            float v[8];
+            pk[u].to_float(v);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s[e] = fmaf(v[e], v[e], s[e]);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += s[e];
+        p += UNROLL * ld;
+    }
+    for (; t < t1; ++t) {
+        Packet<T, 8> pk;
+        pk.template load<true>(p);
+        float v[8];
+        pk.to_float(v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = fmaf(v[e], v[e], acc[e]);
+        p += ld;
+    }
+    store_floats(partials + static_cast<int64_t>(blockIdx.y) * n_cols + c0, acc);
+}
+
+// any width / pitch / alignment: one channel per thread, lanes on adjacent channels
+template <typename T>
+__global__ __launch_bounds__(kBlock) void colsumsq_partial_scalar(const T *__restrict__ x, int64_t n_rows,
+                                                                  int64_t n_cols, int64_t ld,
+                                                                  int64_t rows_per_block,
+                                                                  float *__restrict__ partials) {
+    const int64_t c = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (c >= n_cols) return;
+    const int64_t t0 = static_cast<int64_t>(blockIdx.y) * rows_per_block;
+    int64_t t1 = t0 + rows_per_block;
+    if (t1 > n_rows) t1 = n_rows;
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    const T *p = x + t0 * ld + c;
+    int64_t t = t0;
+    for (; t + 4 <= t1; t += 4) {
+        const float v0 = widen(p[0]), v1 = widen(p[ld]), v2 = widen(p[2 * ld]), v3 = widen(p[3 * ld]);
+        a0 = fmaf(v0, v0, a0);
+        a1 = fmaf(v1, v1, a1);
+        a2 = fmaf(v2, v2, a2);
+        a3 = fmaf(v3, v3, a3);
+        p += 4 * ld;
+    }
+    for (; t < t1; ++t) {
+        const float v = widen(p[0]);
+        a0 = fmaf(v, v, a0);
+        p += ld;
+    }
+    partials[static_cast<int64_t>(blockIdx.y) * n_cols + c] = (a0 + a1) + (a2 + a3);
+}
+
+// sumsq[c] += sum over stripes of partials[s, c]; 64 channels x 4 stripe groups per block
+__global__ __launch_bounds__(kBlock) void colsumsq_reduce(const float *__restrict__ partials, int n_stripes,
+                                                          int64_t n_cols, float *__restrict__ sumsq) {
+    __shared__ double sm[4][kWave];
+    const int lane = threadIdx.x & (kWave - 1), grp = threadIdx.x / kWave;
+    const int64_t c = static_cast<int64_t>(blockIdx.x) * kWave + lane;
+    double a = 0.0;
+    if (c < n_cols)
+        for (int s = grp; s < n_stripes; s += 4) a += static_cast<double>(partials[static_cast<int64_t>(s) * n_cols + c]);
+    sm[grp][lane] = a;
+    __syncthreads();
+    if (grp == 0 && c < n_cols) {
+        const double tot = (sm[0][lane] + sm[1][lane]) + (sm[2][lane] + sm[3][lane]);
+        sumsq[c] = static_cast<float>(static_cast<double>(sumsq[c]) + tot);
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void sqrt_kernel(const float *__restrict__ sumsq, int64_t n,
+                                                      float *__restrict__ norms) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (i < n) norms[i] = sqrtf(sumsq[i]);  // correctly rounded (hipcc default)
+}
+
+template <typename T>
+int launch_colsum_t(const T *x, int64_t n_rows, int64_t n_cols, int64_t ld, float *sumsq, float *partials,
+                    hipStream_t stream) {
+    const ColsumPlan pl = plan_colsum(n_rows, n_cols);
+    if (packet_ok(x, n_cols, ld)) {
+        dim3 grid(pl.tiles_vec, pl.stripes);
+        hipLaunchKernelGGL((colsumsq_partial_vec<T, 8>), grid, dim3(kBlock), 0, stream, x, n_rows, n_cols, ld,
+                           pl.rows_per_block, partials);
+    } else {
+        dim3 grid(pl.tiles_scalar, pl.stripes);
+        hipLaunchKernelGGL((colsumsq_partial_scalar<T>), grid, dim3(kBlock), 0, stream, x, n_rows, n_cols, ld,
+                           pl.rows_per_block, partials);
+    }
+    if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
+    hipLaunchKernelGGL(colsumsq_reduce, dim3(static_cast<unsigned>(ceil_div(n_cols, kWave))), dim3(kBlock), 0,
+                       stream, partials, pl.stripes, n_cols, sumsq);
+    return launch_status();
+}
+
+}  // namespace
+
+ColsumPlan plan_colsum(int64_t n_rows, int64_t n_cols) {
+    ColsumPlan pl;
+    pl.tiles_vec = static_cast<int>(ceil_div(n_cols, kBlock * 8));
+    pl.tiles_scalar = static_cast<int>(ceil_div(n_cols, kBlock));
+    int64_t max_stripes = kTargetBlocks / pl.tiles_vec;
+    if (max_stripes < 1) max_stripes = 1;
+    if (max_stripes > kMaxStripes) max_stripes = kMaxStripes;
+    int64_t rpb = ceil_div(n_rows, max_stripes);
+    if (rpb < kMinRowsPerBlock) rpb = kMinRowsPerBlock;
+    rpb = ceil_div(rpb, 8) * 8;
+    pl.rows_per_block = rpb;
+    pl.stripes = static_cast<int>(ceil_div(n_rows, rpb));
+    if (pl.stripes < 1) pl.stripes = 1;
+    return pl;
+}
+
+size_t colsum_workspace_bytes(int64_t n_rows, int64_t n_cols) {
+    const ColsumPlan pl = plan_colsum(n_rows, n_cols);
+    return static_cast<size_t>(pl.stripes) * static_cast<size_t>(n_cols) * sizeof(float);
+}
+
+int launch_colsum(const void *x, int dtype, int64_t n_rows, int64_t n_cols, int64_t ld, float *sumsq, void *ws,
+                  hipStream_t stream) {
+    float *partials = static_cast<float *>(ws);
+    if (dtype == PRUNE_BF16)
+        return launch_colsum_t(static_cast<const bf16_t *>(x), n_rows, n_cols, ld, sumsq, partials, stream);
+    return launch_colsum_t(static_cast<const float *>(x), n_rows, n_cols, ld, sumsq, partials, stream);
+}
+
+}  // namespace mp
+
+extern "C" int prune_stats_accumulate(const void *x, int dtype, int64_t n_tokens, int64_t n_channels, int64_t ld_x,
+                                      float *sumsq, void *ws, size_t ws_bytes, void *stream) {
+    using namespace mp;
+    if (!valid_dtype(dtype)) return PRUNE_ERR_DTYPE;
+    if (n_tokens < 0 || n_channels <= 0 || ld_x < n_channels) return PRUNE_ERR_SHAPE;
+    if (!sumsq) return PRUNE_ERR_NULL;
+    if (n_tokens == 0) return PRUNE_OK;
+    if (!x || !ws) return PRUNE_ERR_NULL;
+    if (!aligned_to(x, elem_size(dtype)) || !aligned_to(sumsq, 4) || !aligned_to(ws, 16)) return PRUNE_ERR_ALIGNMENT;
+    if (ws_bytes < colsum_workspace_bytes(n_tokens, n_channels)) return PRUNE_ERR_WORKSPACE;
+    return launch_colsum(x, dtype, n_tokens, n_channels, ld_x, sumsq, ws, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int prune_stats_finalize(const float *sumsq, int64_t n_channels, float *norms, void *stream) {
+    using namespace mp;
+    if (n_channels <= 0) return PRUNE_ERR_SHAPE;
+    if (!sumsq || !norms) return PRUNE_ERR_NULL;
+    if (!aligned_to(sumsq, 4) || !aligned_to(norms, 4)) return PRUNE_ERR_ALIGNMENT;
+    hipLaunchKernelGGL(sqrt_kernel, dim3(static_cast<unsigned>(ceil_div(n_channels, kBlock))), dim3(kBlock), 0,
+                       static_cast<hipStream_t>(stream), sumsq, n_channels, norms);
+    return launch_status();
+}

@@ -1,0 +1,123 @@
+"""Call sequencing for one LLaMA-style layer: which entry point runs on which tensor, in what order.
+
+Nothing is computed here.  The two phases mirror the paper's two controllers:
+
+  rank_layer   Parameter Ranking Controller (Algorithm 1): activation norms per
+               distinct projection input, then metric sum and outlier count per
+               projection.  Independent of the pruning target p, so it runs once.
+  plan         Projection Planner (Section 3.3): counts -> zeros per row (host).
+  prune_layer  Parameter Pruning Controller, unstructured category, then (for
+               the composite category) structured removal of MLP channels on
+               the masked weights.
+
+Device buffers are allocated once per LayerState and reused across steps.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import torch
+
+from . import prune
+
+
+@dataclass
+class LayerState:
+    """Device buffers of one layer.  proj_inputs maps projection name -> activation name."""
+
+    weights: Dict[str, torch.Tensor]
+    proj_inputs: Dict[str, str]
+    device: torch.device
+    sumsq: Dict[str, torch.Tensor] = field(default_factory=dict)
+    norms: Dict[str, torch.Tensor] = field(default_factory=dict)
+    score_sum: torch.Tensor = None      # [n_proj] float64
+    count: torch.Tensor = None          # [n_proj] int64
+    tau: torch.Tensor = None            # [n_proj] float32
+    pruned: Dict[str, torch.Tensor] = field(default_factory=dict)   # masked copies (phase 2 output)
+    mask_bits: Dict[str, torch.Tensor] = field(default_factory=dict)
+    ws: torch.Tensor = None
+    names: Tuple[str, ...] = ()
+
+    @classmethod
+    def create(cls, weights: Dict[str, torch.Tensor], proj_inputs: Dict[str, str],
+               act_channels: Dict[str, int], act_tokens: int, want_mask_bits: bool = True) -> "LayerState":
+        dev = next(iter(weights.values())).device
+        st = cls(weights=weights, proj_inputs=proj_inputs, device=dev)
+        st.names = tuple(weights)
+        n = len(st.names)
+        for a, ch in act_channels.items():
+            st.sumsq[a] = torch.zeros(ch, dtype=torch.float32, device=dev)
+            st.norms[a] = torch.empty(ch, dtype=torch.float32, device=dev)
+        st.score_sum = torch.zeros(n, dtype=torch.float64, device=dev)
+        st.count = torch.zeros(n, dtype=torch.int64, device=dev)
+        st.tau = torch.zeros(n, dtype=torch.float32, device=dev)
+        need = 256
+        for a, ch in act_channels.items():
+            need = max(need, prune.workspace_bytes(prune.OP_STATS, max(act_tokens, 1), ch))
+        for name, w in weights.items():
+            need = max(need, prune.workspace_bytes(prune.OP_SCORE, w.shape[0], w.shape[1]))
+            st.pruned[name] = torch.empty_like(w)
+            if want_mask_bits:
+                st.mask_bits[name] = torch.empty((w.shape[0], (w.shape[1] + 31) // 32), dtype=torch.int32, device=dev)
+        if "gate" in weights:
+            inter, hidden = weights["gate"].shape
+            need = max(need, prune.workspace_bytes(prune.OP_STRUCT, inter, hidden))
+        st.ws = torch.empty(need, dtype=torch.uint8, device=dev)
+        return st
+
+
+def rank_layer(st: LayerState, acts: Dict[str, torch.Tensor], alpha: float,
+               scores: Optional[Dict[str, torch.Tensor]] = None) -> None:
+    """Phase 1: norms for every distinct input, then metric sum + outlier count for every projection."""
+    for a, x in acts.items():
+        st.sumsq[a].zero_()
+        prune.stats_accumulate(x, st.sumsq[a], ws=st.ws)
+        prune.stats_finalize(st.sumsq[a], st.norms[a])
+    for i, name in enumerate(st.names):
+        w = st.weights[name]
+        nrm = st.norms[st.proj_inputs[name]]
+        sc = None if scores is None else scores.get(name)
+        prune.score(w, nrm, st.score_sum[i:i + 1], scores=sc, ws=st.ws)
+        prune.outlier_ratio(w, nrm, alpha, st.score_sum[i:i + 1], st.count[i:i + 1], tau=st.tau[i:i + 1], scores=sc)
+
+
+def plan(counts: Sequence[int], numels: Sequence[int], cols: Sequence[int], n_layers: int, n_proj: int, p: float,
+         lam: float, scope: int = prune.SCOPE_GLOBAL):
+    """Host planner over all layers' counts: returns (sparsities, zeros per row, clamped)."""
+    return prune.plan_sparsity(counts, numels, n_layers, n_proj, p, lam, scope, cols=cols)
+
+
+def prune_layer(st: LayerState, ks: Sequence[int], in_place: bool = False) -> None:
+    """Phase 2, unstructured: zero the k lowest-metric entries per row of every projection."""
+    for i, name in enumerate(st.names):
+        w = st.weights[name]
+        prune.select_mask(w, st.norms[st.proj_inputs[name]], int(ks[i]),
+                          w_out=None if in_place else st.pruned[name], mask_bits=st.mask_bits.get(name), ws=st.ws)
+
+
+@dataclass
+class StructResult:
+    group_mag: torch.Tensor
+    kept_idx: torch.Tensor
+    gate: Optional[torch.Tensor]
+    up: Optional[torch.Tensor]
+    down: Optional[torch.Tensor]
+
+
+def alloc_struct(st: LayerState, r: int, compact: bool = True) -> StructResult:
+    gate = st.weights["gate"]
+    inter, hidden = gate.shape
+    kept = inter - r
+    mk = lambda *shape: torch.empty(shape, dtype=gate.dtype, device=st.device)
+    return StructResult(torch.empty(inter, dtype=torch.float32, device=st.device),
+                        torch.empty(kept, dtype=torch.int32, device=st.device),
+                        mk(kept, hidden) if compact else None, mk(kept, hidden) if compact else None,
+                        mk(hidden, kept) if compact else None)
+
+
+def struct_layer(st: LayerState, r: int, out: StructResult, masked: bool = True) -> None:
+    """Phase 2, structured: rank MLP channels on the (masked) weights, drop r, compact."""
+    src = st.pruned if masked else st.weights
+    prune.struct_compact(src["gate"], src["up"], src["down"], r, out.group_mag, out.kept_idx,
+                         out.gate, out.up, out.down, ws=st.ws)

@@ -1,0 +1,261 @@
+"""Thin binding over the C-ABI library (include/mosaic_prune.h).
+
+Argument marshalling only: every function here has the name of the C entry
+point it calls, turns torch tensors into (pointer, extent, pitch) arguments and
+raises on a non-zero status.  Torch is used for device memory and for the
+current stream, nothing else; no step of the method is computed in Python.
+
+The shared library is built in-tree by `paper_2504_06323_amd/build.py`.  If it
+is missing, the first call raises: there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "libmosaic_prune.so")
+_lib = None
+
+F32, BF16 = 0, 1
+OP_STATS, OP_SCORE, OP_OUTLIER, OP_SELECT, OP_STRUCT = range(5)
+SCOPE_GLOBAL, SCOPE_CATEGORY = 0, 1
+
+_c = ctypes
+_vp, _i64, _int, _sz, _u32, _f32, _f64 = (_c.c_void_p, _c.c_int64, _c.c_int, _c.c_size_t, _c.c_uint32,
+                                          _c.c_float, _c.c_double)
+
+_SIGNATURES = {
+    "prune_version": (_int, []),
+    "prune_status_string": (_c.c_char_p, [_int]),
+    "prune_workspace_bytes": (_sz, [_int, _i64, _i64]),
+    "prune_stats_accumulate": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
+    "prune_stats_finalize": (_int, [_vp, _i64, _vp, _vp]),
+    "prune_score": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "prune_outlier_ratio": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _f32, _vp, _vp, _vp, _vp]),
+    "prune_plan_sparsity": (_int, [_vp, _vp, _vp, _int, _int, _f64, _f64, _int, _vp, _vp, _vp]),
+    "prune_select_mask": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _vp, _vp, _u32, _vp, _vp, _sz, _vp]),
+    "prune_struct_compact": (_int, [_vp, _vp, _vp, _int, _i64, _i64, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+}
+
+
+class PruneError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        super().__init__(f"{fn} failed: status {status} ({status_string(status)})")
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load():
+    """Load the shared library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise RuntimeError(
+                f"{_LIB_PATH} is missing: run `python -m paper_2504_06323_amd.build` "
+                "(or __graft_entry__.build()) first; there is no fallback implementation")
+        lib = ctypes.CDLL(_LIB_PATH)
+        for name, (res, args) in _SIGNATURES.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+def exported_symbols() -> Tuple[str, ...]:
+    return tuple(_SIGNATURES)
+
+
+def status_string(status: int) -> str:
+    return load().prune_status_string(status).decode()
+
+
+def version() -> int:
+    return load().prune_version()
+
+
+def workspace_bytes(op: int, rows: int, cols: int) -> int:
+    return int(load().prune_workspace_bytes(op, rows, cols))
+
+
+# --------------------------------------------------------------------------- marshalling helpers
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}: float32 or bfloat16 expected")
+
+
+def _matrix(t: torch.Tensor, name: str) -> Tuple[int, int, int, int]:
+    """(pointer, rows, cols, pitch in elements) of a 2-D device tensor with unit column stride."""
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError(f"{name} must be 2-D with contiguous rows")
+    ld = t.stride(0) if t.shape[0] > 1 else max(t.shape[1], t.stride(0))
+    return t.data_ptr(), t.shape[0], t.shape[1], ld
+
+
+def _vector(t: Optional[torch.Tensor], name: str, dtype: torch.dtype, numel: Optional[int] = None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous {dtype} GPU tensor")
+    if numel is not None and t.numel() != numel:
+        raise ValueError(f"{name} must have {numel} elements, has {t.numel()}")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _workspace(ws: Optional[torch.Tensor], need: int, device) -> Tuple[Optional[int], int, Optional[torch.Tensor]]:
+    if ws is None:
+        ws = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return ws.data_ptr(), ws.numel() * ws.element_size(), ws
+
+
+def alloc_workspace(op: int, rows: int, cols: int, device="cuda") -> torch.Tensor:
+    """Device scratch large enough for one call of `op` (uninitialised)."""
+    return torch.empty(max(workspace_bytes(op, rows, cols), 256), dtype=torch.uint8, device=device)
+
+
+def _check(fn: str, status: int) -> None:
+    if status != 0:
+        raise PruneError(fn, status)
+
+
+# --------------------------------------------------------------------------- entry points
+
+def stats_accumulate(x: torch.Tensor, sumsq: torch.Tensor, ws: Optional[torch.Tensor] = None, stream=None) -> None:
+    """sumsq[j] += sum_t x[t, j]^2 (prune_stats_accumulate)."""
+    ptr, t, c, ld = _matrix(x, "x")
+    ws_ptr, ws_bytes, _keep = _workspace(ws, workspace_bytes(OP_STATS, max(t, 1), c), x.device)
+    _check("prune_stats_accumulate",
+           load().prune_stats_accumulate(ptr, _dtype_code(x), t, c, ld, _vector(sumsq, "sumsq", torch.float32, c),
+                                         ws_ptr, ws_bytes, _stream(stream)))
+
+
+def stats_finalize(sumsq: torch.Tensor, norms: torch.Tensor, stream=None) -> None:
+    """norms = sqrt(sumsq) (prune_stats_finalize)."""
+    n = sumsq.numel()
+    _check("prune_stats_finalize",
+           load().prune_stats_finalize(_vector(sumsq, "sumsq", torch.float32), n,
+                                       _vector(norms, "norms", torch.float32, n), _stream(stream)))
+
+
+def score(w: torch.Tensor, norms: torch.Tensor, score_sum: torch.Tensor, scores: Optional[torch.Tensor] = None,
+          ws: Optional[torch.Tensor] = None, stream=None) -> None:
+    """Eq. 5 metric sum, optionally materialising the metric (prune_score)."""
+    ptr, rows, cols, ld = _matrix(w, "w")
+    ws_ptr, ws_bytes, _keep = _workspace(ws, workspace_bytes(OP_SCORE, rows, cols), w.device)
+    _check("prune_score",
+           load().prune_score(ptr, _dtype_code(w), rows, cols, ld, _vector(norms, "norms", torch.float32, cols),
+                              _vector(scores, "scores", torch.float32, rows * cols),
+                              _vector(score_sum, "score_sum", torch.float64, 1), ws_ptr, ws_bytes, _stream(stream)))
+
+
+def outlier_ratio(w: Optional[torch.Tensor], norms: Optional[torch.Tensor], alpha: float, score_sum: torch.Tensor,
+                  count: torch.Tensor, tau: Optional[torch.Tensor] = None, scores: Optional[torch.Tensor] = None,
+                  stream=None) -> None:
+    """Eq. 6 outlier count against tau = float(alpha * mean) (prune_outlier_ratio)."""
+    if w is not None:
+        ptr, rows, cols, ld = _matrix(w, "w")
+        code = _dtype_code(w)
+    else:
+        if scores is None or scores.dim() != 2:
+            raise ValueError("without w, scores must be a 2-D tensor")
+        ptr, rows, cols, ld, code = None, scores.shape[0], scores.shape[1], scores.shape[1], F32
+    if count.dtype not in (torch.int64, torch.uint64):
+        raise ValueError("count must be a 64-bit integer tensor")
+    _check("prune_outlier_ratio",
+           load().prune_outlier_ratio(ptr, code, rows, cols, ld, _vector(norms, "norms", torch.float32, cols),
+                                      _vector(scores, "scores", torch.float32, rows * cols), float(alpha),
+                                      _vector(score_sum, "score_sum", torch.float64, 1),
+                                      _vector(count, "count", count.dtype, 1),
+                                      _vector(tau, "tau", torch.float32, 1), _stream(stream)))
+
+
+def plan_sparsity(counts: Sequence[int], numels: Sequence[int], n_layers: int, n_proj: int, p: float, lam: float,
+                  scope: int = SCOPE_GLOBAL, cols: Optional[Sequence[int]] = None):
+    """Host planner: outlier counts -> per-projection sparsity targets (prune_plan_sparsity).
+
+    Returns (sparsities, zeros-per-row counts or None when cols is not given, clamped flag),
+    each list holding n_layers * n_proj entries.
+    """
+    n = n_layers * n_proj
+    if len(counts) != n or len(numels) != n or (cols is not None and len(cols) != n):
+        raise ValueError("counts, numels (and cols) need n_layers * n_proj entries")
+    c_counts = (_c.c_ulonglong * n)(*[int(v) for v in counts])
+    c_numels = (_c.c_ulonglong * n)(*[int(v) for v in numels])
+    c_cols = (_c.c_int64 * n)(*[int(v) for v in cols]) if cols is not None else None
+    out = (_c.c_double * n)()
+    k_out = (_c.c_uint32 * n)() if cols is not None else None
+    clamped = _c.c_int(0)
+    _check("prune_plan_sparsity",
+           load().prune_plan_sparsity(c_counts, c_numels, c_cols, n_layers, n_proj, float(p), float(lam), int(scope),
+                                      out, k_out, _c.byref(clamped)))
+    return list(out), (list(k_out) if k_out is not None else None), bool(clamped.value)
+
+
+def select_mask(w: torch.Tensor, norms: Optional[torch.Tensor], k: int, w_out: Optional[torch.Tensor] = None,
+                mask_bits: Optional[torch.Tensor] = None, scores: Optional[torch.Tensor] = None,
+                ws: Optional[torch.Tensor] = None, stream=None) -> None:
+    """Zero the k lowest-metric entries of every row (prune_select_mask).  In place when w_out is None."""
+    ptr, rows, cols, ld = _matrix(w, "w")
+    if w_out is None:
+        out_ptr = ptr
+    else:
+        out_ptr, orows, ocols, old = _matrix(w_out, "w_out")
+        if (orows, ocols, old) != (rows, cols, ld) or w_out.dtype != w.dtype:
+            raise ValueError("w_out must match w in shape, pitch and dtype")
+    words = (cols + 31) // 32
+    if mask_bits is not None and mask_bits.dtype not in (torch.int32, torch.uint32):
+        raise ValueError("mask_bits must be a 32-bit integer tensor")
+    _check("prune_select_mask",
+           load().prune_select_mask(ptr, out_ptr, _dtype_code(w), rows, cols, ld,
+                                    _vector(norms, "norms", torch.float32, cols),
+                                    _vector(scores, "scores", torch.float32, rows * cols), int(k),
+                                    None if mask_bits is None else _vector(mask_bits, "mask_bits", mask_bits.dtype,
+                                                                           rows * words),
+                                    None if ws is None else ws.data_ptr(),
+                                    0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)))
+
+
+def struct_compact(gate: torch.Tensor, up: torch.Tensor, down: torch.Tensor, r: int, group_mag: torch.Tensor,
+                   kept_idx: torch.Tensor, gate_out: Optional[torch.Tensor] = None,
+                   up_out: Optional[torch.Tensor] = None, down_out: Optional[torch.Tensor] = None,
+                   ws: Optional[torch.Tensor] = None, stream=None) -> None:
+    """Rank MLP channels by group magnitude, drop the r lowest, gather the rest (prune_struct_compact)."""
+    for t, name in ((gate, "gate"), (up, "up"), (down, "down")):
+        if not (t.is_cuda and t.is_contiguous() and t.dim() == 2 and t.dtype == gate.dtype):
+            raise ValueError(f"{name} must be a contiguous 2-D GPU tensor of the common dtype")
+    inter, hidden = gate.shape
+    if tuple(up.shape) != (inter, hidden) or tuple(down.shape) != (hidden, inter):
+        raise ValueError("expected gate, up [inter, hidden] and down [hidden, inter]")
+    n_kept = inter - int(r)
+    outs = []
+    for t, name, shape in ((gate_out, "gate_out", (n_kept, hidden)), (up_out, "up_out", (n_kept, hidden)),
+                           (down_out, "down_out", (hidden, n_kept))):
+        if t is None:
+            outs.append(None)
+            continue
+        if not (t.is_cuda and t.is_contiguous() and t.dtype == gate.dtype and tuple(t.shape) == shape):
+            raise ValueError(f"{name} must be a contiguous GPU tensor of shape {shape}")
+        outs.append(t.data_ptr())
+    ws_ptr, ws_bytes, _keep = _workspace(ws, workspace_bytes(OP_STRUCT, inter, hidden), gate.device)
+    _check("prune_struct_compact",
+           load().prune_struct_compact(gate.data_ptr(), up.data_ptr(), down.data_ptr(), _dtype_code(gate), inter,
+                                       hidden, int(r), _vector(group_mag, "group_mag", torch.float32, inter),
+                                       _vector(kept_idx, "kept_idx", torch.int32, n_kept), outs[0], outs[1], outs[2],
+                                       ws_ptr, ws_bytes, _stream(stream)))

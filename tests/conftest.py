@@ -27,3 +27,12 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(scope="session")
+def lib():
+    """The loaded C-ABI library; built first only if no built library is present."""
+    from paper_2504_06323_amd import build as _build, prune
+    if not os.path.exists(prune.lib_path()):
+        _build.build(verbose=False)
+    return prune.load()

@@ -1,0 +1,330 @@
+"""HIP path vs CPU oracle, element by element, through the C-ABI.
+
+Floating-point outputs (sums of squares, norms, metric, metric sum, threshold,
+group magnitudes) are compared within rel 1e-5 (float32 inputs) / 1e-2 (bf16
+inputs).  Integer outputs (outlier count, masks, kept indices, gathers) are
+compared bit-exactly: where a float decides an integer, both sides take the
+decision in the kernel's precision -- the oracle's selection / count runs on
+the kernel's own float32 metric bits (materialised, or recomputed on the host
+as the single IEEE multiply float32(|w|) * float32(norm)).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mosaic_oracle as orc
+from paper_2504_06323_amd import prune, synth
+from util import bits, rel_err, to_np, tol_for
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+DTYPES = [torch.float32, torch.bfloat16]
+
+
+def _sync():
+    torch.cuda.synchronize()
+
+
+def gpu_norms(x, chunks=1):
+    c = x.shape[1]
+    sumsq = torch.zeros(c, dtype=torch.float32, device=DEV)
+    norms = torch.empty(c, dtype=torch.float32, device=DEV)
+    step = (x.shape[0] + chunks - 1) // chunks if x.shape[0] else 1
+    for t0 in range(0, max(x.shape[0], 1), step):
+        prune.stats_accumulate(x[t0:t0 + step], sumsq)
+    prune.stats_finalize(sumsq, norms)
+    _sync()
+    return sumsq, norms
+
+
+def host_metric_f32(w, norms):
+    """The kernel-precision metric recomputed on the host: one float32 multiply per element."""
+    return np.abs(to_np(w).astype(np.float32)) * to_np(norms).astype(np.float32)[None, :]
+
+
+# ----------------------------------------------------------------- stats
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("shape", [(512, 256), (512, 688), (513, 2056), (1000, 4104), (77, 8), (301, 7), (260, 130),
+                                   (1, 16), (4099, 24)])
+def test_stats_vs_oracle(lib, dtype, shape):
+    t, c = shape
+    x = synth.random_matrix(t, c, dtype, seed=t * 31 + c, device=DEV, scale=1.0)
+    x[:, c // 3] *= 20.0
+    sumsq, norms = gpu_norms(x)
+    want = orc.column_sumsq(to_np(x))
+    assert rel_err(to_np(sumsq), want) < tol_for(dtype)
+    assert rel_err(to_np(norms), np.sqrt(want)) < tol_for(dtype)
+    assert rel_err(to_np(sumsq), want) < 2e-6      # what the float accumulation actually delivers
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_stats_pitch_chunks_and_determinism(lib, dtype):
+    big = synth.random_matrix(700, 1024, dtype, seed=5, device=DEV)
+    x = big[:, 64:64 + 688]                               # pitch 1024, 16-byte aligned start
+    y = big[:, 3:3 + 101]                                 # unaligned start, odd width: scalar path
+    for view in (x, y):
+        s1, n1 = gpu_norms(view)
+        s2, n2 = gpu_norms(view)
+        assert np.array_equal(bits(s1), bits(s2)) and np.array_equal(bits(n1), bits(n2))
+        want = orc.column_sumsq(to_np(view))
+        assert rel_err(to_np(s1), want) < 2e-6
+        s3, _ = gpu_norms(view, chunks=3)                  # chunked accumulation into the same buffer
+        assert rel_err(to_np(s3), want) < 2e-6
+
+
+def test_stats_zero_tokens_and_closed_form(lib):
+    x = torch.empty((0, 64), dtype=torch.bfloat16, device=DEV)
+    sumsq = torch.full((64,), 3.0, dtype=torch.float32, device=DEV)
+    prune.stats_accumulate(x, sumsq)
+    _sync()
+    assert (to_np(sumsq) == 3.0).all()
+    x = torch.full((1024, 40), -1.5, dtype=torch.bfloat16, device=DEV)
+    _, norms = gpu_norms(x)
+    assert (to_np(norms) == np.float32(1.5 * 32.0)).all()   # |c| * sqrt(T), exact here
+
+
+# ----------------------------------------------------------------- score + outliers
+
+def _rank_inputs(rows, cols, dtype, seed):
+    w = synth.random_matrix(rows, cols, dtype, seed=seed, device=DEV, scale=0.02, zero_frac=0.01)
+    x = synth.random_matrix(300, cols, dtype, seed=seed + 1, device=DEV)
+    x[:, cols // 2] *= 30.0
+    return w, x
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("shape", [(256, 256), (688, 256), (256, 688), (37, 2056), (129, 4104), (50, 7), (33, 130),
+                                   (1, 8), (2000, 16)])
+def test_score_and_outliers_vs_oracle(lib, dtype, shape):
+    rows, cols = shape
+    w, x = _rank_inputs(rows, cols, dtype, seed=rows * 7 + cols)
+    _, norms = gpu_norms(x)
+    scores = torch.empty((rows, cols), dtype=torch.float32, device=DEV)
+    ssum = torch.zeros(1, dtype=torch.float64, device=DEV)
+    ssum_hot = torch.zeros(1, dtype=torch.float64, device=DEV)
+    prune.score(w, norms, ssum, scores=scores)
+    prune.score(w, norms, ssum_hot)                         # hot mode: sum only
+    _sync()
+    tol = tol_for(dtype)
+    # end to end against the float64 oracle (its own norms)
+    onorms = orc.column_norms(to_np(x))
+    omega = orc.weight_metric(to_np(w), onorms)
+    got = to_np(scores)
+    nz = omega > 0
+    assert rel_err(got[nz], omega[nz]) < tol and (got[~nz] == 0).all()
+    assert abs(ssum.item() - omega.sum()) <= tol * omega.sum()
+    assert ssum.item() == ssum_hot.item()                   # materialising does not change the sum
+    # kernel precision: the metric is exactly one float32 multiply
+    assert np.array_equal(got, host_metric_f32(w, norms))
+    assert abs(ssum.item() - got.astype(np.float64).sum()) <= 1e-6 * got.astype(np.float64).sum()
+
+    for alpha in (0.0, 1.0, 5.0):
+        count = torch.full((1,), -7, dtype=torch.int64, device=DEV)
+        count2 = torch.full((1,), -7, dtype=torch.int64, device=DEV)
+        tau = torch.zeros(1, dtype=torch.float32, device=DEV)
+        prune.outlier_ratio(w, norms, alpha, ssum, count, tau=tau)            # recompute mode
+        prune.outlier_ratio(None, None, alpha, ssum, count2, scores=scores)   # from materialised scores
+        _sync()
+        tau_h = np.float32(tau.item())
+        assert tau_h == orc.threshold_f32(alpha, ssum.item(), rows * cols)
+        # bit-exact protocol: the oracle counts on the kernel's score bits with the kernel's threshold
+        assert count.item() == count2.item() == orc.count_above(got, tau_h)
+        # end to end: oracle threshold within tolerance, counts differ at most by the near-threshold band
+        c_o, o_o, r_o, mean_o = orc.outlier_stats(omega, alpha)
+        assert abs(float(tau_h) - alpha * mean_o) <= tol * alpha * mean_o + 1e-30
+        band = np.count_nonzero(np.abs(omega - alpha * mean_o) <= 2 * tol * alpha * mean_o)
+        assert abs(count.item() - o_o) <= band
+
+
+def test_outlier_strictness_and_planted_column(lib):
+    # constant weights and activations: every metric equals the mean, nothing is strictly above it
+    w = torch.full((64, 128), 0.5, dtype=torch.float32, device=DEV)
+    x = torch.full((16, 128), 2.0, dtype=torch.float32, device=DEV)
+    _, norms = gpu_norms(x)
+    ssum = torch.zeros(1, dtype=torch.float64, device=DEV)
+    count = torch.zeros(1, dtype=torch.int64, device=DEV)
+    prune.score(w, norms, ssum)
+    prune.outlier_ratio(w, norms, 1.0, ssum, count)
+    _sync()
+    assert ssum.item() == 64 * 128 * 0.5 * 8.0 and count.item() == 0
+    # unit-magnitude weights, one channel with a huge norm: exactly that column's rows are outliers
+    w = torch.ones((64, 128), dtype=torch.bfloat16, device=DEV)
+    w[::2] *= -1
+    x[:, 5] = 2.0e4
+    _, norms = gpu_norms(x)
+    prune.score(w, norms, ssum)
+    prune.outlier_ratio(w, norms, 5.0, ssum, count)
+    _sync()
+    assert count.item() == 64
+
+
+# ----------------------------------------------------------------- select + mask
+
+def _check_select(w, norms, k, scores=None, in_place=False):
+    rows, cols = w.shape
+    w_in = w.clone() if in_place else w
+    w_ref = to_np(w)
+    out = w_in if in_place else torch.full_like(w, 7.0)
+    mask = torch.full((rows, (cols + 31) // 32), -1, dtype=torch.int32, device=DEV)
+    prune.select_mask(w_in, norms, k, w_out=None if in_place else out, mask_bits=mask, scores=scores)
+    _sync()
+    metric = to_np(scores) if scores is not None else host_metric_f32(w, norms)
+    pruned = orc.select_smallest_per_row(metric, k)          # oracle selection on the kernel's metric bits
+    want = orc.apply_mask(w_ref, pruned)
+    got = to_np(out)
+    assert np.array_equal(got, want), f"masked weights differ in {np.count_nonzero(got != want)} places"
+    assert np.array_equal(to_np(mask).view(np.uint32), orc.pack_keep_bits(pruned))
+    assert (pruned.sum(axis=1) == k).all()
+    assert np.array_equal(got[~pruned].view(np.uint32), w_ref[~pruned].view(np.uint32))   # survivors bit-identical
+    return out
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("shape", [(256, 256), (688, 256), (256, 688), (19, 2056), (11, 4104), (9, 11008),
+                                   (7, 14336), (5, 16384), (6, 16392), (50, 7), (33, 130), (3, 8), (4, 1000)])
+def test_select_vs_oracle(lib, dtype, shape):
+    rows, cols = shape
+    w, x = _rank_inputs(rows, cols, dtype, seed=rows * 13 + cols)
+    _, norms = gpu_norms(x)
+    for k in sorted({0, 1, cols // 2, cols - 1, cols}):
+        _check_select(w, norms, k)
+    _check_select(w, norms, cols // 3, in_place=True)
+    scores = torch.empty((rows, cols), dtype=torch.float32, device=DEV)
+    ssum = torch.zeros(1, dtype=torch.float64, device=DEV)
+    prune.score(w, norms, ssum, scores=scores)
+    _check_select(w, norms, cols // 2, scores=scores)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("cols", [64, 688, 4096, 1001])
+def test_select_ties(lib, dtype, cols):
+    """Many equal metrics: zeros, constant rows, few distinct values -- the index decides."""
+    rows = 12
+    g = torch.Generator(device="cpu").manual_seed(cols)
+    vals = torch.randint(-3, 4, (rows, cols), generator=g).to(torch.float32) * 0.25
+    vals[0] = 0.0
+    vals[1] = 0.5
+    w = vals.to(dtype).to(DEV)
+    norms = torch.ones(cols, dtype=torch.float32, device=DEV)
+    norms[cols // 2:] = 2.0
+    for k in (1, cols // 4, cols // 2, cols - 3):
+        _check_select(w, norms, k)
+    # an all-zero norm vector makes every metric zero
+    _check_select(w, torch.zeros(cols, dtype=torch.float32, device=DEV), cols // 2)
+
+
+def test_select_pitch_and_determinism(lib):
+    big = synth.random_matrix(40, 2048, torch.bfloat16, seed=77, device=DEV, scale=0.02)
+    w = big[:, 256:256 + 1024]                              # pitch 2048
+    norms = (torch.arange(1024, device=DEV, dtype=torch.float32) % 17) + 0.5
+    o1 = _check_select(w, norms, 400)
+    o2 = _check_select(w, norms, 400)
+    assert np.array_equal(bits(o1), bits(o2))
+    assert np.array_equal(bits(big[:, :256]), bits(synth.random_matrix(40, 2048, torch.bfloat16, seed=77, device=DEV,
+                                                                       scale=0.02)[:, :256]))
+
+
+def test_select_is_magnitude_pruning_when_norms_are_one(lib):
+    w = synth.random_matrix(64, 512, torch.float32, seed=3, device=DEV)
+    norms = torch.ones(512, dtype=torch.float32, device=DEV)
+    out = _check_select(w, norms, 256)
+    kth = np.partition(np.abs(to_np(w)), 255, axis=1)[:, 255]          # library top-k special case
+    got = to_np(out)
+    assert (np.abs(to_np(w))[got == 0].reshape(64, -1).max(axis=1) <= kth).all()
+    assert (np.count_nonzero(got == 0, axis=1) == 256).all()
+
+
+# ----------------------------------------------------------------- structured
+
+def _check_struct(gate, up, down, r, compact=True):
+    inter, hidden = gate.shape
+    g = torch.empty(inter, dtype=torch.float32, device=DEV)
+    kept = torch.full((inter - r,), -1, dtype=torch.int32, device=DEV)
+    outs = [None, None, None]
+    if compact:
+        outs = [torch.empty((inter - r, hidden), dtype=gate.dtype, device=DEV),
+                torch.empty((inter - r, hidden), dtype=gate.dtype, device=DEV),
+                torch.empty((hidden, inter - r), dtype=gate.dtype, device=DEV)]
+    prune.struct_compact(gate, up, down, r, g, kept, *outs)
+    _sync()
+    want_g = orc.group_magnitude(to_np(gate), to_np(up), to_np(down))
+    nz = want_g > 0
+    assert rel_err(to_np(g)[nz], want_g[nz]) < tol_for(gate.dtype)
+    assert rel_err(to_np(g)[nz], want_g[nz]) < 5e-6
+    assert (to_np(g)[~nz] == 0).all()
+    want_kept = orc.struct_rank(to_np(g), r)                # oracle ranking on the kernel's magnitudes
+    assert np.array_equal(to_np(kept), want_kept)
+    if compact:
+        wg, wu, wd = orc.struct_compact(to_np(gate), to_np(up), to_np(down), want_kept)
+        assert np.array_equal(to_np(outs[0]), wg) and np.array_equal(to_np(outs[1]), wu)
+        assert np.array_equal(to_np(outs[2]), wd)
+    return to_np(g), to_np(kept)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("shape", [(688, 256), (2056, 264), (1500, 100), (37, 19), (4104, 512)])
+def test_struct_vs_oracle(lib, dtype, shape):
+    inter, hidden = shape
+    gate = synth.random_matrix(inter, hidden, dtype, seed=inter + 1, device=DEV, scale=0.02, zero_frac=0.3)
+    up = synth.random_matrix(inter, hidden, dtype, seed=inter + 2, device=DEV, scale=0.02, zero_frac=0.3)
+    down = synth.random_matrix(hidden, inter, dtype, seed=inter + 3, device=DEV, scale=0.02, zero_frac=0.3)
+    gate[5] = 0
+    up[5] = 0
+    down[:, 5] = 0                                          # an emptied channel: magnitude exactly zero
+    gate[9] = 0
+    up[9] = 0
+    down[:, 9] = 0                                          # and a second one: a real tie
+    for r in sorted({0, 1, 2, int(0.2 * inter), inter - 1}):
+        _check_struct(gate, up, down, r)
+    g1, k1 = _check_struct(gate, up, down, inter // 3, compact=False)
+    g2, k2 = _check_struct(gate, up, down, inter // 3, compact=False)
+    assert np.array_equal(g1.view(np.uint32), g2.view(np.uint32)) and np.array_equal(k1, k2)
+
+
+# ----------------------------------------------------------------- whole toy layer (configs[0])
+
+def test_toy_layer_end_to_end(lib):
+    """configs[0]: rank, plan, unstructured prune, structured removal; every output against the oracle."""
+    from paper_2504_06323_amd import pipeline
+    cfg = synth.CONFIGS["toy"]
+    shapes = synth.projection_shapes(cfg)
+    weights = {n: synth.make_weight(cfg, 0, n, DEV) for n, _, _, _ in shapes}
+    acts = {a: synth.make_activation(cfg, 0, a, DEV) for a in synth.activation_shapes(cfg)}
+    st = pipeline.LayerState.create(weights, {n: a for n, _, _, a in shapes}, synth.activation_shapes(cfg),
+                                    cfg.n_tokens)
+    scores = {n: torch.empty((r, c), dtype=torch.float32, device=DEV) for n, r, c, _ in shapes}
+    pipeline.rank_layer(st, acts, cfg.alpha, scores=scores)
+    _sync()
+    counts, numels, cols = st.count.tolist(), [r * c for _, r, c, _ in shapes], [c for _, _, c, _ in shapes]
+    ratios = []
+    for i, (n, r, c, a) in enumerate(shapes):
+        norms, omega, C, O, R, mean = orc.rank_projection(to_np(acts[a]), to_np(weights[n]), cfg.alpha)
+        assert rel_err(to_np(st.norms[a]), norms) < 1e-5
+        assert rel_err(to_np(scores[n]), np.maximum(omega, 1e-300)) < 1e-5
+        assert counts[i] == orc.count_above(to_np(scores[n]), np.float32(st.tau[i].item()))
+        assert abs(counts[i] - O) <= np.count_nonzero(np.abs(omega - cfg.alpha * mean) <= 2e-5 * cfg.alpha * mean)
+        assert 0.5 < R < 6.0                                  # planted outliers give a ratio of a few percent
+        ratios.append(100.0 * counts[i] / numels[i])
+    s, ks, clamped = pipeline.plan(counts, numels, cols, 1, len(shapes), cfg.p, cfg.lam)
+    want_s, _ = orc.plan_sparsity(np.array(ratios).reshape(1, -1), cfg.p, cfg.lam, "global")
+    assert np.allclose(s, want_s.reshape(-1), atol=1e-13) and not clamped
+    assert ks == [orc.zeros_per_row(v, c) for v, c in zip(s, cols)]
+    pipeline.prune_layer(st, ks)
+    _sync()
+    for i, (n, r, c, a) in enumerate(shapes):
+        pruned = orc.select_smallest_per_row(to_np(scores[n]), ks[i])
+        assert np.array_equal(to_np(st.pruned[n]), orc.apply_mask(to_np(weights[n]), pruned))
+        assert np.array_equal(to_np(st.mask_bits[n]).view(np.uint32), orc.pack_keep_bits(pruned))
+    r = int(cfg.struct_frac * cfg.inter)
+    res = pipeline.alloc_struct(st, r)
+    pipeline.struct_layer(st, r, res)
+    _sync()
+    masked = {n: to_np(st.pruned[n]) for n in ("gate", "up", "down")}
+    want_g = orc.group_magnitude(masked["gate"], masked["up"], masked["down"])
+    assert rel_err(to_np(res.group_mag), want_g) < 1e-5
+    kept = orc.struct_rank(to_np(res.group_mag), r)
+    assert np.array_equal(to_np(res.kept_idx), kept)
+    wg, wu, wd = orc.struct_compact(masked["gate"], masked["up"], masked["down"], kept)
+    assert np.array_equal(to_np(res.gate), wg) and np.array_equal(to_np(res.up), wu)
+    assert np.array_equal(to_np(res.down), wd)
