@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the projection-pruning hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic LLaMA-7B-shaped layer
+(the workload the headline metric is quoted on): activation statistics for the
+four distinct projection inputs (128 x 2048 calibration tokens), metric sum and
+outlier count for the seven projections, the host planner, per-row selection
+and masking of the seven projections, then structured ranking and compaction
+of the MLP on the masked weights.  All inputs are resident in HBM before the
+timed region starts.  One JSON line goes to stdout; everything else to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E peak
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(cfg, shapes, act_shapes, r):
+    """Bytes the method itself must move per step (what the roofline is priced on)."""
+    es = 2 if str(cfg.dtype).endswith("bfloat16") else 4
+    numel = sum(rw * c for _, rw, c, _ in shapes)
+    stats = sum(cfg.n_tokens * ch * es + ch * 4 for ch in act_shapes.values())
+    score = numel * es
+    count = numel * es
+    select = numel * (2 * es) + numel // 8
+    mlp = 3 * cfg.inter * cfg.hidden
+    struct_rank = mlp * es
+    kept_frac = (cfg.inter - r) / cfg.inter
+    compact = mlp * es + int(mlp * es * kept_frac)
+    return dict(stats=stats, score=score, count=count, select=select, struct_rank=struct_rank, compact=compact,
+                total=stats + score + count + select + struct_rank + compact)
+
+
+def cpu_baseline(cfg, shapes, weights, acts, frac_den=8):
+    """Time the CPU oracle, as it stands, on a 1/frac_den sample of the same layer."""
+    import numpy as np
+    import torch
+    from oracle import mosaic_oracle as orc
+
+    n_seqs = max(1, cfg.n_seqs // frac_den)
+    t_rows = n_seqs * cfg.seq_len
+    host = lambda t: t.detach().cpu().to(torch.float32).numpy()
+    xs = {a: host(x[:t_rows]) for a, x in acts.items()}
+    ws = {n: host(w[::frac_den]) for n, w in weights.items()}
+    sampled = sum(w.size for w in ws.values())
+    t0 = time.perf_counter()
+    norms = {a: orc.column_norms(x) for a, x in xs.items()}
+    ratios, omegas = [], {}
+    for n, rw, c, a in shapes:
+        omega = orc.weight_metric(ws[n], norms[a])
+        _, _, ratio, _ = orc.outlier_stats(omega, cfg.alpha)
+        ratios.append(ratio)
+        omegas[n] = omega
+    s, _ = orc.plan_sparsity(np.array(ratios).reshape(1, -1), cfg.p, cfg.lam, "global")
+    masked = {}
+    for i, (n, rw, c, a) in enumerate(shapes):
+        masked[n], _ = orc.prune_projection(ws[n], omegas[n], orc.zeros_per_row(s[0, i], c))
+    # structured part on the sample: every frac_den-th MLP channel forms the sampled MLP
+    gate, up = masked["gate"], masked["up"]
+    down = host(weights["down"][:, ::frac_den])
+    g = orc.group_magnitude(gate, up, down)
+    kept = orc.struct_rank(g, int(cfg.struct_frac * g.shape[0]))
+    orc.struct_compact(gate, up, down, kept)
+    dt = time.perf_counter() - t0
+    return {"value": sampled / dt, "unit": "weights/s", "cores": 1, "kind": "oracle",
+            "sample": f"1/{frac_den} of the layer: {n_seqs} of {cfg.n_seqs} calibration sequences for the activation "
+                      f"statistics, every {frac_den}th output row of each projection ({sampled} weights); "
+                      f"NumPy float64, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama7b_layer")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-den", type=int, default=8)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py measures one GPU: every box of this build has one MI355X and the path has no "
+            "multi-GPU leg. Run with --gpus 1.")
+        sys.exit(2)
+
+    import torch
+    from paper_2504_06323_amd import pipeline, prune, synth
+
+    if not torch.cuda.is_available():
+        log("bench.py needs a GPU")
+        sys.exit(2)
+    prune.load()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.workload]
+    shapes = synth.projection_shapes(cfg)
+    act_shapes = synth.activation_shapes(cfg)
+    numel = synth.layer_numel(cfg)
+    r = int(cfg.struct_frac * cfg.inter)
+
+    t0 = time.perf_counter()
+    weights = {n: synth.make_weight(cfg, 0, n, dev) for n, _, _, _ in shapes}
+    acts = {a: synth.make_activation(cfg, 0, a, dev) for a in act_shapes}
+    torch.cuda.synchronize()
+    log(f"inputs generated in {time.perf_counter() - t0:.1f} s: {numel} weights, "
+        f"{sum(x.numel() for x in acts.values())} activation elements")
+
+    st = pipeline.LayerState.create(weights, {n: a for n, _, _, a in shapes}, act_shapes, cfg.n_tokens)
+    res = pipeline.alloc_struct(st, r)
+    numels = [rw * c for _, rw, c, _ in shapes]
+    cols = [c for _, _, c, _ in shapes]
+    names = list(act_shapes)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    stats_events = []   # (start, stop, bytes) around every statistics launch of the timed region
+    pass_events = []    # per-step boundaries for the stderr breakdown
+
+    def step(record: bool):
+        # phase 1: ranking (independent of p)
+        marks = [ev() for _ in range(5)] if record else None
+        if record:
+            marks[0].record()
+        for a in names:
+            x = acts[a]
+            st.sumsq[a].zero_()
+            if record:
+                e0, e1 = ev(), ev()
+                e0.record()
+            prune.stats_accumulate(x, st.sumsq[a], ws=st.ws)
+            if record:
+                e1.record()
+                stats_events.append((e0, e1, x.numel() * x.element_size() + x.shape[1] * 4))
+            prune.stats_finalize(st.sumsq[a], st.norms[a])
+        if record:
+            marks[1].record()
+        for i, name in enumerate(st.names):
+            w, nrm = st.weights[name], st.norms[st.proj_inputs[name]]
+            prune.score(w, nrm, st.score_sum[i:i + 1], ws=st.ws)
+            prune.outlier_ratio(w, nrm, cfg.alpha, st.score_sum[i:i + 1], st.count[i:i + 1], tau=st.tau[i:i + 1])
+        if record:
+            marks[2].record()
+        counts = st.count.tolist()          # 7 integers cross to the host: the planner needs every ratio
+        _, ks, _ = pipeline.plan(counts, numels, cols, 1, len(shapes), cfg.p, cfg.lam)
+        # phase 2: pruning
+        pipeline.prune_layer(st, ks)
+        if record:
+            marks[3].record()
+        pipeline.struct_layer(st, r, res)
+        if record:
+            marks[4].record()
+            pass_events.append(marks)
+        return counts, ks
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        counts, ks = step(True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    ab = algorithmic_bytes(cfg, shapes, act_shapes, r)
+    stats_ms = [a.elapsed_time(b) for a, b, _ in stats_events]
+    stats_bytes = [n for _, _, n in stats_events]
+    avg_ms = sum(stats_ms) / len(stats_ms)
+    avg_bytes = sum(stats_bytes) / len(stats_bytes)
+    achieved = avg_bytes / (avg_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "colsumsq_partial_vec (activation statistics)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "avg_launch_ms": round(avg_ms, 4), "avg_launch_bytes": int(avg_bytes),
+                "launches": len(stats_ms)}
+
+    seg = [[m[i].elapsed_time(m[i + 1]) for i in range(4)] for m in pass_events]
+    mean = lambda j: sum(s[j] for s in seg) / len(seg)
+    gb = lambda key: ab[key] / 1e9
+    log(f"step {ms_per_step:.3f} ms | stats {mean(0):.3f} ms ({gb('stats') / mean(0) * 1e3:.0f} GB/s) | "
+        f"score+count {mean(1):.3f} ms ({(gb('score') + gb('count')) / mean(1) * 1e3:.0f} GB/s) | "
+        f"plan+select {mean(2):.3f} ms ({gb('select') / mean(2) * 1e3:.0f} GB/s) | "
+        f"struct {mean(3):.3f} ms ({(gb('struct_rank') + gb('compact')) / mean(3) * 1e3:.0f} GB/s)")
+    log(f"outlier counts {counts}; zeros per row {ks}; removed MLP channels {r}")
+
+    out = {
+        "metric": "projection weights pruned/s (GB/s scored+masked) and % of HBM peak, 1 GPU",
+        "value": numel * args.steps / elapsed,
+        "unit": "weights/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: one LLaMA-7B-shaped layer, bf16 storage, hidden {cfg.hidden}, "
+                               f"intermediate {cfg.inter}, {cfg.n_seqs} x {cfg.seq_len} calibration tokens, "
+                               f"4 distinct activation tensors, alpha {cfg.alpha}, target sparsity {cfg.p}, "
+                               f"{r} of {cfg.inter} MLP channels removed structurally",
+                   "weights_per_step": numel,
+                   "algorithmic_bytes_per_step": ab["total"],
+                   "storage_dtype": "bf16"},
+        "algorithmic_gbps": round(ab["total"] / elapsed * args.steps / 1e9, 1),
+        "hbm_frac_whole_step": round(ab["total"] / elapsed * args.steps / 1e9 / HBM_PEAK_GBPS, 4),
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, shapes, weights, acts, args.cpu_sample_den)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -139,14 +139,14 @@ int prune_plan_sparsity(const unsigned long long *counts, const unsigned long lo
  * omega are zeroed; among equal omega the lower column goes first, so the
  * result is unique.  omega is recomputed from (w, norms) as in prune_score, or
  * read from `scores` (contiguous [rows, cols], non-negative) when non-NULL.
- *   w_out[i, j] = pruned(i, j) ? 0 : w[i, j]          same dtype and ld as w
- * w_out may equal w (in place) or be a separate buffer; partial overlap is
- * not allowed.  mask_bits is optional: uint32 [rows, ceil(cols / 32)], bit b of
+ *   w_out[i, j] = pruned(i, j) ? 0 : w[i, j]          same dtype as w, pitch ld_out
+ * w_out may equal w (in place, then ld_out == ld_w) or be a separate buffer;
+ * partial overlap is not allowed.  mask_bits is optional: uint32 [rows, ceil(cols / 32)], bit b of
  * word q of a row is 1 iff column 32 * q + b is kept; bits past cols are 0.
  * 0 <= k <= cols; k == 0 copies w to w_out.
  */
 int prune_select_mask(const void *w, void *w_out, int dtype, int64_t rows, int64_t cols, int64_t ld_w,
-                      const float *norms, const float *scores, uint32_t k, uint32_t *mask_bits, void *ws,
+                      int64_t ld_out, const float *norms, const float *scores, uint32_t k, uint32_t *mask_bits, void *ws,
                       size_t ws_bytes, void *stream);
 
 /*

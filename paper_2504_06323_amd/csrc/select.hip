@@ -14,7 +14,7 @@ namespace mp {
 namespace {
 
 template <typename T, int BLOCK, int NCHUNK, bool FROM_SCORES>
-__global__ __launch_bounds__(BLOCK) void select_rows_vec(const T *w, T *w_out, int64_t cols, int64_t ld,
+__global__ __launch_bounds__(BLOCK) void select_rows_vec(const T *w, T *w_out, int64_t cols, int64_t ld, int64_t ld_out,
                                                          const float *__restrict__ norms,
                                                          const float *__restrict__ scores, uint32_t k, int idx_bits,
                                                          uint8_t *__restrict__ mask_bytes, int64_t mask_row_bytes) {
@@ -69,7 +69,7 @@ __global__ __launch_bounds__(BLOCK) void select_rows_vec(const T *w, T *w_out, i
             for (int e = 0; e < 8; ++e)
                 keep |= (composite(key[c][e], static_cast<uint32_t>(col0 + e), idx_bits) > bound ? 1u : 0u) << e;
             pk[c].apply_keep(keep);
-            pk[c].store(w_out + row * ld + col0);
+            pk[c].store(w_out + row * ld_out + col0);
             if (mask_bytes) {
                 uint8_t *mrow = mask_bytes + row * mask_row_bytes;
                 mrow[col0 >> 3] = static_cast<uint8_t>(keep);
@@ -82,7 +82,7 @@ __global__ __launch_bounds__(BLOCK) void select_rows_vec(const T *w, T *w_out, i
 
 // any width / pitch / alignment; keys are recomputed from memory on every digit pass
 template <typename T, int BLOCK, bool FROM_SCORES>
-__global__ __launch_bounds__(BLOCK) void select_rows_generic(const T *w, T *w_out, int64_t cols, int64_t ld,
+__global__ __launch_bounds__(BLOCK) void select_rows_generic(const T *w, T *w_out, int64_t cols, int64_t ld, int64_t ld_out,
                                                              const float *__restrict__ norms,
                                                              const float *__restrict__ scores, uint32_t k,
                                                              int idx_bits, uint32_t *__restrict__ mask_words,
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(BLOCK) void select_rows_generic(const T *w, T *w_ou
             },
             k, idx_bits, sm);
     }
-    T *orow = w_out + row * ld;
+    T *orow = w_out + row * ld_out;
     for (int64_t q = tid; q < words_per_row; q += BLOCK) {
         uint32_t word = 0;
         for (int b = 0; b < 32; ++b) {
@@ -121,12 +121,12 @@ __global__ __launch_bounds__(BLOCK) void select_rows_generic(const T *w, T *w_ou
 
 template <typename T>
 __global__ __launch_bounds__(256) void copy_rows(const T *__restrict__ src, T *__restrict__ dst, int64_t rows,
-                                                 int64_t cols, int64_t ld) {
+                                                 int64_t cols, int64_t ld, int64_t ld_out) {
     const int64_t n = rows * cols;
     for (int64_t i = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; i < n;
          i += static_cast<int64_t>(gridDim.x) * 256) {
         const int64_t r = i / cols, c = i - r * cols;
-        dst[r * ld + c] = src[r * ld + c];
+        dst[r * ld_out + c] = src[r * ld + c];
     }
 }
 
@@ -143,23 +143,23 @@ __global__ __launch_bounds__(256) void fill_keep_all(uint32_t *__restrict__ mask
 }
 
 template <typename T, bool FROM_SCORES>
-int launch_select(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld, const float *norms,
+int launch_select(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld, int64_t ld_out, const float *norms,
                   const float *scores, uint32_t k, uint32_t *mask_bits, hipStream_t stream) {
     const int idx_bits = index_bits_for(cols);
     const int64_t words = ceil_div(cols, 32);
     const dim3 grid(static_cast<unsigned>(rows));
-    bool vec = packet_ok(w, cols, ld) && aligned_to(w_out, 16) && cols <= 16384;
+    bool vec = packet_ok(w, cols, ld) && packet_ok(w_out, cols, ld_out) && cols <= 16384;
     if (FROM_SCORES ? !aligned_to(scores, 16) : !aligned_to(norms, 16)) vec = false;
     if (!vec) {
         hipLaunchKernelGGL((select_rows_generic<T, 256, FROM_SCORES>), grid, dim3(256), 0, stream, w, w_out, cols,
-                           ld, norms, scores, k, idx_bits, mask_bits, words);
+                           ld, ld_out, norms, scores, k, idx_bits, mask_bits, words);
         return launch_status();
     }
     uint8_t *mb = reinterpret_cast<uint8_t *>(mask_bits);
     const int64_t mrb = words * 4;
 #define MP_SELECT_CASE(BLOCK, NCHUNK)                                                                              \
     hipLaunchKernelGGL((select_rows_vec<T, BLOCK, NCHUNK, FROM_SCORES>), grid, dim3(BLOCK), 0, stream, w, w_out,   \
-                       cols, ld, norms, scores, k, idx_bits, mb, mrb)
+                       cols, ld, ld_out, norms, scores, k, idx_bits, mb, mrb)
     if (cols <= 512) MP_SELECT_CASE(64, 1);
     else if (cols <= 1024) MP_SELECT_CASE(64, 2);
     else if (cols <= 2048) MP_SELECT_CASE(256, 1);
@@ -175,11 +175,11 @@ int launch_select(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld, 
 }
 
 template <typename T>
-int select_dispatch(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld, const float *norms,
+int select_dispatch(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld, int64_t ld_out, const float *norms,
                     const float *scores, uint32_t k, uint32_t *mask_bits, hipStream_t stream) {
     if (k == 0) {  // nothing to prune: copy through, every bit kept
         if (w_out != w) {
-            hipLaunchKernelGGL(copy_rows<T>, dim3(2048), dim3(256), 0, stream, w, w_out, rows, cols, ld);
+            hipLaunchKernelGGL(copy_rows<T>, dim3(2048), dim3(256), 0, stream, w, w_out, rows, cols, ld, ld_out);
             if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
         }
         if (mask_bits) {
@@ -189,8 +189,8 @@ int select_dispatch(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld
         }
         return PRUNE_OK;
     }
-    return scores ? launch_select<T, true>(w, w_out, rows, cols, ld, norms, scores, k, mask_bits, stream)
-                  : launch_select<T, false>(w, w_out, rows, cols, ld, norms, scores, k, mask_bits, stream);
+    return scores ? launch_select<T, true>(w, w_out, rows, cols, ld, ld_out, norms, scores, k, mask_bits, stream)
+                  : launch_select<T, false>(w, w_out, rows, cols, ld, ld_out, norms, scores, k, mask_bits, stream);
 }
 
 }  // namespace
@@ -200,14 +200,15 @@ size_t select_workspace_bytes(int64_t, int64_t) { return 0; }  // the row lives 
 }  // namespace mp
 
 extern "C" int prune_select_mask(const void *w, void *w_out, int dtype, int64_t rows, int64_t cols, int64_t ld_w,
-                                 const float *norms, const float *scores, uint32_t k, uint32_t *mask_bits, void *ws,
+                                 int64_t ld_out, const float *norms, const float *scores, uint32_t k, uint32_t *mask_bits, void *ws,
                                  size_t ws_bytes, void *stream_) {
     using namespace mp;
     (void)ws;
     (void)ws_bytes;
     if (!valid_dtype(dtype)) return PRUNE_ERR_DTYPE;
-    if (rows <= 0 || cols <= 0 || ld_w < cols || cols > (int64_t(1) << 32) || rows > 0x7fffffff)
+    if (rows <= 0 || cols <= 0 || ld_w < cols || ld_out < cols || cols > (int64_t(1) << 32) || rows > 0x7fffffff)
         return PRUNE_ERR_SHAPE;
+    if (w_out == w && ld_out != ld_w) return PRUNE_ERR_SHAPE;
     if (!w || !w_out || (!scores && !norms)) return PRUNE_ERR_NULL;
     if (static_cast<int64_t>(k) > cols) return PRUNE_ERR_RANGE;
     const size_t es = elem_size(dtype);
@@ -216,13 +217,14 @@ extern "C" int prune_select_mask(const void *w, void *w_out, int dtype, int64_t 
         return PRUNE_ERR_ALIGNMENT;
     if (w_out != w) {  // separate output must not partially overlap the input
         const uintptr_t a = reinterpret_cast<uintptr_t>(w), b = reinterpret_cast<uintptr_t>(w_out);
-        const uintptr_t span = static_cast<uintptr_t>((rows - 1) * ld_w + cols) * es;
-        if ((a < b && a + span > b) || (b < a && b + span > a)) return PRUNE_ERR_RANGE;
+        const uintptr_t span_a = static_cast<uintptr_t>((rows - 1) * ld_w + cols) * es;
+        const uintptr_t span_b = static_cast<uintptr_t>((rows - 1) * ld_out + cols) * es;
+        if ((a < b && a + span_a > b) || (b < a && b + span_b > a)) return PRUNE_ERR_RANGE;
     }
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     if (dtype == PRUNE_BF16)
-        return select_dispatch(static_cast<const bf16_t *>(w), static_cast<bf16_t *>(w_out), rows, cols, ld_w, norms,
+        return select_dispatch(static_cast<const bf16_t *>(w), static_cast<bf16_t *>(w_out), rows, cols, ld_w, ld_out, norms,
                                scores, k, mask_bits, stream);
-    return select_dispatch(static_cast<const float *>(w), static_cast<float *>(w_out), rows, cols, ld_w, norms, scores,
+    return select_dispatch(static_cast<const float *>(w), static_cast<float *>(w_out), rows, cols, ld_w, ld_out, norms, scores,
                            k, mask_bits, stream);
 }

@@ -36,7 +36,7 @@ _SIGNATURES = {
     "prune_score": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]),
     "prune_outlier_ratio": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _f32, _vp, _vp, _vp, _vp]),
     "prune_plan_sparsity": (_int, [_vp, _vp, _vp, _int, _int, _f64, _f64, _int, _vp, _vp, _vp]),
-    "prune_select_mask": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _vp, _vp, _u32, _vp, _vp, _sz, _vp]),
+    "prune_select_mask": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _i64, _vp, _vp, _u32, _vp, _vp, _sz, _vp]),
     "prune_struct_compact": (_int, [_vp, _vp, _vp, _int, _i64, _i64, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
 }
 
@@ -214,16 +214,16 @@ def select_mask(w: torch.Tensor, norms: Optional[torch.Tensor], k: int, w_out: O
     """Zero the k lowest-metric entries of every row (prune_select_mask).  In place when w_out is None."""
     ptr, rows, cols, ld = _matrix(w, "w")
     if w_out is None:
-        out_ptr = ptr
+        out_ptr, ld_out = ptr, ld
     else:
-        out_ptr, orows, ocols, old = _matrix(w_out, "w_out")
-        if (orows, ocols, old) != (rows, cols, ld) or w_out.dtype != w.dtype:
-            raise ValueError("w_out must match w in shape, pitch and dtype")
+        out_ptr, orows, ocols, ld_out = _matrix(w_out, "w_out")
+        if (orows, ocols) != (rows, cols) or w_out.dtype != w.dtype:
+            raise ValueError("w_out must match w in shape and dtype")
     words = (cols + 31) // 32
     if mask_bits is not None and mask_bits.dtype not in (torch.int32, torch.uint32):
         raise ValueError("mask_bits must be a 32-bit integer tensor")
     _check("prune_select_mask",
-           load().prune_select_mask(ptr, out_ptr, _dtype_code(w), rows, cols, ld,
+           load().prune_select_mask(ptr, out_ptr, _dtype_code(w), rows, cols, ld, ld_out,
                                     _vector(norms, "norms", torch.float32, cols),
                                     _vector(scores, "scores", torch.float32, rows * cols), int(k),
                                     None if mask_bits is None else _vector(mask_bits, "mask_bits", mask_bits.dtype,

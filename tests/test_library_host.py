@@ -68,11 +68,12 @@ def test_error_paths_return_before_any_launch(lib):
     assert orr(None, 1, 8, 8, 8, None, None, 5.0, fake, fake, None, None) == E["null"]
     assert orr(fake, 1, 8, 8, 8, fake, None, 5.0, fake, None, None, None) == E["null"]
     sm = lib.prune_select_mask
-    assert sm(fake, fake, 1, 8, 8, 8, fake, None, 9, None, None, 0, None) == E["rng"]   # k > cols
-    assert sm(fake, fake, 1, 8, 8, 4, fake, None, 1, None, None, 0, None) == E["shape"]
-    assert sm(fake, None, 1, 8, 8, 8, fake, None, 1, None, None, 0, None) == E["null"]
-    assert sm(fake, fake, 1, 8, 8, 8, None, None, 1, None, None, 0, None) == E["null"]
-    assert sm(fake, ctypes.c_void_p(0x1010), 1, 8, 8, 8, fake, None, 1, None, None, 0, None) == E["rng"]  # overlap
+    assert sm(fake, fake, 1, 8, 8, 8, 8, fake, None, 9, None, None, 0, None) == E["rng"]   # k > cols
+    assert sm(fake, fake, 1, 8, 8, 4, 8, fake, None, 1, None, None, 0, None) == E["shape"]
+    assert sm(fake, fake, 1, 8, 8, 8, 16, fake, None, 1, None, None, 0, None) == E["shape"]  # in place, other pitch
+    assert sm(fake, None, 1, 8, 8, 8, 8, fake, None, 1, None, None, 0, None) == E["null"]
+    assert sm(fake, fake, 1, 8, 8, 8, 8, None, None, 1, None, None, 0, None) == E["null"]
+    assert sm(fake, ctypes.c_void_p(0x1010), 1, 8, 8, 8, 8, fake, None, 1, None, None, 0, None) == E["rng"]  # overlap
     st = lib.prune_struct_compact
     assert st(fake, fake, fake, 1, 8, 8, 8, fake, fake, None, None, None, fake, 1 << 20, None) == E["rng"]  # r >= inter
     assert st(fake, fake, fake, 1, 8, 8, 1, fake, fake, fake, None, None, fake, 1 << 20, None) == E["null"]  # 1 of 3 outs
