@@ -88,7 +88,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama7b_layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-den", type=int, default=8)
+    ap.add_argument("--cpu-sample-den", type=int, default=2)
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py measures one GPU: every box of this build has one MI355X and the path has no "

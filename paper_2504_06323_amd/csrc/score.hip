@@ -16,7 +16,7 @@ namespace mp {
 namespace {
 
 constexpr int kBlock = 256;
-constexpr int kTargetBlocks = 2048;
+constexpr int kTargetBlocks = 512;  // two resident blocks per compute unit: long stripes stream best
 constexpr int kMinRowsPerBlock = 8;
 constexpr int kUnroll = 4;
 
@@ -65,8 +65,13 @@ __global__ __launch_bounds__(kBlock) void metric_scan(const T *__restrict__ w, i
     for (int e = 0; e < VEC; ++e) nrm[e] = 1.f;
     if (active && !FROM_SCORES) load_floats(norms + c0, nrm);
 
+    __shared__ float sm_tau;
     float tau = 0.f;
-    if (MODE == 1) tau = threshold_from_sum(alpha, score_sum, rows * cols);
+    if (MODE == 1) {  // one double division per block, not per thread
+        if (threadIdx.x == 0) sm_tau = threshold_from_sum(alpha, score_sum, rows * cols);
+        __syncthreads();
+        tau = sm_tau;
+    }
 
     double dsum = 0.0;
     uint32_t cnt = 0;

@@ -16,15 +16,18 @@ namespace mp {
 namespace {
 
 constexpr int kBlock = 256;
-constexpr int kTargetBlocks = 4096;  // blocks aimed for on the packet path (16 per CU)
+// One resident block per compute unit (MI355X has 256): measured fastest.  Long
+// private stripes stream at ~7.1 TB/s; more, shorter blocks lose up to 25 % to the
+// tail wave of blocks and to the extra partial rows.
+constexpr int kTargetBlocks = 256;
 constexpr int kMinRowsPerBlock = 32;
 constexpr int kMaxStripes = 4096;
 
-template <typename T, int UNROLL>
-__global__ __launch_bounds__(kBlock) void colsumsq_partial_vec(const T *__restrict__ x, int64_t n_rows,
+template <typename T, int UNROLL, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void colsumsq_partial_vec(const T *__restrict__ x, int64_t n_rows,
                                                                int64_t n_cols, int64_t ld, int64_t rows_per_block,
                                                                float *__restrict__ partials) {
-    const int64_t c0 = (static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x) * 8;
+    const int64_t c0 = (static_cast<int64_t>(blockIdx.x) * BLOCK + threadIdx.x) * 8;
     if (c0 >= n_cols) return;  // n_cols is a multiple of 8 on this path; no barriers below
     const int64_t t0 = static_cast<int64_t>(blockIdx.y) * rows_per_block;
     int64_t t1 = t0 + rows_per_block;
@@ -96,19 +99,39 @@ __global__ __launch_bounds__(kBlock) void colsumsq_partial_scalar(const T *__res
     partials[static_cast<int64_t>(blockIdx.y) * n_cols + c] = (a0 + a1) + (a2 + a3);
 }
 
-// sumsq[c] += sum over stripes of partials[s, c]; 64 channels x 4 stripe groups per block
-__global__ __launch_bounds__(kBlock) void colsumsq_reduce(const float *__restrict__ partials, int n_stripes,
-                                                          int64_t n_cols, float *__restrict__ sumsq) {
-    __shared__ double sm[4][kWave];
+// sumsq[c] += sum over stripes of partials[s, c].  A block owns 64 adjacent channels; its 16 waves
+// each add every 16th stripe (4 independent chains per thread keep loads in flight), then the 16
+// per-wave sums of a channel are added in index order.
+constexpr int kReduceBlock = 1024;
+constexpr int kReduceGroups = kReduceBlock / kWave;
+
+__global__ __launch_bounds__(kReduceBlock) void colsumsq_reduce(const float *__restrict__ partials, int n_stripes,
+                                                                int64_t n_cols, float *__restrict__ sumsq) {
+    __shared__ double sm[kReduceGroups][kWave];
     const int lane = threadIdx.x & (kWave - 1), grp = threadIdx.x / kWave;
     const int64_t c = static_cast<int64_t>(blockIdx.x) * kWave + lane;
-    double a = 0.0;
-    if (c < n_cols)
-        for (int s = grp; s < n_stripes; s += 4) a += static_cast<double>(partials[static_cast<int64_t>(s) * n_cols + c]);
-    sm[grp][lane] = a;
+    double a0 = 0.0, a1 = 0.0, a2 = 0.0, a3 = 0.0;
+    if (c < n_cols) {
+        const float *p = partials + c;
+        int s = grp;
+        for (; s + 3 * kReduceGroups < n_stripes; s += 4 * kReduceGroups) {
+            const float v0 = p[static_cast<int64_t>(s) * n_cols];
+            const float v1 = p[static_cast<int64_t>(s + kReduceGroups) * n_cols];
+            const float v2 = p[static_cast<int64_t>(s + 2 * kReduceGroups) * n_cols];
+            const float v3 = p[static_cast<int64_t>(s + 3 * kReduceGroups) * n_cols];
+            a0 += static_cast<double>(v0);
+            a1 += static_cast<double>(v1);
+            a2 += static_cast<double>(v2);
+            a3 += static_cast<double>(v3);
+        }
+        for (; s < n_stripes; s += kReduceGroups) a0 += static_cast<double>(p[static_cast<int64_t>(s) * n_cols]);
+    }
+    sm[grp][lane] = (a0 + a1) + (a2 + a3);
     __syncthreads();
     if (grp == 0 && c < n_cols) {
-        const double tot = (sm[0][lane] + sm[1][lane]) + (sm[2][lane] + sm[3][lane]);
+        double tot = 0.0;
+#pragma unroll
+        for (int g = 0; g < kReduceGroups; ++g) tot += sm[g][lane];
         sumsq[c] = static_cast<float>(static_cast<double>(sumsq[c]) + tot);
     }
 }
@@ -125,7 +148,7 @@ int launch_colsum_t(const T *x, int64_t n_rows, int64_t n_cols, int64_t ld, floa
     const ColsumPlan pl = plan_colsum(n_rows, n_cols);
     if (packet_ok(x, n_cols, ld)) {
         dim3 grid(pl.tiles_vec, pl.stripes);
-        hipLaunchKernelGGL((colsumsq_partial_vec<T, 8>), grid, dim3(kBlock), 0, stream, x, n_rows, n_cols, ld,
+        hipLaunchKernelGGL((colsumsq_partial_vec<T, 8, kBlock>), grid, dim3(kBlock), 0, stream, x, n_rows, n_cols, ld,
                            pl.rows_per_block, partials);
     } else {
         dim3 grid(pl.tiles_scalar, pl.stripes);
@@ -133,7 +156,7 @@ int launch_colsum_t(const T *x, int64_t n_rows, int64_t n_cols, int64_t ld, floa
                            pl.rows_per_block, partials);
     }
     if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
-    hipLaunchKernelGGL(colsumsq_reduce, dim3(static_cast<unsigned>(ceil_div(n_cols, kWave))), dim3(kBlock), 0,
+    hipLaunchKernelGGL(colsumsq_reduce, dim3(static_cast<unsigned>(ceil_div(n_cols, kWave))), dim3(kReduceBlock), 0,
                        stream, partials, pl.stripes, n_cols, sumsq);
     return launch_status();
 }
