@@ -14,21 +14,24 @@ namespace mp {
 namespace {
 
 template <typename T, int BLOCK, int NCHUNK, bool FROM_SCORES>
-__global__ __launch_bounds__(BLOCK) void select_rows_vec(const T *w, T *w_out, int64_t cols, int64_t ld, int64_t ld_out,
-                                                         const float *__restrict__ norms,
-                                                         const float *__restrict__ scores, uint32_t k, int idx_bits,
-                                                         uint8_t *__restrict__ mask_bytes, int64_t mask_row_bytes) {
+__global__ __launch_bounds__(BLOCK, 4) void select_rows_vec(const T *w, T *w_out, uint32_t cols, int64_t ld,
+                                                            int64_t ld_out, const float *__restrict__ norms,
+                                                            const float *__restrict__ scores, uint32_t k,
+                                                            int idx_bits, uint8_t *__restrict__ mask_bytes,
+                                                            uint32_t mask_row_bytes) {
     __shared__ SelectSmem<BLOCK> sm;
     const int64_t row = blockIdx.x;
-    const int tid = threadIdx.x;
+    const uint32_t tid = threadIdx.x;
+    const T *wrow = w + row * ld;  // uniform row bases; per-lane offsets stay 32-bit
+    T *orow = w_out + row * ld_out;
 
     Packet<T, 8> pk[NCHUNK];
     uint32_t key[NCHUNK][8];
 #pragma unroll
     for (int c = 0; c < NCHUNK; ++c) {
-        const int64_t col0 = (static_cast<int64_t>(c) * BLOCK + tid) * 8;
+        const uint32_t col0 = (c * BLOCK + tid) * 8;
         if (col0 < cols) {
-            pk[c].load(w + row * ld + col0);
+            pk[c].load(wrow + col0);
             float om[8];
             if (FROM_SCORES) {
                 load_floats(scores + row * cols + col0, om);
@@ -44,37 +47,42 @@ __global__ __launch_bounds__(BLOCK) void select_rows_vec(const T *w, T *w_out, i
         }
     }
 
-    uint64_t bound = ~uint64_t(0);  // k == cols: everything goes
+    SelectBound bound = {0xffffffffu, 0xffffffffu};  // k == cols: everything goes
     if (k < cols) {
         bound = block_select_bound<BLOCK>(
-            [&](auto f) {
+            [&](auto f, uint32_t salt) {
 #pragma unroll
                 for (int c = 0; c < NCHUNK; ++c) {
-                    const int64_t col0 = (static_cast<int64_t>(c) * BLOCK + tid) * 8;
+                    const uint32_t col0 = (c * BLOCK + tid + salt) * 8;
                     if (col0 < cols) {
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) f(key[c][e], static_cast<uint32_t>(col0 + e));
+                        for (int e = 0; e < 8; ++e) f(key[c][e], col0 + e);
                     }
                 }
             },
             k, idx_bits, sm);
     }
 
+    const bool whole_bins = bound.idx == 0xffffffffu;  // uniform: no tie to split by column
 #pragma unroll
     for (int c = 0; c < NCHUNK; ++c) {
-        const int64_t col0 = (static_cast<int64_t>(c) * BLOCK + tid) * 8;
+        const uint32_t col0 = (c * BLOCK + tid) * 8;
         if (col0 < cols) {
             uint32_t keep = 0;
+            if (whole_bins) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                keep |= (composite(key[c][e], static_cast<uint32_t>(col0 + e), idx_bits) > bound ? 1u : 0u) << e;
+                for (int e = 0; e < 8; ++e) keep |= (key[c][e] > bound.key ? 1u : 0u) << e;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) keep |= (is_selected(key[c][e], col0 + e, bound) ? 0u : 1u) << e;
+            }
             pk[c].apply_keep(keep);
-            pk[c].store(w_out + row * ld_out + col0);
+            pk[c].store(orow + col0);
             if (mask_bytes) {
                 uint8_t *mrow = mask_bytes + row * mask_row_bytes;
                 mrow[col0 >> 3] = static_cast<uint8_t>(keep);
                 if (col0 + 8 == cols)  // owner of the last packet clears the padding of the last word
-                    for (int64_t b = (cols >> 3); b < mask_row_bytes; ++b) mrow[b] = 0;
+                    for (uint32_t b = (cols >> 3); b < mask_row_bytes; ++b) mrow[b] = 0;
             }
         }
     }
@@ -95,10 +103,10 @@ __global__ __launch_bounds__(BLOCK) void select_rows_generic(const T *w, T *w_ou
         const float om = FROM_SCORES ? scores[row * cols + j] : metric(widen(wr[j]), norms[j]);
         return key_of(om);
     };
-    uint64_t bound = ~uint64_t(0);
+    SelectBound bound = {0xffffffffu, 0xffffffffu};
     if (k < cols) {
         bound = block_select_bound<BLOCK>(
-            [&](auto f) {
+            [&](auto f, uint32_t) {
                 for (int64_t j = tid; j < cols; j += BLOCK) f(key_at(j), static_cast<uint32_t>(j));
             },
             k, idx_bits, sm);
@@ -109,7 +117,7 @@ __global__ __launch_bounds__(BLOCK) void select_rows_generic(const T *w, T *w_ou
         for (int b = 0; b < 32; ++b) {
             const int64_t j = q * 32 + b;
             if (j < cols) {
-                const bool keep = composite(key_at(j), static_cast<uint32_t>(j), idx_bits) > bound;
+                const bool keep = !is_selected(key_at(j), static_cast<uint32_t>(j), bound);
                 const T v = wr[j];
                 orow[j] = keep ? v : T(0);
                 word |= (keep ? 1u : 0u) << b;
@@ -159,17 +167,24 @@ int launch_select(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld, 
     const int64_t mrb = words * 4;
 #define MP_SELECT_CASE(BLOCK, NCHUNK)                                                                              \
     hipLaunchKernelGGL((select_rows_vec<T, BLOCK, NCHUNK, FROM_SCORES>), grid, dim3(BLOCK), 0, stream, w, w_out,   \
-                       cols, ld, ld_out, norms, scores, k, idx_bits, mb, mrb)
-    if (cols <= 512) MP_SELECT_CASE(64, 1);
-    else if (cols <= 1024) MP_SELECT_CASE(64, 2);
-    else if (cols <= 2048) MP_SELECT_CASE(256, 1);
-    else if (cols <= 4096) MP_SELECT_CASE(256, 2);
-    else if (cols <= 6144) MP_SELECT_CASE(256, 3);
-    else if (cols <= 8192) MP_SELECT_CASE(256, 4);
-    else if (cols <= 10240) MP_SELECT_CASE(256, 5);
-    else if (cols <= 12288) MP_SELECT_CASE(256, 6);
-    else if (cols <= 14336) MP_SELECT_CASE(256, 7);
-    else MP_SELECT_CASE(256, 8);
+                       static_cast<uint32_t>(cols), ld, ld_out, norms, scores, k, idx_bits, mb,                   \
+                       static_cast<uint32_t>(mrb))
+    const int64_t packets = cols / 8;
+    // waves per row grow with the row width so that a thread holds at most 4 packets (32 keys)
+    const int block = packets <= 128 ? 64 : packets <= 256 ? 128 : packets <= 1024 ? 256 : 512;
+    const int nchunk = static_cast<int>(ceil_div(packets, block));
+#define MP_SELECT_BLOCK(BLOCK)                   \
+    switch (nchunk) {                            \
+        case 1: MP_SELECT_CASE(BLOCK, 1); break; \
+        case 2: MP_SELECT_CASE(BLOCK, 2); break; \
+        case 3: MP_SELECT_CASE(BLOCK, 3); break; \
+        default: MP_SELECT_CASE(BLOCK, 4); break; \
+    }
+    if (block == 64) { MP_SELECT_BLOCK(64) }
+    else if (block == 128) { MP_SELECT_BLOCK(128) }
+    else if (block == 256) { MP_SELECT_BLOCK(256) }
+    else { MP_SELECT_BLOCK(512) }
+#undef MP_SELECT_BLOCK
 #undef MP_SELECT_CASE
     return launch_status();
 }

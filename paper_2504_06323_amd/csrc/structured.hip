@@ -53,10 +53,10 @@ __global__ __launch_bounds__(kRankBlock) void rank_channels(const float *__restr
     __shared__ uint32_t wave_cnt[kRankBlock / kWave];
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     bool have_bound = false;
-    uint64_t bound = 0;
+    SelectBound bound = {0u, 0u};
     if (r > 0) {
         bound = block_select_bound<kRankBlock>(
-            [&](auto f) {
+            [&](auto f, uint32_t) {
                 for (int64_t c = tid; c < inter; c += kRankBlock) f(key_of(g[c]), static_cast<uint32_t>(c));
             },
             r, idx_bits, sm);
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(kRankBlock) void rank_channels(const float *__restr
     for (int64_t c0 = 0; c0 < inter; c0 += kRankBlock) {
         const int64_t c = c0 + tid;
         bool keep = false;
-        if (c < inter) keep = !have_bound || composite(key_of(g[c]), static_cast<uint32_t>(c), idx_bits) > bound;
+        if (c < inter) keep = !have_bound || !is_selected(key_of(g[c]), static_cast<uint32_t>(c), bound);
         const unsigned long long ballot = __ballot(keep);
         const uint32_t before_in_wave = __popcll(ballot & ((1ull << lane) - 1ull));
         if (lane == 0) wave_cnt[wv] = __popcll(ballot);
