@@ -44,6 +44,19 @@ def algorithmic_bytes(cfg, shapes, act_shapes, r):
                 total=stats + score + count + select + struct_rank + compact)
 
 
+def measured_traffic(workload):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, or None."""
+    path = os.path.join(ROOT, "profiles", f"stats_{workload}_hbm_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return int(float(line.split(":", 1)[1]))
+    except OSError:
+        pass
+    return None
+
+
 def cpu_baseline(cfg, shapes, weights, acts, frac_den=8):
     """Time the CPU oracle, as it stands, on a 1/frac_den sample of the same layer."""
     import numpy as np
@@ -89,6 +102,9 @@ def main():
     ap.add_argument("--workload", default="llama7b_layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-den", type=int, default=2)
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="before the warm-up, run a plain float32 copy kernel (read N MiB, write N MiB) three "
+                         "times so that a rocprofv3 --pmc run of this command carries a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py measures one GPU: every box of this build has one MI355X and the path has no "
@@ -162,6 +178,14 @@ def main():
             pass_events.append(marks)
         return counts, ks
 
+    if args.calibration_copy_mib > 0:
+        src = torch.ones(args.calibration_copy_mib * (1 << 20) // 4, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step(False)
     torch.cuda.synchronize()
@@ -180,7 +204,7 @@ def main():
     achieved = avg_bytes / (avg_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "colsumsq_partial_vec (activation statistics)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(cfg.name),
                 "avg_launch_ms": round(avg_ms, 4), "avg_launch_bytes": int(avg_bytes),
                 "launches": len(stats_ms)}
 

@@ -1,0 +1,199 @@
+"""Full-size parity: the workloads of the benchmark and of the larger configurations, in the launch
+configuration bench.py times (hot mode: no materialised scores, shared workspace, out-of-place masking).
+
+At these sizes the float64 oracle is applied to sampled outputs (channels of the activation
+statistics, rows of the masks) and in full where NumPy finishes in seconds (metric sums, outlier
+counts, group magnitudes, gathers); integer results are compared bit-exactly in the kernel's
+precision as in test_gpu_parity.py, and properties that hold at any size (exactly k pruned per row,
+survivors untouched, keep-bits consistent with the zeros) are checked over every row.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mosaic_oracle as orc
+from paper_2504_06323_amd import pipeline, prune, synth
+from util import rel_err, to_np
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda"
+
+
+def _sample(n, count, seed):
+    rng = np.random.default_rng(seed)
+    idx = set(rng.choice(n, size=min(count, n), replace=False).tolist()) | {0, n - 1}
+    return np.array(sorted(idx))
+
+
+def _metric_f32(w_np, norms_np):
+    """Kernel-precision metric on the host: one float32 multiply per element."""
+    return np.abs(w_np.astype(np.float32)) * norms_np.astype(np.float32)[None, :]
+
+
+def _popcount32(a):
+    a = a.astype(np.uint32)
+    a = a - ((a >> 1) & 0x55555555)
+    a = (a & 0x33333333) + ((a >> 2) & 0x33333333)
+    a = (a + (a >> 4)) & 0x0F0F0F0F
+    return (a * 0x01010101 >> 24) & 0xFF
+
+
+def _check_norms(x, norms_gpu, seed):
+    """Sampled channels (plus the largest-norm ones, i.e. the planted outliers) against the oracle."""
+    c = x.shape[1]
+    idx = np.union1d(_sample(c, 24, seed), np.argsort(to_np(norms_gpu))[-4:])
+    cols = to_np(x[:, torch.as_tensor(idx, device=x.device)])
+    want = orc.column_norms(cols)
+    got = to_np(norms_gpu)[idx]
+    assert rel_err(got, want) < 1e-2            # the stated bf16 tolerance
+    assert rel_err(got, want) < 5e-6            # what fp32 stripes + fp64 cross-stripe sums deliver
+
+
+def _check_rank(w, norms, alpha, ssum, count, tau):
+    w_np, n_np = to_np(w), to_np(norms)
+    m32 = _metric_f32(w_np, n_np)
+    assert tau == orc.threshold_f32(alpha, ssum, w_np.size)
+    assert count == orc.count_above(m32, tau)                         # bit-exact in the kernel's precision
+    omega = orc.weight_metric(w_np, n_np.astype(np.float64))          # float64 oracle on the same norms
+    c, o, ratio, mean = orc.outlier_stats(omega, alpha)
+    assert abs(ssum - omega.sum()) <= 1e-6 * omega.sum()
+    band = np.count_nonzero(np.abs(omega - alpha * mean) <= 1e-5 * alpha * mean)
+    assert abs(count - o) <= band
+    return m32
+
+
+def _check_mask(w, m32, k, w_out, mask_bits, seed, n_rows=12):
+    w_np, out, bits = to_np(w), to_np(w_out), to_np(mask_bits).view(np.uint32)
+    rows, cols = w_np.shape
+    # every row: exactly k pruned, keep-bits consistent, survivors bit-identical, pruned entries zero
+    assert (_popcount32(bits).sum(axis=1) == cols - k).all()
+    keep = ((bits[:, :, None] >> np.arange(32, dtype=np.uint32)) & 1).reshape(rows, -1)[:, :cols].astype(bool)
+    assert np.array_equal(out.view(np.uint32)[keep], w_np.view(np.uint32)[keep])
+    assert (out[~keep] == 0).all()
+    # pruned metrics never exceed kept metrics (row by row)
+    hi_pruned = np.where(keep, -np.inf, m32).max(axis=1)
+    lo_kept = np.where(keep, m32, np.inf).min(axis=1)
+    assert (hi_pruned <= lo_kept).all()
+    # sampled rows: the oracle's stable-sort selection on the kernel's metric bits
+    idx = _sample(rows, n_rows, seed)
+    pruned = orc.select_smallest_per_row(m32[idx], k)
+    assert np.array_equal(~keep[idx], pruned)
+    assert np.array_equal(out[idx], orc.apply_mask(w_np[idx], pruned))
+
+
+def _run_layer(cfg_name, check_struct=True):
+    cfg = synth.CONFIGS[cfg_name]
+    shapes = synth.projection_shapes(cfg)
+    act_shapes = synth.activation_shapes(cfg)
+    print(f"[fullsize] {cfg_name}: generating inputs", flush=True)
+    weights = {n: synth.make_weight(cfg, 0, n, DEV) for n, _, _, _ in shapes}
+    acts = {a: synth.make_activation(cfg, 0, a, DEV) for a in act_shapes}
+    st = pipeline.LayerState.create(weights, {n: a for n, _, _, a in shapes}, act_shapes, cfg.n_tokens)
+    print(f"[fullsize] {cfg_name}: phase 1", flush=True)
+    pipeline.rank_layer(st, acts, cfg.alpha)
+    torch.cuda.synchronize()
+    for i, a in enumerate(act_shapes):
+        _check_norms(acts[a], st.norms[a], seed=100 + i)
+    del acts
+    torch.cuda.empty_cache()
+    counts, ssums, taus = st.count.tolist(), st.score_sum.tolist(), to_np(st.tau)
+    metrics = {}
+    for i, (n, r, c, a) in enumerate(shapes):
+        metrics[n] = _check_rank(weights[n], st.norms[a], cfg.alpha, ssums[i], counts[i], taus[i])
+    numels, cols = [r * c for _, r, c, _ in shapes], [c for _, _, c, _ in shapes]
+    s, ks, clamped = pipeline.plan(counts, numels, cols, 1, len(shapes), cfg.p, cfg.lam)
+    ratios = 100.0 * np.array(counts) / np.array(numels)
+    want_s, _ = orc.plan_sparsity(ratios.reshape(1, -1), cfg.p, cfg.lam, "global", cols=np.array(cols).reshape(1, -1))
+    assert np.allclose(s, want_s.reshape(-1), atol=1e-13) and not clamped
+    assert ks == [orc.zeros_per_row(v, c) for v, c in zip(s, cols)]
+    assert abs(np.mean(s) - cfg.p) < 1e-12
+    print(f"[fullsize] {cfg_name}: phase 2, zeros per row {ks}", flush=True)
+    pipeline.prune_layer(st, ks)
+    torch.cuda.synchronize()
+    for i, (n, r, c, a) in enumerate(shapes):
+        _check_mask(weights[n], metrics[n], ks[i], st.pruned[n], st.mask_bits[n], seed=200 + i)
+    del metrics
+    if not check_struct:
+        return
+    r = int(cfg.struct_frac * cfg.inter)
+    print(f"[fullsize] {cfg_name}: structured removal of {r} channels", flush=True)
+    res = pipeline.alloc_struct(st, r)
+    pipeline.struct_layer(st, r, res)
+    torch.cuda.synchronize()
+    masked = {n: to_np(st.pruned[n]) for n in ("gate", "up", "down")}
+    want_g = orc.group_magnitude(masked["gate"], masked["up"], masked["down"])
+    assert rel_err(to_np(res.group_mag), want_g) < 1e-2 and rel_err(to_np(res.group_mag), want_g) < 5e-6
+    kept = orc.struct_rank(to_np(res.group_mag), r)
+    assert np.array_equal(to_np(res.kept_idx), kept)
+    assert len(kept) == cfg.inter - r
+    wg, wu, wd = orc.struct_compact(masked["gate"], masked["up"], masked["down"], kept)
+    assert np.array_equal(to_np(res.gate), wg) and np.array_equal(to_np(res.up), wu)
+    assert np.array_equal(to_np(res.down), wd)
+
+
+def test_llama7b_layer_bench_configuration(lib):
+    """configs[1], exactly what bench.py runs."""
+    _run_layer("llama7b_layer")
+
+
+def test_llama3_8b_layer_gqa_composite(lib):
+    """configs[2]: grouped-query shapes (k/v 1024 x 4096), 14336-wide MLP, 50 % unstructured + 20 % structured."""
+    _run_layer("llama3_8b_layer")
+
+
+@pytest.mark.timeout(600)
+def test_llama2_13b_stress_layer(lib):
+    """configs[4], one layer: 256 x 4096 calibration tokens, x100 outlier channels, 60 % + 30 %."""
+    _run_layer("llama2_13b_stress")
+
+
+@pytest.mark.timeout(900)
+def test_full_model_llama3_8b_sweep(lib):
+    """configs[3]: 32 layers, 224 projections ranked once, pruned at 30 / 50 / 70 % reusing the ranking."""
+    cfg = synth.CONFIGS["llama3_8b_full"]
+    shapes = synth.projection_shapes(cfg)
+    act_shapes = synth.activation_shapes(cfg)
+    proj_inputs = {n: a for n, _, _, a in shapes}
+    n_proj = len(shapes)
+    checked_layers = (0, 31)
+    states, counts, metrics = [], [], {}
+    for layer in range(cfg.n_layers):
+        if layer % 8 == 0:
+            print(f"[fullsize] full model: ranking layer {layer}", flush=True)
+        weights = {n: synth.make_weight(cfg, layer, n, DEV) for n, _, _, _ in shapes}
+        acts = {a: synth.make_activation(cfg, layer, a, DEV) for a in act_shapes}
+        st = pipeline.LayerState.create(weights, proj_inputs, act_shapes, cfg.n_tokens,
+                                        want_mask_bits=layer in checked_layers)
+        if states:                       # one masked copy and one workspace serve every layer
+            st.pruned, st.ws = states[0].pruned, states[0].ws
+        pipeline.rank_layer(st, acts, cfg.alpha)
+        torch.cuda.synchronize()
+        if layer in checked_layers:
+            for i, a in enumerate(act_shapes):
+                _check_norms(acts[a], st.norms[a], seed=1000 * layer + i)
+            ssums, taus, cnts = st.score_sum.tolist(), to_np(st.tau), st.count.tolist()
+            for i, (n, r, c, a) in enumerate(shapes):
+                metrics[(layer, n)] = _check_rank(weights[n], st.norms[a], cfg.alpha, ssums[i], cnts[i], taus[i])
+        del acts
+        states.append(st)
+        counts += st.count.tolist()
+    assert len(counts) == 224
+    numels = [r * c for _, r, c, _ in shapes] * cfg.n_layers
+    cols = [c for _, _, c, _ in shapes] * cfg.n_layers
+    ratios = (100.0 * np.array(counts) / np.array(numels)).reshape(cfg.n_layers, n_proj)
+    assert ratios.std() > 0                                   # layers differ, so the targets are non-uniform
+    for p in cfg.p_sweep:
+        s, ks, clamped = pipeline.plan(counts, numels, cols, cfg.n_layers, n_proj, p, cfg.lam)
+        want_s, _ = orc.plan_sparsity(ratios, p, cfg.lam, "global", cols=np.array(cols).reshape(cfg.n_layers, n_proj))
+        assert np.allclose(np.array(s).reshape(cfg.n_layers, n_proj), want_s, atol=1e-13) and not clamped
+        assert abs(np.mean(s) - p) < 1e-12 and max(s) - min(s) == pytest.approx(2 * cfg.lam, rel=1e-9)
+        print(f"[fullsize] full model: pruning at p = {p}", flush=True)
+        for layer, st in enumerate(states):
+            lk = ks[layer * n_proj:(layer + 1) * n_proj]
+            pipeline.prune_layer(st, lk)                      # phase 2 only: the ranking is reused
+            if layer in checked_layers:
+                torch.cuda.synchronize()
+                for i, (n, r, c, a) in enumerate(shapes):
+                    _check_mask(st.weights[n], metrics[(layer, n)], lk[i], st.pruned[n], st.mask_bits[n],
+                                seed=layer * 10 + i, n_rows=6)
+        torch.cuda.synchronize()
