@@ -134,14 +134,17 @@ __device__ __forceinline__ float wave_sum(float v) {
     return v;
 }
 
-// inclusive prefix sum across the 64 lanes of a wave
+// inclusive prefix sum across the 64 lanes of a wave, in registers (data-parallel primitives, no LDS):
+// a Hillis-Steele scan inside every row of 16 lanes, then the row totals are carried forward.
 __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t v) {
-    const int lane = threadIdx.x & (kWave - 1);
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-        uint32_t n = __shfl_up(v, off, kWave);
-        if (lane >= off) v += n;
-    }
+    // update_dpp(old, src, ctrl, row_mask, bank_mask, bound_ctrl): lanes without a valid source, and
+    // lanes of rows that row_mask switches off, receive `old` (zero here)
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x111, 0xf, 0xf, false);  // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x112, 0xf, 0xf, false);  // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x114, 0xf, 0xf, false);  // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x118, 0xf, 0xf, false);  // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0u, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2 and 3
     return v;
 }
 

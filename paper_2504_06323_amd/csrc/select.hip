@@ -49,6 +49,8 @@ __global__ __launch_bounds__(BLOCK, 4) void select_rows_vec(const T *w, T *w_out
 
     SelectBound bound = {0xffffffffu, 0xffffffffu};  // k == cols: everything goes
     if (k < cols) {
+        for (int b = tid; b < kSelBins; b += BLOCK) sm.hist[b] = 0u;
+        __syncthreads();
         bound = block_select_bound<BLOCK>(
             [&](auto f, uint32_t salt) {
 #pragma unroll
@@ -105,6 +107,8 @@ __global__ __launch_bounds__(BLOCK) void select_rows_generic(const T *w, T *w_ou
     };
     SelectBound bound = {0xffffffffu, 0xffffffffu};
     if (k < cols) {
+        for (int b = tid; b < kSelBins; b += BLOCK) sm.hist[b] = 0u;
+        __syncthreads();
         bound = block_select_bound<BLOCK>(
             [&](auto f, uint32_t) {
                 for (int64_t j = tid; j < cols; j += BLOCK) f(key_at(j), static_cast<uint32_t>(j));

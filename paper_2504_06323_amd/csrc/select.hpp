@@ -4,9 +4,9 @@
 // float orders like the float) and a unique index.  Items are ordered by key,
 // then by index, so the k smallest are unique even when keys repeat.  A
 // most-significant-digit-first radix search with an LDS histogram walks the key
-// in digits of 11, 11 and 9 bits; it stops as soon as the bin that holds the
+// in digits of 11, 8, 8 and 4 bits; it stops as soon as the bin that holds the
 // k-th item is needed in full, which for real-valued data is usually after two
-// digits.  Only when the k-th key itself has duplicates that must be split does
+// or three digits.  Only when the k-th key itself has duplicates that must be split does
 // the search continue over the index bits of the items carrying that key.
 // Everything is 32-bit arithmetic; a one-wave block needs no hardware barrier.
 #pragma once
@@ -16,7 +16,6 @@
 namespace mp {
 
 constexpr int kSelBins = 2048;
-constexpr int kSelDigit = 11;
 
 template <int BLOCK>
 struct SelectSmem {
@@ -44,25 +43,29 @@ inline int index_bits_for(int64_t n) {  // bits needed for indices 0 .. n-1 (at 
     return b;
 }
 
-// The histogram is complete and visible.  Finds the bin holding the `need`-th item (1-based,
-// counted from bin 0), returns how many items lie in lower bins and how many in that bin, and
-// leaves the histogram zeroed for the next digit.
-template <int BLOCK>
+// The histogram over bins [0, BINS) is complete and visible.  Finds the bin holding the `need`-th item
+// (1-based, counted from bin 0), returns how many items lie in lower bins and how many in that bin,
+// and leaves those bins zeroed for the next digit.
+template <int BLOCK, int BINS>
 __device__ __forceinline__ void locate_bin(SelectSmem<BLOCK> &sm, uint32_t need, uint32_t &bin, uint32_t &before,
                                            uint32_t &count) {
-    constexpr int BPT = kSelBins / BLOCK;  // bins owned by a thread
-    static_assert(BPT % 4 == 0 || BPT == 2, "bins per thread");
+    constexpr int BPT = BINS >= BLOCK ? BINS / BLOCK : 1;  // bins owned by a thread
+    static_assert(BPT < 4 || BPT % 4 == 0, "bins per thread");
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const bool owner = BINS >= BLOCK || tid < BINS;
     uint32_t *mine = &sm.hist[tid * BPT];
     uint32_t s = 0;
-    if constexpr (BPT >= 4) {
+    if (owner) {
+        if constexpr (BPT >= 4) {
 #pragma unroll
-        for (int i = 0; i < BPT; i += 4) {
-            const u32x4 v = *reinterpret_cast<const u32x4 *>(mine + i);
-            s += (v[0] + v[1]) + (v[2] + v[3]);
+            for (int i = 0; i < BPT; i += 4) {
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(mine + i);
+                s += (v[0] + v[1]) + (v[2] + v[3]);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < BPT; ++i) s += mine[i];
         }
-    } else {
-        s = mine[0] + mine[1];
     }
     const uint32_t incl = wave_inclusive_scan(s);
     uint32_t excl = incl - s;
@@ -84,13 +87,15 @@ __device__ __forceinline__ void locate_bin(SelectSmem<BLOCK> &sm, uint32_t need,
             run += h;
         }
     }
-    if constexpr (BPT >= 4) {
-        const u32x4 z = {0u, 0u, 0u, 0u};
+    if (owner) {
+        if constexpr (BPT >= 4) {
+            const u32x4 z = {0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int i = 0; i < BPT; i += 4) *reinterpret_cast<u32x4 *>(mine + i) = z;
-    } else {
-        mine[0] = 0u;
-        mine[1] = 0u;
+            for (int i = 0; i < BPT; i += 4) *reinterpret_cast<u32x4 *>(mine + i) = z;
+        } else {
+#pragma unroll
+            for (int i = 0; i < BPT; ++i) mine[i] = 0u;
+        }
     }
     __syncthreads();
     bin = sm.sel_bin;
@@ -104,45 +109,45 @@ __device__ __forceinline__ void locate_bin(SelectSmem<BLOCK> &sm, uint32_t need,
 // its indices from (thread id + salt) keeps them from being hoisted out of that loop into
 // registers that the common path would then have to carry.
 // 1 <= k <= number of items.  All threads of the block call this; all get the same bound.
+// The histogram must be all zero (and visible to the block) on entry; it is all zero again on return.
+//
+// Digits: key bits 30..20 first (2048 bins: the exponent and three mantissa bits, which is where
+// the values of a row spread), then 8 bits at a time (256 bins: few candidates are left, so the
+// per-digit cost is what matters), the last key digit being 4 bits.
 template <int BLOCK, class ForEach>
 __device__ SelectBound block_select_bound(ForEach for_each, uint32_t k, int idx_bits, SelectSmem<BLOCK> &sm) {
-    for (int b = threadIdx.x; b < kSelBins; b += BLOCK) sm.hist[b] = 0u;
-    __syncthreads();
     uint32_t need = k, bin, before, count;
 
-    // key bits 30..20
     for_each([&](uint32_t key, uint32_t) { atomicAdd(&sm.hist[key >> 20], 1u); }, 0u);
     __syncthreads();
-    locate_bin<BLOCK>(sm, need, bin, before, count);
+    locate_bin<BLOCK, kSelBins>(sm, need, bin, before, count);
     need -= before;
-    uint32_t prefix = bin;
+    uint32_t prefix = bin;  // key bits above `pos`
     if (need == count) return {(prefix << 20) | 0xfffffu, 0xffffffffu};
 
-    // key bits 19..9
-    for_each([&](uint32_t key, uint32_t) {
-        if ((key >> 20) == prefix) atomicAdd(&sm.hist[(key >> 9) & 0x7ffu], 1u);
-    }, 0u);
-    __syncthreads();
-    locate_bin<BLOCK>(sm, need, bin, before, count);
-    need -= before;
-    prefix = (prefix << 11) | bin;
-    if (need == count) return {(prefix << 9) | 0x1ffu, 0xffffffffu};
-
-    // key bits 8..0
-    for_each([&](uint32_t key, uint32_t) {
-        if ((key >> 9) == prefix) atomicAdd(&sm.hist[key & 0x1ffu], 1u);
-    }, 0u);
-    __syncthreads();
-    locate_bin<BLOCK>(sm, need, bin, before, count);
-    need -= before;
-    const uint32_t v = (prefix << 9) | bin;
-    if (need == count) return {v, 0xffffffffu};
+    int pos = 20;
+#pragma unroll 1
+    while (pos > 0) {
+        const int width = pos >= 8 ? 8 : pos;  // 8, 8, 4
+        const int shift = pos - width;
+        const uint32_t dmask = (1u << width) - 1u;
+        for_each([&](uint32_t key, uint32_t) {
+            if ((key >> pos) == prefix) atomicAdd(&sm.hist[(key >> shift) & dmask], 1u);
+        }, 0u);
+        __syncthreads();
+        locate_bin<BLOCK, 256>(sm, need, bin, before, count);
+        need -= before;
+        prefix = (prefix << width) | bin;
+        pos = shift;
+        if (need == count) return {pos ? (((prefix + 1u) << pos) - 1u) : prefix, 0xffffffffu};
+    }
+    const uint32_t v = prefix;
 
     // the k-th key is v and only some of its copies are selected: lowest indices first
-    int pos = idx_bits;  // index bits [pos, idx_bits) are fixed to ipre
+    pos = idx_bits;  // index bits [pos, idx_bits) are fixed to ipre
     uint32_t ipre = 0;
     for (;;) {
-        const int width = pos < kSelDigit ? pos : kSelDigit;
+        const int width = pos < 8 ? pos : 8;
         const int shift = pos - width;
         const uint32_t dmask = (1u << width) - 1u;
         uint32_t salt = 0u, vv = v;
@@ -152,7 +157,7 @@ __device__ SelectBound block_select_bound(ForEach for_each, uint32_t k, int idx_
             if (key == vv && hi == ipre) atomicAdd(&sm.hist[(idx >> shift) & dmask], 1u);
         }, salt);
         __syncthreads();
-        locate_bin<BLOCK>(sm, need, bin, before, count);
+        locate_bin<BLOCK, 256>(sm, need, bin, before, count);
         need -= before;
         ipre = (ipre << width) | bin;
         pos = shift;

@@ -55,6 +55,8 @@ __global__ __launch_bounds__(kRankBlock) void rank_channels(const float *__restr
     bool have_bound = false;
     SelectBound bound = {0u, 0u};
     if (r > 0) {
+        for (int b = tid; b < kSelBins; b += kRankBlock) sm.hist[b] = 0u;
+        __syncthreads();
         bound = block_select_bound<kRankBlock>(
             [&](auto f, uint32_t) {
                 for (int64_t c = tid; c < inter; c += kRankBlock) f(key_of(g[c]), static_cast<uint32_t>(c));
