@@ -160,10 +160,9 @@ def main():
             prune.stats_finalize(st.sumsq[a], st.norms[a])
         if record:
             marks[1].record()
-        for i, name in enumerate(st.names):
-            w, nrm = st.weights[name], st.norms[st.proj_inputs[name]]
-            prune.score(w, nrm, st.score_sum[i:i + 1], ws=st.ws)
-            prune.outlier_ratio(w, nrm, cfg.alpha, st.score_sum[i:i + 1], st.count[i:i + 1], tau=st.tau[i:i + 1])
+        prune.score_outlier_batch([st.weights[n] for n in st.names],
+                                  [st.norms[st.proj_inputs[n]] for n in st.names], cfg.alpha, st.score_sum,
+                                  st.count, taus=st.tau, ws=st.ws)
         if record:
             marks[2].record()
         counts = st.count.tolist()          # 7 integers cross to the host: the planner needs every ratio

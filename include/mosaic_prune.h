@@ -57,10 +57,19 @@ typedef enum {
     PRUNE_OP_SCORE = 1,   /* rows, cols of W */
     PRUNE_OP_OUTLIER = 2, /* needs no workspace (returns 0) */
     PRUNE_OP_SELECT = 3,  /* rows, cols of W */
-    PRUNE_OP_STRUCT = 4   /* rows = inter, cols = hidden */
+    PRUNE_OP_STRUCT = 4,  /* rows = inter, cols = hidden */
+    PRUNE_OP_BATCH = 5    /* prune_score_outlier_batch: rows, cols of the largest projection of the batch */
 } prune_op;
 
 typedef enum { PRUNE_SCOPE_GLOBAL = 0, PRUNE_SCOPE_CATEGORY = 1 } prune_scope;
+
+/* One projection of a batch: weight [rows, cols] (device, pitch ld_w) and the norms [cols] (device)
+ * of the activation it multiplies. */
+typedef struct {
+    const void *w;
+    int64_t rows, cols, ld_w;
+    const float *norms;
+} prune_projection;
 
 /* host, pure.  Library version as major * 10000 + minor * 100 + patch. */
 int prune_version(void);
@@ -114,6 +123,25 @@ int prune_score(const void *w, int dtype, int64_t rows, int64_t cols, int64_t ld
 int prune_outlier_ratio(const void *w, int dtype, int64_t rows, int64_t cols, int64_t ld_w,
                         const float *norms, const float *scores, float alpha, const double *score_sum,
                         unsigned long long *count, float *tau, void *stream);
+
+/*
+ * Weight metric and projection outliers of several projections at once (the
+ * loop over the projections of a layer in Algorithm 1; Eq. 5 and Eq. 6 for
+ * each): three launches for the whole batch instead of four per projection.
+ * For every i < n_proj
+ *   score_sums[i], taus[i], counts[i]
+ * are what prune_score (without materialised scores) followed by
+ * prune_outlier_ratio compute for projs[i]; the sums are accumulated in a
+ * different fixed order, so they may differ from the single calls in the last
+ * bits, and counts are exact for the threshold taus[i] that is reported.
+ * projs is a HOST array (read during the call); score_sums, counts, taus
+ * (optional) are device arrays of n_proj entries.  All projections share dtype.
+ * ws_bytes >= prune_workspace_bytes(PRUNE_OP_BATCH, rows, cols) of the largest
+ * projection.  Projections that cannot use 128-bit accesses make the call run
+ * the single-projection kernels one after the other, with the same results.
+ */
+int prune_score_outlier_batch(const prune_projection *projs, int n_proj, int dtype, float alpha, double *score_sums,
+                              unsigned long long *counts, float *taus, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * host only, touches no device (Algorithm 1's normalize(R_LLM) and the

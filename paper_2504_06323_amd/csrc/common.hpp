@@ -196,5 +196,6 @@ int launch_colsum(const void *x, int dtype, int64_t n_rows, int64_t n_cols, int6
 size_t score_workspace_bytes(int64_t rows, int64_t cols);
 size_t select_workspace_bytes(int64_t rows, int64_t cols);
 size_t struct_workspace_bytes(int64_t inter, int64_t hidden);
+size_t rank_batch_workspace_bytes();
 
 }  // namespace mp

@@ -14,6 +14,7 @@ size_t colsum_workspace_bytes(int64_t n_rows, int64_t n_cols);
 size_t score_workspace_bytes(int64_t rows, int64_t cols);
 size_t select_workspace_bytes(int64_t rows, int64_t cols);
 size_t struct_workspace_bytes(int64_t inter, int64_t hidden);
+size_t rank_batch_workspace_bytes();
 }  // namespace mp
 
 extern "C" int prune_version(void) { return 100; }
@@ -41,6 +42,10 @@ extern "C" size_t prune_workspace_bytes(int op, int64_t rows, int64_t cols) {
         case PRUNE_OP_OUTLIER: return 0;
         case PRUNE_OP_SELECT: n = mp::select_workspace_bytes(rows, cols); break;
         case PRUNE_OP_STRUCT: n = mp::struct_workspace_bytes(rows, cols); break;
+        case PRUNE_OP_BATCH:
+            n = mp::score_workspace_bytes(rows, cols);
+            if (n < mp::rank_batch_workspace_bytes()) n = mp::rank_batch_workspace_bytes();
+            break;
         default: return 0;
     }
     return (n + 255) / 256 * 256;

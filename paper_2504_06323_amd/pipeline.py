@@ -56,7 +56,8 @@ class LayerState:
         for a, ch in act_channels.items():
             need = max(need, prune.workspace_bytes(prune.OP_STATS, max(act_tokens, 1), ch))
         for name, w in weights.items():
-            need = max(need, prune.workspace_bytes(prune.OP_SCORE, w.shape[0], w.shape[1]))
+            need = max(need, prune.workspace_bytes(prune.OP_SCORE, w.shape[0], w.shape[1]),
+                       prune.workspace_bytes(prune.OP_BATCH, w.shape[0], w.shape[1]))
             st.pruned[name] = torch.empty_like(w)
             if want_mask_bits:
                 st.mask_bits[name] = torch.empty((w.shape[0], (w.shape[1] + 31) // 32), dtype=torch.int32, device=dev)
@@ -74,10 +75,14 @@ def rank_layer(st: LayerState, acts: Dict[str, torch.Tensor], alpha: float,
         st.sumsq[a].zero_()
         prune.stats_accumulate(x, st.sumsq[a], ws=st.ws)
         prune.stats_finalize(st.sumsq[a], st.norms[a])
-    for i, name in enumerate(st.names):
+    if scores is None:      # hot mode: every projection of the layer in one batch
+        prune.score_outlier_batch([st.weights[n] for n in st.names], [st.norms[st.proj_inputs[n]] for n in st.names],
+                                  alpha, st.score_sum, st.count, taus=st.tau, ws=st.ws)
+        return
+    for i, name in enumerate(st.names):     # parity mode: scores materialised, one projection at a time
         w = st.weights[name]
         nrm = st.norms[st.proj_inputs[name]]
-        sc = None if scores is None else scores.get(name)
+        sc = scores.get(name)
         prune.score(w, nrm, st.score_sum[i:i + 1], scores=sc, ws=st.ws)
         prune.outlier_ratio(w, nrm, alpha, st.score_sum[i:i + 1], st.count[i:i + 1], tau=st.tau[i:i + 1], scores=sc)
 

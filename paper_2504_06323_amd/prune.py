@@ -20,7 +20,7 @@ _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "csrc", "li
 _lib = None
 
 F32, BF16 = 0, 1
-OP_STATS, OP_SCORE, OP_OUTLIER, OP_SELECT, OP_STRUCT = range(5)
+OP_STATS, OP_SCORE, OP_OUTLIER, OP_SELECT, OP_STRUCT, OP_BATCH = range(6)
 SCOPE_GLOBAL, SCOPE_CATEGORY = 0, 1
 
 _c = ctypes
@@ -35,10 +35,17 @@ _SIGNATURES = {
     "prune_stats_finalize": (_int, [_vp, _i64, _vp, _vp]),
     "prune_score": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]),
     "prune_outlier_ratio": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _f32, _vp, _vp, _vp, _vp]),
+    "prune_score_outlier_batch": (_int, [_vp, _int, _int, _f32, _vp, _vp, _vp, _vp, _sz, _vp]),
     "prune_plan_sparsity": (_int, [_vp, _vp, _vp, _int, _int, _f64, _f64, _int, _vp, _vp, _vp]),
     "prune_select_mask": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _i64, _vp, _vp, _u32, _vp, _vp, _sz, _vp]),
     "prune_struct_compact": (_int, [_vp, _vp, _vp, _int, _i64, _i64, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
 }
+
+
+class Projection(ctypes.Structure):
+    """Mirror of the C struct prune_projection."""
+
+    _fields_ = [("w", _vp), ("rows", _i64), ("cols", _i64), ("ld_w", _i64), ("norms", _vp)]
 
 
 class PruneError(RuntimeError):
@@ -184,6 +191,33 @@ def outlier_ratio(w: Optional[torch.Tensor], norms: Optional[torch.Tensor], alph
                                       _vector(score_sum, "score_sum", torch.float64, 1),
                                       _vector(count, "count", count.dtype, 1),
                                       _vector(tau, "tau", torch.float32, 1), _stream(stream)))
+
+
+def score_outlier_batch(ws_: Sequence[torch.Tensor], norms: Sequence[torch.Tensor], alpha: float,
+                        score_sums: torch.Tensor, counts: torch.Tensor, taus: Optional[torch.Tensor] = None,
+                        ws: Optional[torch.Tensor] = None, stream=None) -> None:
+    """Metric sum, threshold and outlier count of several projections in three launches
+    (prune_score_outlier_batch).  ws_ are the weights, norms the matching norm vectors."""
+    n = len(ws_)
+    if n == 0 or len(norms) != n:
+        raise ValueError("need as many norm vectors as weights")
+    arr = (Projection * n)()
+    code, need = _dtype_code(ws_[0]), 256
+    for i, (w, nrm) in enumerate(zip(ws_, norms)):
+        if _dtype_code(w) != code:
+            raise TypeError("all projections of a batch share one dtype")
+        ptr, rows, cols, ld = _matrix(w, "w")
+        arr[i] = Projection(ptr, rows, cols, ld, _vector(nrm, "norms", torch.float32, cols))
+        need = max(need, workspace_bytes(OP_BATCH, rows, cols))
+    if counts.dtype not in (torch.int64, torch.uint64):
+        raise ValueError("counts must be a 64-bit integer tensor")
+    ws_ptr, ws_bytes, _keep = _workspace(ws, need, ws_[0].device)
+    _check("prune_score_outlier_batch",
+           load().prune_score_outlier_batch(arr, n, code, float(alpha),
+                                            _vector(score_sums, "score_sums", torch.float64, n),
+                                            _vector(counts, "counts", counts.dtype, n),
+                                            _vector(taus, "taus", torch.float32, n), ws_ptr, ws_bytes,
+                                            _stream(stream)))
 
 
 def plan_sparsity(counts: Sequence[int], numels: Sequence[int], n_layers: int, n_proj: int, p: float, lam: float,

@@ -328,3 +328,44 @@ def test_toy_layer_end_to_end(lib):
     wg, wu, wd = orc.struct_compact(masked["gate"], masked["up"], masked["down"], kept)
     assert np.array_equal(to_np(res.gate), wg) and np.array_equal(to_np(res.up), wu)
     assert np.array_equal(to_np(res.down), wd)
+
+
+# ----------------------------------------------------------------- batched ranking
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("case", ["layer", "many", "ragged"])
+def test_score_outlier_batch_vs_oracle(lib, dtype, case):
+    """One call for several projections: per projection the same sums, thresholds and counts as the oracle."""
+    if case == "layer":
+        shapes = [(256, 256), (64, 256), (64, 256), (256, 256), (688, 256), (688, 256), (256, 688)]
+    elif case == "many":                       # more projections than one launch table holds
+        shapes = [(8 + 3 * i, 64 + 8 * (i % 5)) for i in range(37)]
+    else:                                      # widths that rule out 128-bit accesses: per-projection kernels
+        shapes = [(33, 130), (50, 7), (129, 2056)]
+    ws_, norms = [], []
+    for i, (rows, cols) in enumerate(shapes):
+        w, x = _rank_inputs(rows, cols, dtype, seed=1000 + i)
+        ws_.append(w)
+        norms.append(gpu_norms(x)[1])
+    n = len(shapes)
+    alpha = 3.0
+    sums = torch.zeros(n, dtype=torch.float64, device=DEV)
+    counts = torch.full((n,), -1, dtype=torch.int64, device=DEV)
+    taus = torch.zeros(n, dtype=torch.float32, device=DEV)
+    prune.score_outlier_batch(ws_, norms, alpha, sums, counts, taus=taus)
+    sums2, counts2 = torch.zeros_like(sums), torch.zeros_like(counts)
+    prune.score_outlier_batch(ws_, norms, alpha, sums2, counts2)            # again, without the optional output
+    _sync()
+    assert np.array_equal(bits(sums.view(torch.int64)), bits(sums2.view(torch.int64)))   # reproducible
+    assert counts.tolist() == counts2.tolist()
+    for i, (rows, cols) in enumerate(shapes):
+        m32 = host_metric_f32(ws_[i], norms[i])
+        ref = m32.astype(np.float64).sum()
+        assert abs(sums[i].item() - ref) <= 1e-6 * ref
+        tau = np.float32(taus[i].item())
+        assert tau == orc.threshold_f32(alpha, sums[i].item(), rows * cols)
+        assert counts[i].item() == orc.count_above(m32, tau)
+        single = torch.zeros(1, dtype=torch.float64, device=DEV)
+        prune.score(ws_[i], norms[i], single)
+        _sync()
+        assert abs(single.item() - sums[i].item()) <= 1e-9 * ref
