@@ -17,9 +17,9 @@ namespace mp {
 namespace {
 
 constexpr int kBlock = 256;
-constexpr int kUnroll = 4;
+constexpr int kUnroll = 8;
 constexpr int kMaxBatch = 16;
-constexpr int kTargetBlocks = 1024;  // four resident blocks per compute unit
+constexpr int kTargetBlocks = 512;  // two resident blocks per compute unit: measured fastest (long stripes)
 constexpr int kMaxBlocks = 2 * kTargetBlocks;
 
 struct BatchDesc {
@@ -66,7 +66,7 @@ __global__ __launch_bounds__(kBlock) void batch_metric_scan(const BatchArgs args
         for (; r + kUnroll <= r1; r += kUnroll) {
             Packet<T, 8> pk[kUnroll];
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) pk[u].load(ptr + u * d.ld);
+            for (int u = 0; u < kUnroll; ++u) pk[u].template load<true>(ptr + u * d.ld);
             float fs = 0.f;
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(kBlock) void batch_metric_scan(const BatchArgs args
         }
         for (; r < r1; ++r) {
             Packet<T, 8> pk;
-            pk.load(ptr);
+            pk.template load<true>(ptr);
             float v[8], fs = 0.f;
             pk.to_float(v);
 #pragma unroll

@@ -82,7 +82,7 @@ __global__ __launch_bounds__(kBlock) void metric_scan(const T *__restrict__ w, i
         for (; r + kUnroll <= r1; r += kUnroll) {
             Packet<T, VEC> pk[kUnroll];
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u) pk[u].load(p + u * ld);
+            for (int u = 0; u < kUnroll; ++u) pk[u].template load<true>(p + u * ld);
             float fs = 0.f;
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
@@ -105,7 +105,7 @@ __global__ __launch_bounds__(kBlock) void metric_scan(const T *__restrict__ w, i
         }
         for (; r < r1; ++r) {
             Packet<T, VEC> pk;
-            pk.load(p);
+            pk.template load<true>(p);
             float v[VEC], om[VEC];
             pk.to_float(v);
             float fs = 0.f;

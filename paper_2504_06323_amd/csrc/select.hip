@@ -31,7 +31,7 @@ __global__ __launch_bounds__(BLOCK, 4) void select_rows_vec(const T *w, T *w_out
     for (int c = 0; c < NCHUNK; ++c) {
         const uint32_t col0 = (c * BLOCK + tid) * 8;
         if (col0 < cols) {
-            pk[c].load(wrow + col0);
+            pk[c].template load<true>(wrow + col0);
             float om[8];
             if (FROM_SCORES) {
                 load_floats(scores + row * cols + col0, om);

@@ -29,8 +29,8 @@ __global__ __launch_bounds__(kBlock) void row_sumsq_pair(const T *__restrict__ g
     const T *pg = gate + c * hidden, *pu = up + c * hidden;
     for (int64_t j = static_cast<int64_t>(lane) * VEC; j < hidden; j += kWave * VEC) {
         Packet<T, VEC> a, b;
-        a.load(pg + j);
-        b.load(pu + j);
+        a.template load<true>(pg + j);
+        b.template load<true>(pu + j);
         float va[VEC], vb[VEC];
         a.to_float(va);
         b.to_float(vb);
@@ -96,7 +96,7 @@ __global__ __launch_bounds__(kBlock) void gather_rows(const T *__restrict__ src,
     T *d = dst + n * width;
     for (int64_t j = static_cast<int64_t>(threadIdx.x) * VEC; j < width; j += kBlock * VEC) {
         Packet<T, VEC> pk;
-        pk.load(s + j);
+        pk.template load<true>(s + j);
         pk.store(d + j);
     }
 }

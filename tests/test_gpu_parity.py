@@ -368,4 +368,4 @@ def test_score_outlier_batch_vs_oracle(lib, dtype, case):
         single = torch.zeros(1, dtype=torch.float64, device=DEV)
         prune.score(ws_[i], norms[i], single)
         _sync()
-        assert abs(single.item() - sums[i].item()) <= 1e-9 * ref
+        assert abs(single.item() - sums[i].item()) <= 1e-7 * ref      # float32 groups of 32 vs 64 metrics before widening
