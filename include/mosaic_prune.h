@@ -177,6 +177,27 @@ int prune_select_mask(const void *w, void *w_out, int dtype, int64_t rows, int64
                       int64_t ld_out, const float *norms, const float *scores, uint32_t k, uint32_t *mask_bits, void *ws,
                       size_t ws_bytes, void *stream);
 
+/* One projection of a prune_select_mask_batch call; fields as the arguments of prune_select_mask. */
+typedef struct {
+    const void *w;
+    void *w_out;
+    int64_t rows, cols, ld_w, ld_out;
+    const float *norms;
+    uint32_t k;
+    uint32_t *mask_bits; /* nullable */
+} prune_select_item;
+
+/*
+ * prune_select_mask for several projections (Section 4.1.3, category 1, applied to
+ * the projections of a layer): projections whose rows have the same width class
+ * share one launch.  Every item is processed exactly as by prune_select_mask with
+ * scores == NULL (the metric is recomputed from w and norms); the whole batch is
+ * validated before anything is launched.  items is a HOST array of n_items <= 1024
+ * entries, read during the call; all items share dtype.  Needs no workspace.
+ */
+int prune_select_mask_batch(const prune_select_item *items, int n_items, int dtype, void *ws, size_t ws_bytes,
+                            void *stream);
+
 /*
  * Structured removal of MLP intermediate channels (Section 4.1.3, categories
  * 2 and 3; Fig. 4: the nodes between projections are pruned as a group).

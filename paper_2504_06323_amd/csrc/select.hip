@@ -13,18 +13,14 @@ namespace mp {
 
 namespace {
 
+// One row: load it, form the metric keys, search the bound, write the masked row and its keep-bits.
+// wrow / orow / srow / mrow are the row's base addresses (uniform over the block).
 template <typename T, int BLOCK, int NCHUNK, bool FROM_SCORES>
-__global__ __launch_bounds__(BLOCK, 4) void select_rows_vec(const T *w, T *w_out, uint32_t cols, int64_t ld,
-                                                            int64_t ld_out, const float *__restrict__ norms,
-                                                            const float *__restrict__ scores, uint32_t k,
-                                                            int idx_bits, uint8_t *__restrict__ mask_bytes,
-                                                            uint32_t mask_row_bytes) {
-    __shared__ SelectSmem<BLOCK> sm;
-    const int64_t row = blockIdx.x;
+__device__ __forceinline__ void select_one_row(const T *wrow, T *orow, uint32_t cols,
+                                               const float *__restrict__ norms, const float *__restrict__ srow,
+                                               uint32_t k, int idx_bits, uint8_t *__restrict__ mrow,
+                                               uint32_t mask_row_bytes, SelectSmem<BLOCK> &sm) {
     const uint32_t tid = threadIdx.x;
-    const T *wrow = w + row * ld;  // uniform row bases; per-lane offsets stay 32-bit
-    T *orow = w_out + row * ld_out;
-
     Packet<T, 8> pk[NCHUNK];
     uint32_t key[NCHUNK][8];
 #pragma unroll
@@ -34,7 +30,7 @@ __global__ __launch_bounds__(BLOCK, 4) void select_rows_vec(const T *w, T *w_out
             pk[c].template load<true>(wrow + col0);
             float om[8];
             if (FROM_SCORES) {
-                load_floats(scores + row * cols + col0, om);
+                load_floats(srow + col0, om);
             } else {
                 float v[8], nrm[8];
                 pk[c].to_float(v);
@@ -80,14 +76,61 @@ __global__ __launch_bounds__(BLOCK, 4) void select_rows_vec(const T *w, T *w_out
             }
             pk[c].apply_keep(keep);
             pk[c].store(orow + col0);
-            if (mask_bytes) {
-                uint8_t *mrow = mask_bytes + row * mask_row_bytes;
+            if (mrow) {
                 mrow[col0 >> 3] = static_cast<uint8_t>(keep);
                 if (col0 + 8 == cols)  // owner of the last packet clears the padding of the last word
                     for (uint32_t b = (cols >> 3); b < mask_row_bytes; ++b) mrow[b] = 0;
             }
         }
     }
+}
+
+template <typename T, int BLOCK, int NCHUNK, bool FROM_SCORES>
+__global__ __launch_bounds__(BLOCK, 4) void select_rows_vec(const T *w, T *w_out, uint32_t cols, int64_t ld,
+                                                            int64_t ld_out, const float *__restrict__ norms,
+                                                            const float *__restrict__ scores, uint32_t k,
+                                                            int idx_bits, uint8_t *__restrict__ mask_bytes,
+                                                            uint32_t mask_row_bytes) {
+    __shared__ SelectSmem<BLOCK> sm;
+    const int64_t row = blockIdx.x;
+    select_one_row<T, BLOCK, NCHUNK, FROM_SCORES>(w + row * ld, w_out + row * ld_out, cols, norms,
+                                                  FROM_SCORES ? scores + row * cols : nullptr, k, idx_bits,
+                                                  mask_bytes ? mask_bytes + row * mask_row_bytes : nullptr,
+                                                  mask_row_bytes, sm);
+}
+
+// Several projections of equal width class in one launch: the block index is mapped to
+// (projection, row) through a small table in the kernel arguments.
+constexpr int kMaxSelectBatch = 16;
+
+struct SelectItem {
+    const void *w;
+    void *w_out;
+    const float *norms;
+    uint8_t *mask_bytes;
+    int64_t ld, ld_out;
+    uint32_t cols, k, mask_row_bytes, row0;  // row0: first block of this projection
+    int idx_bits, pad;
+};
+
+struct SelectArgs {
+    SelectItem it[kMaxSelectBatch];
+    int n;
+};
+
+template <typename T, int BLOCK, int NCHUNK>
+__global__ __launch_bounds__(BLOCK, 4) void select_rows_batch(const SelectArgs args) {
+    __shared__ SelectSmem<BLOCK> sm;
+    int p = 0;
+    for (int i = 1; i < args.n; ++i)
+        if (blockIdx.x >= args.it[i].row0) p = i;
+    const SelectItem &it = args.it[p];
+    const int64_t row = blockIdx.x - it.row0;
+    select_one_row<T, BLOCK, NCHUNK, false>(static_cast<const T *>(it.w) + row * it.ld,
+                                            static_cast<T *>(it.w_out) + row * it.ld_out, it.cols, it.norms, nullptr,
+                                            it.k, it.idx_bits,
+                                            it.mask_bytes ? it.mask_bytes + row * it.mask_row_bytes : nullptr,
+                                            it.mask_row_bytes, sm);
 }
 
 // any width / pitch / alignment; keys are recomputed from memory on every digit pass
@@ -154,6 +197,39 @@ __global__ __launch_bounds__(256) void fill_keep_all(uint32_t *__restrict__ mask
     }
 }
 
+// waves per row grow with the row width so that a thread holds at most 4 packets (32 keys)
+inline void select_variant(int64_t cols, int &block, int &nchunk) {
+    const int64_t packets = cols / 8;
+    block = packets <= 128 ? 64 : packets <= 256 ? 128 : packets <= 1024 ? 256 : 512;
+    nchunk = static_cast<int>(ceil_div(packets, block));
+}
+
+inline bool select_packets_ok(const void *w, const void *w_out, int64_t cols, int64_t ld, int64_t ld_out,
+                              const float *norms) {
+    return packet_ok(w, cols, ld) && packet_ok(w_out, cols, ld_out) && cols <= 16384 && aligned_to(norms, 16);
+}
+
+template <typename T>
+int launch_select_batch(const SelectArgs &args, int total_rows, int block, int nchunk, hipStream_t stream) {
+    const dim3 grid(static_cast<unsigned>(total_rows));
+#define MP_BATCH_CASE(BLOCK, NCHUNK) \
+    hipLaunchKernelGGL((select_rows_batch<T, BLOCK, NCHUNK>), grid, dim3(BLOCK), 0, stream, args)
+#define MP_BATCH_BLOCK(BLOCK)                   \
+    switch (nchunk) {                           \
+        case 1: MP_BATCH_CASE(BLOCK, 1); break; \
+        case 2: MP_BATCH_CASE(BLOCK, 2); break; \
+        case 3: MP_BATCH_CASE(BLOCK, 3); break; \
+        default: MP_BATCH_CASE(BLOCK, 4); break; \
+    }
+    if (block == 64) { MP_BATCH_BLOCK(64) }
+    else if (block == 128) { MP_BATCH_BLOCK(128) }
+    else if (block == 256) { MP_BATCH_BLOCK(256) }
+    else { MP_BATCH_BLOCK(512) }
+#undef MP_BATCH_BLOCK
+#undef MP_BATCH_CASE
+    return launch_status();
+}
+
 template <typename T, bool FROM_SCORES>
 int launch_select(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld, int64_t ld_out, const float *norms,
                   const float *scores, uint32_t k, uint32_t *mask_bits, hipStream_t stream) {
@@ -173,10 +249,8 @@ int launch_select(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld, 
     hipLaunchKernelGGL((select_rows_vec<T, BLOCK, NCHUNK, FROM_SCORES>), grid, dim3(BLOCK), 0, stream, w, w_out,   \
                        static_cast<uint32_t>(cols), ld, ld_out, norms, scores, k, idx_bits, mb,                   \
                        static_cast<uint32_t>(mrb))
-    const int64_t packets = cols / 8;
-    // waves per row grow with the row width so that a thread holds at most 4 packets (32 keys)
-    const int block = packets <= 128 ? 64 : packets <= 256 ? 128 : packets <= 1024 ? 256 : 512;
-    const int nchunk = static_cast<int>(ceil_div(packets, block));
+    int block, nchunk;
+    select_variant(cols, block, nchunk);
 #define MP_SELECT_BLOCK(BLOCK)                   \
     switch (nchunk) {                            \
         case 1: MP_SELECT_CASE(BLOCK, 1); break; \
@@ -218,12 +292,10 @@ size_t select_workspace_bytes(int64_t, int64_t) { return 0; }  // the row lives 
 
 }  // namespace mp
 
-extern "C" int prune_select_mask(const void *w, void *w_out, int dtype, int64_t rows, int64_t cols, int64_t ld_w,
-                                 int64_t ld_out, const float *norms, const float *scores, uint32_t k, uint32_t *mask_bits, void *ws,
-                                 size_t ws_bytes, void *stream_) {
-    using namespace mp;
-    (void)ws;
-    (void)ws_bytes;
+namespace mp {
+namespace {
+int validate_select(const void *w, const void *w_out, int dtype, int64_t rows, int64_t cols, int64_t ld_w,
+                    int64_t ld_out, const float *norms, const float *scores, uint32_t k, const uint32_t *mask_bits) {
     if (!valid_dtype(dtype)) return PRUNE_ERR_DTYPE;
     if (rows <= 0 || cols <= 0 || ld_w < cols || ld_out < cols || cols > (int64_t(1) << 32) || rows > 0x7fffffff)
         return PRUNE_ERR_SHAPE;
@@ -240,10 +312,100 @@ extern "C" int prune_select_mask(const void *w, void *w_out, int dtype, int64_t 
         const uintptr_t span_b = static_cast<uintptr_t>((rows - 1) * ld_out + cols) * es;
         if ((a < b && a + span_a > b) || (b < a && b + span_b > a)) return PRUNE_ERR_RANGE;
     }
+    return PRUNE_OK;
+}
+}  // namespace
+}  // namespace mp
+
+extern "C" int prune_select_mask(const void *w, void *w_out, int dtype, int64_t rows, int64_t cols, int64_t ld_w,
+                                 int64_t ld_out, const float *norms, const float *scores, uint32_t k,
+                                 uint32_t *mask_bits, void *ws, size_t ws_bytes, void *stream_) {
+    using namespace mp;
+    (void)ws;
+    (void)ws_bytes;
+    const int st = validate_select(w, w_out, dtype, rows, cols, ld_w, ld_out, norms, scores, k, mask_bits);
+    if (st != PRUNE_OK) return st;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     if (dtype == PRUNE_BF16)
-        return select_dispatch(static_cast<const bf16_t *>(w), static_cast<bf16_t *>(w_out), rows, cols, ld_w, ld_out, norms,
-                               scores, k, mask_bits, stream);
-    return select_dispatch(static_cast<const float *>(w), static_cast<float *>(w_out), rows, cols, ld_w, ld_out, norms, scores,
-                           k, mask_bits, stream);
+        return select_dispatch(static_cast<const bf16_t *>(w), static_cast<bf16_t *>(w_out), rows, cols, ld_w, ld_out,
+                               norms, scores, k, mask_bits, stream);
+    return select_dispatch(static_cast<const float *>(w), static_cast<float *>(w_out), rows, cols, ld_w, ld_out, norms,
+                           scores, k, mask_bits, stream);
+}
+
+extern "C" int prune_select_mask_batch(const prune_select_item *items, int n_items, int dtype, void *ws,
+                                       size_t ws_bytes, void *stream_) {
+    using namespace mp;
+    (void)ws;
+    (void)ws_bytes;
+    if (!valid_dtype(dtype)) return PRUNE_ERR_DTYPE;
+    if (n_items <= 0) return PRUNE_ERR_SHAPE;
+    if (!items) return PRUNE_ERR_NULL;
+    for (int i = 0; i < n_items; ++i) {  // reject the whole batch before anything is launched
+        const prune_select_item &q = items[i];
+        const int st = validate_select(q.w, q.w_out, dtype, q.rows, q.cols, q.ld_w, q.ld_out, q.norms, nullptr, q.k,
+                                       q.mask_bits);
+        if (st != PRUNE_OK) return st;
+    }
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    // projections that share a kernel variant go into one launch; the rest take the single-projection path
+    bool done[1024];
+    if (n_items > 1024) return PRUNE_ERR_RANGE;
+    for (int i = 0; i < n_items; ++i) done[i] = false;
+    for (int i = 0; i < n_items; ++i) {
+        if (done[i]) continue;
+        const prune_select_item &q = items[i];
+        const bool batchable = q.k > 0 && select_packets_ok(q.w, q.w_out, q.cols, q.ld_w, q.ld_out, q.norms);
+        if (!batchable) {
+            const int st = prune_select_mask(q.w, q.w_out, dtype, q.rows, q.cols, q.ld_w, q.ld_out, q.norms, nullptr,
+                                             q.k, q.mask_bits, ws, ws_bytes, stream_);
+            if (st != PRUNE_OK) return st;
+            done[i] = true;
+            continue;
+        }
+        int block, nchunk;
+        select_variant(q.cols, block, nchunk);
+        SelectArgs args;
+        args.n = 0;
+        int64_t total_rows = 0;
+        auto flush = [&]() -> int {
+            if (args.n == 0) return PRUNE_OK;
+            const int st = dtype == PRUNE_BF16
+                               ? launch_select_batch<bf16_t>(args, static_cast<int>(total_rows), block, nchunk, stream)
+                               : launch_select_batch<float>(args, static_cast<int>(total_rows), block, nchunk, stream);
+            args.n = 0;
+            total_rows = 0;
+            return st;
+        };
+        for (int j = i; j < n_items; ++j) {
+            if (done[j]) continue;
+            const prune_select_item &r = items[j];
+            if (!(r.k > 0 && select_packets_ok(r.w, r.w_out, r.cols, r.ld_w, r.ld_out, r.norms))) continue;
+            int b2, c2;
+            select_variant(r.cols, b2, c2);
+            if (b2 != block || c2 != nchunk) continue;
+            if (args.n == kMaxSelectBatch || total_rows + r.rows > 0x7fffffff) {
+                const int st = flush();
+                if (st != PRUNE_OK) return st;
+            }
+            SelectItem &it = args.it[args.n++];
+            it.w = r.w;
+            it.w_out = r.w_out;
+            it.norms = r.norms;
+            it.mask_bytes = reinterpret_cast<uint8_t *>(r.mask_bits);
+            it.ld = r.ld_w;
+            it.ld_out = r.ld_out;
+            it.cols = static_cast<uint32_t>(r.cols);
+            it.k = r.k;
+            it.mask_row_bytes = static_cast<uint32_t>(ceil_div(r.cols, 32) * 4);
+            it.row0 = static_cast<uint32_t>(total_rows);
+            it.idx_bits = index_bits_for(r.cols);
+            it.pad = 0;
+            total_rows += r.rows;
+            done[j] = true;
+        }
+        const int st = flush();
+        if (st != PRUNE_OK) return st;
+    }
+    return PRUNE_OK;
 }

@@ -95,10 +95,10 @@ def plan(counts: Sequence[int], numels: Sequence[int], cols: Sequence[int], n_la
 
 def prune_layer(st: LayerState, ks: Sequence[int], in_place: bool = False) -> None:
     """Phase 2, unstructured: zero the k lowest-metric entries per row of every projection."""
-    for i, name in enumerate(st.names):
-        w = st.weights[name]
-        prune.select_mask(w, st.norms[st.proj_inputs[name]], int(ks[i]),
-                          w_out=None if in_place else st.pruned[name], mask_bits=st.mask_bits.get(name), ws=st.ws)
+    names = st.names
+    prune.select_mask_batch([st.weights[n] for n in names], [st.norms[st.proj_inputs[n]] for n in names],
+                            [int(k) for k in ks], w_outs=None if in_place else [st.pruned[n] for n in names],
+                            mask_bits=[st.mask_bits.get(n) for n in names])
 
 
 @dataclass

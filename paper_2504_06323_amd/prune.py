@@ -38,6 +38,7 @@ _SIGNATURES = {
     "prune_score_outlier_batch": (_int, [_vp, _int, _int, _f32, _vp, _vp, _vp, _vp, _sz, _vp]),
     "prune_plan_sparsity": (_int, [_vp, _vp, _vp, _int, _int, _f64, _f64, _int, _vp, _vp, _vp]),
     "prune_select_mask": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _i64, _vp, _vp, _u32, _vp, _vp, _sz, _vp]),
+    "prune_select_mask_batch": (_int, [_vp, _int, _int, _vp, _sz, _vp]),
     "prune_struct_compact": (_int, [_vp, _vp, _vp, _int, _i64, _i64, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
 }
 
@@ -46,6 +47,13 @@ class Projection(ctypes.Structure):
     """Mirror of the C struct prune_projection."""
 
     _fields_ = [("w", _vp), ("rows", _i64), ("cols", _i64), ("ld_w", _i64), ("norms", _vp)]
+
+
+class SelectItem(ctypes.Structure):
+    """Mirror of the C struct prune_select_item."""
+
+    _fields_ = [("w", _vp), ("w_out", _vp), ("rows", _i64), ("cols", _i64), ("ld_w", _i64), ("ld_out", _i64),
+                ("norms", _vp), ("k", _u32), ("mask_bits", _vp)]
 
 
 class PruneError(RuntimeError):
@@ -264,6 +272,36 @@ def select_mask(w: torch.Tensor, norms: Optional[torch.Tensor], k: int, w_out: O
                                                                            rows * words),
                                     None if ws is None else ws.data_ptr(),
                                     0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)))
+
+
+def select_mask_batch(ws_: Sequence[torch.Tensor], norms: Sequence[torch.Tensor], ks: Sequence[int],
+                      w_outs: Optional[Sequence[Optional[torch.Tensor]]] = None,
+                      mask_bits: Optional[Sequence[Optional[torch.Tensor]]] = None, stream=None) -> None:
+    """prune_select_mask for several projections, same-width projections sharing a launch
+    (prune_select_mask_batch).  In place where w_outs (or an entry of it) is None."""
+    n = len(ws_)
+    if n == 0 or len(norms) != n or len(ks) != n:
+        raise ValueError("need one norm vector and one k per weight")
+    arr = (SelectItem * n)()
+    code = _dtype_code(ws_[0])
+    for i, w in enumerate(ws_):
+        if _dtype_code(w) != code:
+            raise TypeError("all projections of a batch share one dtype")
+        ptr, rows, cols, ld = _matrix(w, "w")
+        out = None if w_outs is None else w_outs[i]
+        if out is None:
+            out_ptr, ld_out = ptr, ld
+        else:
+            out_ptr, orows, ocols, ld_out = _matrix(out, "w_out")
+            if (orows, ocols) != (rows, cols) or out.dtype != w.dtype:
+                raise ValueError("w_out must match w in shape and dtype")
+        mb = None if mask_bits is None else mask_bits[i]
+        if mb is not None and mb.dtype not in (torch.int32, torch.uint32):
+            raise ValueError("mask_bits must be a 32-bit integer tensor")
+        arr[i] = SelectItem(ptr, out_ptr, rows, cols, ld, ld_out, _vector(norms[i], "norms", torch.float32, cols),
+                            int(ks[i]),
+                            None if mb is None else _vector(mb, "mask_bits", mb.dtype, rows * ((cols + 31) // 32)))
+    _check("prune_select_mask_batch", load().prune_select_mask_batch(arr, n, code, None, 0, _stream(stream)))
 
 
 def struct_compact(gate: torch.Tensor, up: torch.Tensor, down: torch.Tensor, r: int, group_mag: torch.Tensor,

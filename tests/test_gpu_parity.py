@@ -369,3 +369,30 @@ def test_score_outlier_batch_vs_oracle(lib, dtype, case):
         prune.score(ws_[i], norms[i], single)
         _sync()
         assert abs(single.item() - sums[i].item()) <= 1e-7 * ref      # float32 groups of 32 vs 64 metrics before widening
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_select_mask_batch_vs_oracle(lib, dtype):
+    """Several projections per call: equal-width ones share a launch, odd ones take the single path."""
+    shapes = [(40, 1024), (16, 1024), (9, 688), (25, 1024), (7, 4104), (5, 130), (12, 1024), (3, 16392)] + \
+             [(4 + i, 512) for i in range(20)]                     # more than one launch table of one width
+    ws_, norms, ks, outs, masks = [], [], [], [], []
+    for i, (rows, cols) in enumerate(shapes):
+        w, x = _rank_inputs(rows, cols, dtype, seed=2000 + i)
+        ws_.append(w)
+        norms.append(gpu_norms(x)[1])
+        ks.append([cols // 2, 0, cols // 3, cols, 1][i % 5])
+        outs.append(None if i % 4 == 3 else torch.full_like(w, 7.0))
+        masks.append(None if i % 3 == 2 else torch.full((rows, (cols + 31) // 32), -1, dtype=torch.int32, device=DEV))
+    originals = [to_np(w).copy() for w in ws_]
+    metrics = [host_metric_f32(w, n) for w, n in zip(ws_, norms)]
+    prune.select_mask_batch(ws_, norms, ks, w_outs=outs, mask_bits=masks)
+    _sync()
+    for i, (rows, cols) in enumerate(shapes):
+        pruned = orc.select_smallest_per_row(metrics[i], ks[i])
+        got = to_np(outs[i] if outs[i] is not None else ws_[i])
+        assert np.array_equal(got, orc.apply_mask(originals[i], pruned)), f"item {i} {shapes[i]} k={ks[i]}"
+        if masks[i] is not None:
+            assert np.array_equal(to_np(masks[i]).view(np.uint32), orc.pack_keep_bits(pruned)), f"item {i}"
+        if outs[i] is not None:
+            assert np.array_equal(to_np(ws_[i]), originals[i])          # the input is untouched when out of place

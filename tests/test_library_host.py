@@ -86,6 +86,19 @@ def test_error_paths_return_before_any_launch(lib):
     assert sm(fake, None, 1, 8, 8, 8, 8, fake, None, 1, None, None, 0, None) == E["null"]
     assert sm(fake, fake, 1, 8, 8, 8, 8, None, None, 1, None, None, 0, None) == E["null"]
     assert sm(fake, ctypes.c_void_p(0x1010), 1, 8, 8, 8, 8, fake, None, 1, None, None, 0, None) == E["rng"]  # overlap
+    smb = lib.prune_select_mask_batch
+    item = lambda **kw: prune.SelectItem(**{**dict(w=0x1000, w_out=0x1000, rows=8, cols=8, ld_w=8, ld_out=8,
+                                                   norms=0x1000, k=1, mask_bits=None), **kw})
+    one = lambda **kw: (prune.SelectItem * 1)(item(**kw))
+    assert smb(one(), 0, 1, None, 0, None) == E["shape"]
+    assert smb(None, 1, 1, None, 0, None) == E["null"]
+    assert smb(one(), 1, 4, None, 0, None) == E["dtype"]
+    assert smb(one(k=9), 1, 1, None, 0, None) == E["rng"]
+    assert smb(one(norms=None), 1, 1, None, 0, None) == E["null"]
+    assert smb(one(ld_w=4), 1, 1, None, 0, None) == E["shape"]
+    assert smb(one(w_out=0x1010), 1, 1, None, 0, None) == E["rng"]
+    two = (prune.SelectItem * 2)(item(), item(w_out=None))          # a bad second item rejects the whole batch
+    assert smb(two, 2, 1, None, 0, None) == E["null"]
     st = lib.prune_struct_compact
     assert st(fake, fake, fake, 1, 8, 8, 8, fake, fake, None, None, None, fake, 1 << 20, None) == E["rng"]  # r >= inter
     assert st(fake, fake, fake, 1, 8, 8, 1, fake, fake, fake, None, None, fake, 1 << 20, None) == E["null"]  # 1 of 3 outs
