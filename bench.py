@@ -149,15 +149,13 @@ def main():
             marks[0].record()
         for a in names:
             x = acts[a]
-            st.sumsq[a].zero_()
             if record:
                 e0, e1 = ev(), ev()
                 e0.record()
-            prune.stats_accumulate(x, st.sumsq[a], ws=st.ws)
+            prune.stats_norms(x, st.sumsq[a], st.norms[a], ws=st.ws)
             if record:
                 e1.record()
-                stats_events.append((e0, e1, x.numel() * x.element_size() + x.shape[1] * 4))
-            prune.stats_finalize(st.sumsq[a], st.norms[a])
+                stats_events.append((e0, e1, x.numel() * x.element_size() + x.shape[1] * 8))
         if record:
             marks[1].record()
         prune.score_outlier_batch([st.weights[n] for n in st.names],

@@ -94,6 +94,15 @@ size_t prune_workspace_bytes(int op, int64_t rows, int64_t cols);
 int prune_stats_accumulate(const void *x, int dtype, int64_t n_tokens, int64_t n_channels, int64_t ld_x,
                            float *sumsq, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * The same statistics for a tensor that is handed over whole, in one call:
+ *   sumsq[j] = sum over t < n_tokens of x[t * ld_x + j]^2 ;  norms[j] = sqrt(sumsq[j])
+ * Both outputs are overwritten (no zeroing by the caller, no finalize call).
+ * n_tokens == 0 writes zeros.  Workspace as for prune_stats_accumulate.
+ */
+int prune_stats_norms(const void *x, int dtype, int64_t n_tokens, int64_t n_channels, int64_t ld_x, float *sumsq,
+                      float *norms, void *ws, size_t ws_bytes, void *stream);
+
 /* norms[j] = sqrt(sumsq[j]) (correctly rounded float sqrt).  In place allowed. */
 int prune_stats_finalize(const float *sumsq, int64_t n_channels, float *norms, void *stream);
 

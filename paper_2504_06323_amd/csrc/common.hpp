@@ -189,9 +189,10 @@ struct ColsumPlan {
 };
 ColsumPlan plan_colsum(int64_t n_rows, int64_t n_cols);
 size_t colsum_workspace_bytes(int64_t n_rows, int64_t n_cols);
-// sumsq[j] += sum_t x[t, j]^2; ws holds the per-stripe partials
+// sumsq[j] (+)= sum_t x[t, j]^2 (accumulate picks += or =); norms (optional) = sqrt of the result;
+// ws holds the per-stripe partials
 int launch_colsum(const void *x, int dtype, int64_t n_rows, int64_t n_cols, int64_t ld, float *sumsq, void *ws,
-                  hipStream_t stream);
+                  hipStream_t stream, bool accumulate = true, float *norms = nullptr);
 
 size_t score_workspace_bytes(int64_t rows, int64_t cols);
 size_t select_workspace_bytes(int64_t rows, int64_t cols);

@@ -105,8 +105,10 @@ __global__ __launch_bounds__(kBlock) void colsumsq_partial_scalar(const T *__res
 constexpr int kReduceBlock = 1024;
 constexpr int kReduceGroups = kReduceBlock / kWave;
 
+// accumulate == 0 overwrites sumsq instead; norms (optional) receives sqrt of the new sumsq.
 __global__ __launch_bounds__(kReduceBlock) void colsumsq_reduce(const float *__restrict__ partials, int n_stripes,
-                                                                int64_t n_cols, float *__restrict__ sumsq) {
+                                                                int64_t n_cols, float *__restrict__ sumsq,
+                                                                int accumulate, float *__restrict__ norms) {
     __shared__ double sm[kReduceGroups][kWave];
     const int lane = threadIdx.x & (kWave - 1), grp = threadIdx.x / kWave;
     const int64_t c = static_cast<int64_t>(blockIdx.x) * kWave + lane;
@@ -132,7 +134,9 @@ __global__ __launch_bounds__(kReduceBlock) void colsumsq_reduce(const float *__r
         double tot = 0.0;
 #pragma unroll
         for (int g = 0; g < kReduceGroups; ++g) tot += sm[g][lane];
-        sumsq[c] = static_cast<float>(static_cast<double>(sumsq[c]) + tot);
+        const float total = static_cast<float>((accumulate ? static_cast<double>(sumsq[c]) : 0.0) + tot);
+        sumsq[c] = total;
+        if (norms) norms[c] = sqrtf(total);  // correctly rounded (hipcc default)
     }
 }
 
@@ -144,8 +148,13 @@ __global__ __launch_bounds__(kBlock) void sqrt_kernel(const float *__restrict__ 
 
 template <typename T>
 int launch_colsum_t(const T *x, int64_t n_rows, int64_t n_cols, int64_t ld, float *sumsq, float *partials,
-                    hipStream_t stream) {
+                    hipStream_t stream, bool accumulate, float *norms) {
     const ColsumPlan pl = plan_colsum(n_rows, n_cols);
+    if (n_rows == 0) {  // nothing to stream: the reduction alone writes zeros (or leaves the running sums)
+        hipLaunchKernelGGL(colsumsq_reduce, dim3(static_cast<unsigned>(ceil_div(n_cols, kWave))), dim3(kReduceBlock),
+                           0, stream, partials, 0, n_cols, sumsq, accumulate ? 1 : 0, norms);
+        return launch_status();
+    }
     if (packet_ok(x, n_cols, ld)) {
         dim3 grid(pl.tiles_vec, pl.stripes);
         hipLaunchKernelGGL((colsumsq_partial_vec<T, 8, kBlock>), grid, dim3(kBlock), 0, stream, x, n_rows, n_cols, ld,
@@ -157,7 +166,7 @@ int launch_colsum_t(const T *x, int64_t n_rows, int64_t n_cols, int64_t ld, floa
     }
     if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
     hipLaunchKernelGGL(colsumsq_reduce, dim3(static_cast<unsigned>(ceil_div(n_cols, kWave))), dim3(kReduceBlock), 0,
-                       stream, partials, pl.stripes, n_cols, sumsq);
+                       stream, partials, pl.stripes, n_cols, sumsq, accumulate ? 1 : 0, norms);
     return launch_status();
 }
 
@@ -185,11 +194,13 @@ size_t colsum_workspace_bytes(int64_t n_rows, int64_t n_cols) {
 }
 
 int launch_colsum(const void *x, int dtype, int64_t n_rows, int64_t n_cols, int64_t ld, float *sumsq, void *ws,
-                  hipStream_t stream) {
+                  hipStream_t stream, bool accumulate, float *norms) {
     float *partials = static_cast<float *>(ws);
     if (dtype == PRUNE_BF16)
-        return launch_colsum_t(static_cast<const bf16_t *>(x), n_rows, n_cols, ld, sumsq, partials, stream);
-    return launch_colsum_t(static_cast<const float *>(x), n_rows, n_cols, ld, sumsq, partials, stream);
+        return launch_colsum_t(static_cast<const bf16_t *>(x), n_rows, n_cols, ld, sumsq, partials, stream, accumulate,
+                               norms);
+    return launch_colsum_t(static_cast<const float *>(x), n_rows, n_cols, ld, sumsq, partials, stream, accumulate,
+                           norms);
 }
 
 }  // namespace mp
@@ -205,6 +216,20 @@ extern "C" int prune_stats_accumulate(const void *x, int dtype, int64_t n_tokens
     if (!aligned_to(x, elem_size(dtype)) || !aligned_to(sumsq, 4) || !aligned_to(ws, 16)) return PRUNE_ERR_ALIGNMENT;
     if (ws_bytes < colsum_workspace_bytes(n_tokens, n_channels)) return PRUNE_ERR_WORKSPACE;
     return launch_colsum(x, dtype, n_tokens, n_channels, ld_x, sumsq, ws, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int prune_stats_norms(const void *x, int dtype, int64_t n_tokens, int64_t n_channels, int64_t ld_x,
+                                 float *sumsq, float *norms, void *ws, size_t ws_bytes, void *stream) {
+    using namespace mp;
+    if (!valid_dtype(dtype)) return PRUNE_ERR_DTYPE;
+    if (n_tokens < 0 || n_channels <= 0 || ld_x < n_channels) return PRUNE_ERR_SHAPE;
+    if (!sumsq || !norms || !ws || (n_tokens > 0 && !x)) return PRUNE_ERR_NULL;
+    if ((x && !aligned_to(x, elem_size(dtype))) || !aligned_to(sumsq, 4) || !aligned_to(norms, 4) ||
+        !aligned_to(ws, 16))
+        return PRUNE_ERR_ALIGNMENT;
+    if (ws_bytes < colsum_workspace_bytes(n_tokens > 0 ? n_tokens : 1, n_channels)) return PRUNE_ERR_WORKSPACE;
+    return launch_colsum(x, dtype, n_tokens, n_channels, ld_x, sumsq, ws, static_cast<hipStream_t>(stream), false,
+                         norms);
 }
 
 extern "C" int prune_stats_finalize(const float *sumsq, int64_t n_channels, float *norms, void *stream) {

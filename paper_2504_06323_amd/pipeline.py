@@ -71,10 +71,8 @@ class LayerState:
 def rank_layer(st: LayerState, acts: Dict[str, torch.Tensor], alpha: float,
                scores: Optional[Dict[str, torch.Tensor]] = None) -> None:
     """Phase 1: norms for every distinct input, then metric sum + outlier count for every projection."""
-    for a, x in acts.items():
-        st.sumsq[a].zero_()
-        prune.stats_accumulate(x, st.sumsq[a], ws=st.ws)
-        prune.stats_finalize(st.sumsq[a], st.norms[a])
+    for a, x in acts.items():        # each activation tensor is resident whole: one call gives sums and norms
+        prune.stats_norms(x, st.sumsq[a], st.norms[a], ws=st.ws)
     if scores is None:      # hot mode: every projection of the layer in one batch
         prune.score_outlier_batch([st.weights[n] for n in st.names], [st.norms[st.proj_inputs[n]] for n in st.names],
                                   alpha, st.score_sum, st.count, taus=st.tau, ws=st.ws)

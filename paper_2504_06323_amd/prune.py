@@ -32,6 +32,7 @@ _SIGNATURES = {
     "prune_status_string": (_c.c_char_p, [_int]),
     "prune_workspace_bytes": (_sz, [_int, _i64, _i64]),
     "prune_stats_accumulate": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
+    "prune_stats_norms": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
     "prune_stats_finalize": (_int, [_vp, _i64, _vp, _vp]),
     "prune_score": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]),
     "prune_outlier_ratio": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _f32, _vp, _vp, _vp, _vp]),
@@ -159,6 +160,16 @@ def stats_accumulate(x: torch.Tensor, sumsq: torch.Tensor, ws: Optional[torch.Te
     _check("prune_stats_accumulate",
            load().prune_stats_accumulate(ptr, _dtype_code(x), t, c, ld, _vector(sumsq, "sumsq", torch.float32, c),
                                          ws_ptr, ws_bytes, _stream(stream)))
+
+
+def stats_norms(x: torch.Tensor, sumsq: torch.Tensor, norms: torch.Tensor, ws: Optional[torch.Tensor] = None,
+                stream=None) -> None:
+    """sumsq = column sums of squares of the whole tensor, norms = sqrt(sumsq) (prune_stats_norms)."""
+    ptr, t, c, ld = _matrix(x, "x")
+    ws_ptr, ws_bytes, _keep = _workspace(ws, workspace_bytes(OP_STATS, max(t, 1), c), x.device)
+    _check("prune_stats_norms",
+           load().prune_stats_norms(ptr, _dtype_code(x), t, c, ld, _vector(sumsq, "sumsq", torch.float32, c),
+                                    _vector(norms, "norms", torch.float32, c), ws_ptr, ws_bytes, _stream(stream)))
 
 
 def stats_finalize(sumsq: torch.Tensor, norms: torch.Tensor, stream=None) -> None:

@@ -73,6 +73,25 @@ def test_stats_pitch_chunks_and_determinism(lib, dtype):
         assert rel_err(to_np(s3), want) < 2e-6
 
 
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("shape", [(512, 688), (1000, 4104), (301, 7), (0, 64)])
+def test_stats_norms_one_call(lib, dtype, shape):
+    """The one-call form overwrites both outputs and equals accumulate + finalize bit for bit."""
+    t, c = shape
+    x = synth.random_matrix(max(t, 1), c, dtype, seed=t + c, device=DEV)[:t]
+    sumsq = torch.full((c,), 123.0, dtype=torch.float32, device=DEV)      # stale contents must not leak in
+    norms = torch.full((c,), -1.0, dtype=torch.float32, device=DEV)
+    prune.stats_norms(x, sumsq, norms)
+    _sync()
+    want = orc.column_sumsq(to_np(x)) if t else np.zeros(c)
+    if t:
+        assert rel_err(to_np(sumsq), want) < 2e-6 and rel_err(to_np(norms), np.sqrt(want)) < 2e-6
+        s2, n2 = gpu_norms(x)
+        assert np.array_equal(bits(sumsq), bits(s2)) and np.array_equal(bits(norms), bits(n2))
+    else:
+        assert (to_np(sumsq) == 0).all() and (to_np(norms) == 0).all()
+
+
 def test_stats_zero_tokens_and_closed_form(lib):
     x = torch.empty((0, 64), dtype=torch.bfloat16, device=DEV)
     sumsq = torch.full((64,), 3.0, dtype=torch.float32, device=DEV)

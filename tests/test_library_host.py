@@ -56,6 +56,12 @@ def test_error_paths_return_before_any_launch(lib):
     assert sa(odd, 1, 8, 8, 8, fake, fake, 1 << 20, None) == E["align"]
     assert sa(fake, 1, 8, 8, 8, fake, fake, 4, None) == E["ws"]
     assert sa(None, 1, 0, 8, 8, fake, None, 0, None) == 0                       # zero tokens: valid no-op
+    sn = lib.prune_stats_norms
+    assert sn(fake, 1, 8, 8, 8, fake, None, fake, 1 << 20, None) == E["null"]
+    assert sn(None, 1, 8, 8, 8, fake, fake, fake, 1 << 20, None) == E["null"]
+    assert sn(fake, 1, 8, 8, 4, fake, fake, fake, 1 << 20, None) == E["shape"]
+    assert sn(fake, 3, 8, 8, 8, fake, fake, fake, 1 << 20, None) == E["dtype"]
+    assert sn(fake, 1, 8, 8, 8, fake, fake, fake, 4, None) == E["ws"]
     assert lib.prune_stats_finalize(None, 8, fake, None) == E["null"]
     assert lib.prune_stats_finalize(fake, 0, fake, None) == E["shape"]
     sc = lib.prune_score
