@@ -58,10 +58,15 @@ typedef enum {
     PRUNE_OP_OUTLIER = 2, /* needs no workspace (returns 0) */
     PRUNE_OP_SELECT = 3,  /* rows, cols of W */
     PRUNE_OP_STRUCT = 4,  /* rows = inter, cols = hidden */
-    PRUNE_OP_BATCH = 5    /* prune_score_outlier_batch: rows, cols of the largest projection of the batch */
+    PRUNE_OP_BATCH = 5    /* prune_score_outlier_batch: a constant, rows and cols are ignored (pass 1, 1) */
 } prune_op;
 
 typedef enum { PRUNE_SCOPE_GLOBAL = 0, PRUNE_SCOPE_CATEGORY = 1 } prune_scope;
+
+/* Which mean an outlier is measured against: that of its own projection (Eq. 6, projection
+ * outlier distribution) or that of all projections handed over together, i.e. of the layer
+ * (Eq. 3 and Eq. 4, layer outlier distribution). */
+typedef enum { PRUNE_OUTLIERS_PER_PROJECTION = 0, PRUNE_OUTLIERS_PER_LAYER = 1 } prune_outlier_scope;
 
 /* One projection of a batch: weight [rows, cols] (device, pitch ld_w) and the norms [cols] (device)
  * of the activation it multiplies. */
@@ -134,23 +139,28 @@ int prune_outlier_ratio(const void *w, int dtype, int64_t rows, int64_t cols, in
                         unsigned long long *count, float *tau, void *stream);
 
 /*
- * Weight metric and projection outliers of several projections at once (the
- * loop over the projections of a layer in Algorithm 1; Eq. 5 and Eq. 6 for
- * each): three launches for the whole batch instead of four per projection.
- * For every i < n_proj
+ * Weight metric and outliers of several projections at once (the loop over the
+ * projections of a layer in Algorithm 1): three launches for the whole batch
+ * instead of four per projection.
+ * outlier_scope == PRUNE_OUTLIERS_PER_PROJECTION (Eq. 5, Eq. 6): for every i
  *   score_sums[i], taus[i], counts[i]
  * are what prune_score (without materialised scores) followed by
  * prune_outlier_ratio compute for projs[i]; the sums are accumulated in a
  * different fixed order, so they may differ from the single calls in the last
  * bits, and counts are exact for the threshold taus[i] that is reported.
+ * outlier_scope == PRUNE_OUTLIERS_PER_LAYER (Eq. 3, Eq. 4, with the batch being
+ * the projections of one layer, at most 16): score_sums[i] as above, but every
+ *   taus[i] = float(alpha * sum_i score_sums[i] / sum_i rows_i * cols_i)
+ * and counts[i] = #{omega in projs[i] : omega > that threshold}; the layer's
+ * outlier count is the sum of counts[].
  * projs is a HOST array (read during the call); score_sums, counts, taus
  * (optional) are device arrays of n_proj entries.  All projections share dtype.
- * ws_bytes >= prune_workspace_bytes(PRUNE_OP_BATCH, rows, cols) of the largest
- * projection.  Projections that cannot use 128-bit accesses make the call run
- * the single-projection kernels one after the other, with the same results.
+ * ws_bytes >= prune_workspace_bytes(PRUNE_OP_BATCH, 1, 1) (a constant).  If any
+ * projection rules out 128-bit accesses the whole batch runs on scalar accesses.
  */
-int prune_score_outlier_batch(const prune_projection *projs, int n_proj, int dtype, float alpha, double *score_sums,
-                              unsigned long long *counts, float *taus, void *ws, size_t ws_bytes, void *stream);
+int prune_score_outlier_batch(const prune_projection *projs, int n_proj, int dtype, float alpha, int outlier_scope,
+                              double *score_sums, unsigned long long *counts, float *taus, void *ws, size_t ws_bytes,
+                              void *stream);
 
 /*
  * host only, touches no device (Algorithm 1's normalize(R_LLM) and the

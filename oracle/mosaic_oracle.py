@@ -14,6 +14,7 @@ notation of the paper (Mosaic, arXiv 2504.06323):
   * weight metric  omega         -- Eq. 5
   * projection outliers O, C, R  -- Eq. 6 and the three assignments of
                                     Algorithm 1 that follow the weight metric
+  * layer outliers               -- Eq. 3 and Eq. 4 (the layer-level rule)
   * normalize(R_LLM) + planner   -- Algorithm 1's return value and the
                                     Projection Planner of Section 3.3
   * unstructured masking         -- Section 4.1.3, category 1
@@ -30,6 +31,7 @@ Parity status of each function:
   column_sumsq / column_norms      pinned (closed forms, library norm)
   weight_metric                    pinned (hand example, magnitude special case)
   outlier_stats / count_above      pinned (hand example, brute force, strictness)
+  layer_outlier_stats              pinned (hand example, brute force, one-projection special case)
   plan_sparsity                    PARITY UNPINNED against the paper: the paper gives no
                                    formula for normalize() or for the planner's scaling;
                                    pinned only by the invariants it states (mean = p,
@@ -86,6 +88,22 @@ def outlier_stats(omega, alpha: float):
     mean = flat.sum() / c
     o = int(np.count_nonzero(flat > alpha * mean))
     return c, o, 100.0 * o / c, mean
+
+
+def layer_outlier_stats(omegas, alpha: float):
+    """Layer Outlier Distribution (Eq. 3, Eq. 4): the layer-level rule the projection rule refines.
+
+    omegas are the weight metrics of all projections of one layer.  The metric
+    vector of the layer is their concatenation; a parameter is an outlier if its
+    metric exceeds alpha times the mean over the whole layer (strict).  Returns
+    (C, O, R, mean, per-projection outlier counts).
+    """
+    flat = np.concatenate([_f64(o).reshape(-1) for o in omegas])
+    c = flat.size
+    mean = flat.sum() / c
+    per_proj = [int(np.count_nonzero(_f64(o) > alpha * mean)) for o in omegas]
+    o = int(np.count_nonzero(flat > alpha * mean))
+    return c, o, 100.0 * o / c, mean, per_proj
 
 
 def count_above(scores, tau) -> int:

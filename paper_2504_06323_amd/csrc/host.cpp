@@ -42,10 +42,7 @@ extern "C" size_t prune_workspace_bytes(int op, int64_t rows, int64_t cols) {
         case PRUNE_OP_OUTLIER: return 0;
         case PRUNE_OP_SELECT: n = mp::select_workspace_bytes(rows, cols); break;
         case PRUNE_OP_STRUCT: n = mp::struct_workspace_bytes(rows, cols); break;
-        case PRUNE_OP_BATCH:
-            n = mp::score_workspace_bytes(rows, cols);
-            if (n < mp::rank_batch_workspace_bytes()) n = mp::rank_batch_workspace_bytes();
-            break;
+        case PRUNE_OP_BATCH: n = mp::rank_batch_workspace_bytes(); break;
         default: return 0;
     }
     return (n + 255) / 256 * 256;

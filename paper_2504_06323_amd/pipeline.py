@@ -69,14 +69,20 @@ class LayerState:
 
 
 def rank_layer(st: LayerState, acts: Dict[str, torch.Tensor], alpha: float,
-               scores: Optional[Dict[str, torch.Tensor]] = None) -> None:
-    """Phase 1: norms for every distinct input, then metric sum + outlier count for every projection."""
+               scores: Optional[Dict[str, torch.Tensor]] = None,
+               outlier_scope: int = prune.OUTLIERS_PER_PROJECTION) -> None:
+    """Phase 1: norms for every distinct input, then metric sum + outlier count for every projection.
+
+    outlier_scope = prune.OUTLIERS_PER_LAYER measures outliers against the layer mean (the
+    layer-level rule the paper starts from) instead of each projection's own mean."""
     for a, x in acts.items():        # each activation tensor is resident whole: one call gives sums and norms
         prune.stats_norms(x, st.sumsq[a], st.norms[a], ws=st.ws)
     if scores is None:      # hot mode: every projection of the layer in one batch
         prune.score_outlier_batch([st.weights[n] for n in st.names], [st.norms[st.proj_inputs[n]] for n in st.names],
-                                  alpha, st.score_sum, st.count, taus=st.tau, ws=st.ws)
+                                  alpha, st.score_sum, st.count, taus=st.tau, ws=st.ws, outlier_scope=outlier_scope)
         return
+    if outlier_scope != prune.OUTLIERS_PER_PROJECTION:
+        raise ValueError("materialised scores are only offered with per-projection thresholds")
     for i, name in enumerate(st.names):     # parity mode: scores materialised, one projection at a time
         w = st.weights[name]
         nrm = st.norms[st.proj_inputs[name]]

@@ -22,6 +22,7 @@ _lib = None
 F32, BF16 = 0, 1
 OP_STATS, OP_SCORE, OP_OUTLIER, OP_SELECT, OP_STRUCT, OP_BATCH = range(6)
 SCOPE_GLOBAL, SCOPE_CATEGORY = 0, 1
+OUTLIERS_PER_PROJECTION, OUTLIERS_PER_LAYER = 0, 1
 
 _c = ctypes
 _vp, _i64, _int, _sz, _u32, _f32, _f64 = (_c.c_void_p, _c.c_int64, _c.c_int, _c.c_size_t, _c.c_uint32,
@@ -36,7 +37,7 @@ _SIGNATURES = {
     "prune_stats_finalize": (_int, [_vp, _i64, _vp, _vp]),
     "prune_score": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]),
     "prune_outlier_ratio": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _f32, _vp, _vp, _vp, _vp]),
-    "prune_score_outlier_batch": (_int, [_vp, _int, _int, _f32, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "prune_score_outlier_batch": (_int, [_vp, _int, _int, _f32, _int, _vp, _vp, _vp, _vp, _sz, _vp]),
     "prune_plan_sparsity": (_int, [_vp, _vp, _vp, _int, _int, _f64, _f64, _int, _vp, _vp, _vp]),
     "prune_select_mask": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _i64, _vp, _vp, _u32, _vp, _vp, _sz, _vp]),
     "prune_select_mask_batch": (_int, [_vp, _int, _int, _vp, _sz, _vp]),
@@ -214,25 +215,26 @@ def outlier_ratio(w: Optional[torch.Tensor], norms: Optional[torch.Tensor], alph
 
 def score_outlier_batch(ws_: Sequence[torch.Tensor], norms: Sequence[torch.Tensor], alpha: float,
                         score_sums: torch.Tensor, counts: torch.Tensor, taus: Optional[torch.Tensor] = None,
-                        ws: Optional[torch.Tensor] = None, stream=None) -> None:
+                        ws: Optional[torch.Tensor] = None, stream=None,
+                        outlier_scope: int = OUTLIERS_PER_PROJECTION) -> None:
     """Metric sum, threshold and outlier count of several projections in three launches
-    (prune_score_outlier_batch).  ws_ are the weights, norms the matching norm vectors."""
+    (prune_score_outlier_batch).  ws_ are the weights, norms the matching norm vectors;
+    outlier_scope picks per-projection (Eq. 6) or per-layer (Eq. 4) thresholds."""
     n = len(ws_)
     if n == 0 or len(norms) != n:
         raise ValueError("need as many norm vectors as weights")
     arr = (Projection * n)()
-    code, need = _dtype_code(ws_[0]), 256
+    code, need = _dtype_code(ws_[0]), workspace_bytes(OP_BATCH, 1, 1)
     for i, (w, nrm) in enumerate(zip(ws_, norms)):
         if _dtype_code(w) != code:
             raise TypeError("all projections of a batch share one dtype")
         ptr, rows, cols, ld = _matrix(w, "w")
         arr[i] = Projection(ptr, rows, cols, ld, _vector(nrm, "norms", torch.float32, cols))
-        need = max(need, workspace_bytes(OP_BATCH, rows, cols))
     if counts.dtype not in (torch.int64, torch.uint64):
         raise ValueError("counts must be a 64-bit integer tensor")
     ws_ptr, ws_bytes, _keep = _workspace(ws, need, ws_[0].device)
     _check("prune_score_outlier_batch",
-           load().prune_score_outlier_batch(arr, n, code, float(alpha),
+           load().prune_score_outlier_batch(arr, n, code, float(alpha), int(outlier_scope),
                                             _vector(score_sums, "score_sums", torch.float64, n),
                                             _vector(counts, "counts", counts.dtype, n),
                                             _vector(taus, "taus", torch.float32, n), ws_ptr, ws_bytes,

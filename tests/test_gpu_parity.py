@@ -415,3 +415,37 @@ def test_select_mask_batch_vs_oracle(lib, dtype):
             assert np.array_equal(to_np(masks[i]).view(np.uint32), orc.pack_keep_bits(pruned)), f"item {i}"
         if outs[i] is not None:
             assert np.array_equal(to_np(ws_[i]), originals[i])          # the input is untouched when out of place
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("aligned", [True, False])
+def test_layer_scope_outliers_vs_oracle(lib, dtype, aligned):
+    """Layer-level rule (Eq. 3, Eq. 4): one threshold from the mean over all projections of the batch."""
+    shapes = [(256, 256), (64, 256), (688, 256), (256, 688)] if aligned else [(33, 130), (50, 7), (129, 2056)]
+    ws_, norms = [], []
+    for i, (rows, cols) in enumerate(shapes):
+        w, x = _rank_inputs(rows, cols, dtype, seed=3000 + i)
+        ws_.append(w * (1.0 + 3.0 * i))                  # different scales: layer and projection rules differ
+        norms.append(gpu_norms(x)[1])
+    n = len(shapes)
+    alpha = 4.0
+    sums = torch.zeros(n, dtype=torch.float64, device=DEV)
+    counts = torch.zeros(n, dtype=torch.int64, device=DEV)
+    taus = torch.zeros(n, dtype=torch.float32, device=DEV)
+    prune.score_outlier_batch(ws_, norms, alpha, sums, counts, taus=taus, outlier_scope=prune.OUTLIERS_PER_LAYER)
+    _sync()
+    m32 = [host_metric_f32(w, nr) for w, nr in zip(ws_, norms)]
+    numel = sum(r * c for r, c in shapes)
+    tau = np.float32(taus[0].item())
+    assert (to_np(taus) == tau).all()
+    assert tau == orc.threshold_f32(alpha, float(np.sum(sums.tolist())), numel)
+    assert counts.tolist() == [orc.count_above(m, tau) for m in m32]            # bit-exact, kernel precision
+    omegas = [orc.weight_metric(to_np(w), to_np(nr).astype(np.float64)) for w, nr in zip(ws_, norms)]
+    c, o, r, mean, per_proj = orc.layer_outlier_stats(omegas, alpha)
+    assert abs(float(tau) - alpha * mean) <= 1e-6 * alpha * mean
+    band = sum(np.count_nonzero(np.abs(om - alpha * mean) <= 1e-5 * alpha * mean) for om in omegas)
+    assert abs(sum(counts.tolist()) - o) <= band
+    per = torch.zeros(n, dtype=torch.int64, device=DEV)
+    prune.score_outlier_batch(ws_, norms, alpha, sums, per, outlier_scope=prune.OUTLIERS_PER_PROJECTION)
+    _sync()
+    assert per.tolist() != counts.tolist()                                     # the two rules really differ here

@@ -76,15 +76,18 @@ def test_error_paths_return_before_any_launch(lib):
     sb = lib.prune_score_outlier_batch
     good = prune.Projection(0x1000, 8, 8, 8, 0x1000)
     arr = (prune.Projection * 1)(good)
-    assert sb(arr, 0, 1, 5.0, fake, fake, None, fake, 1 << 20, None) == E["shape"]
-    assert sb(None, 1, 1, 5.0, fake, fake, None, fake, 1 << 20, None) == E["null"]
-    assert sb(arr, 1, 1, -1.0, fake, fake, None, fake, 1 << 20, None) == E["rng"]
-    assert sb(arr, 1, 9, 5.0, fake, fake, None, fake, 1 << 20, None) == E["dtype"]
-    assert sb(arr, 1, 1, 5.0, fake, fake, None, fake, 8, None) == E["ws"]
+    assert sb(arr, 0, 1, 5.0, 0, fake, fake, None, fake, 1 << 20, None) == E["shape"]
+    assert sb(None, 1, 1, 5.0, 0, fake, fake, None, fake, 1 << 20, None) == E["null"]
+    assert sb(arr, 1, 1, -1.0, 0, fake, fake, None, fake, 1 << 20, None) == E["rng"]
+    assert sb(arr, 1, 9, 5.0, 0, fake, fake, None, fake, 1 << 20, None) == E["dtype"]
+    assert sb(arr, 1, 1, 5.0, 0, fake, fake, None, fake, 8, None) == E["ws"]
+    assert sb(arr, 1, 1, 5.0, 7, fake, fake, None, fake, 1 << 20, None) == E["rng"]      # unknown outlier scope
+    many = (prune.Projection * 17)(*([good] * 17))
+    assert sb(many, 17, 1, 5.0, 1, fake, fake, None, fake, 1 << 20, None) == E["rng"]    # a layer has at most 16
     bad = (prune.Projection * 1)(prune.Projection(0x1000, 8, 8, 4, 0x1000))
-    assert sb(bad, 1, 1, 5.0, fake, fake, None, fake, 1 << 20, None) == E["shape"]
+    assert sb(bad, 1, 1, 5.0, 0, fake, fake, None, fake, 1 << 20, None) == E["shape"]
     bad = (prune.Projection * 1)(prune.Projection(0x1000, 8, 8, 8, None))
-    assert sb(bad, 1, 1, 5.0, fake, fake, None, fake, 1 << 20, None) == E["null"]
+    assert sb(bad, 1, 1, 5.0, 0, fake, fake, None, fake, 1 << 20, None) == E["null"]
     sm = lib.prune_select_mask
     assert sm(fake, fake, 1, 8, 8, 8, 8, fake, None, 9, None, None, 0, None) == E["rng"]   # k > cols
     assert sm(fake, fake, 1, 8, 8, 4, 8, fake, None, 1, None, None, 0, None) == E["shape"]

@@ -48,6 +48,31 @@ def test_hand_strictness(golden):
     assert orc.outlier_stats(omega, ex["alpha"] * (1 - 1e-12))[1] == omega.size
 
 
+def test_hand_layer_outliers(golden):
+    ex = golden["layer_outliers"]
+    omegas = [np.array(o, float) for o in ex["omegas"]]
+    for case in ex["cases"]:
+        c, o, r, mean, per_proj = orc.layer_outlier_stats(omegas, case["alpha"])
+        assert (c, o, per_proj) == (ex["C"], case["O"], case["per_projection"])
+        assert mean == pytest.approx(ex["mean"], rel=1e-14) and r == pytest.approx(100.0 * case["O"] / ex["C"])
+
+
+def test_layer_outliers_bruteforce_and_special_case():
+    rng = np.random.default_rng(31)
+    omegas = [np.abs(rng.standard_cauchy((5, 7))), np.abs(rng.standard_cauchy((3, 4))) * 10, np.abs(rng.standard_normal((6, 2)))]
+    vals = [float(v) for o in omegas for v in o.reshape(-1)]
+    mean = math.fsum(vals) / len(vals)
+    for alpha in (0.5, 1.0, 5.0):
+        c, o, r, m, per_proj = orc.layer_outlier_stats(omegas, alpha)
+        assert c == len(vals) and m == pytest.approx(mean, rel=1e-13)
+        assert o == sum(1 for v in vals if v > alpha * mean) == sum(per_proj)
+        assert per_proj == [sum(1 for v in om.reshape(-1) if v > alpha * mean) for om in omegas]
+        # a layer made of one projection is the projection rule
+        assert orc.layer_outlier_stats(omegas[:1], alpha)[:4] == orc.outlier_stats(omegas[0], alpha)
+    # the two rules differ when projections have different scales: the small-scale one has no layer outliers
+    assert orc.layer_outlier_stats(omegas, 5.0)[4][2] == 0 < orc.outlier_stats(omegas[2], 2.0)[1]
+
+
 def test_hand_row_selection(golden):
     ex = golden["row_selection"]
     omega, w = np.array(ex["omega"], float), np.array(ex["W"], float)
