@@ -236,6 +236,34 @@ int prune_struct_compact(const void *gate, const void *up, const void *down, int
                          int64_t hidden, uint32_t r, float *group_mag, int32_t *kept_idx, void *gate_out,
                          void *up_out, void *down_out, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * Structured removal of coupled groups that span several projections (Section
+ * 4.1.3, categories 2 and 3: attention heads and feed-forward channels; Fig. 4:
+ * nodes between projections pruned as a group).  Group g < n_groups owns
+ *   rows [g * row_per[i], (g + 1) * row_per[i])  of row_mats[i]  ([n_groups * row_per[i], row_width[i]])
+ *   cols [g * col_per[i], (g + 1) * col_per[i])  of col_mats[i]  ([col_height[i], n_groups * col_per[i]])
+ * e.g. one group per key/value head of grouped-query attention: rows of q (all
+ * query heads of the group), k and v as row matrices, columns of o as a column
+ * matrix; or one feed-forward channel: gate and up rows, down column.
+ *   group_mag[g] = sum of squares of everything group g owns
+ * The r groups of lowest magnitude are removed (lower g first among equals);
+ * kept_idx gets the other n_groups - r indices ascending; when row_outs and
+ * col_outs are given, row_outs[i] = the kept groups' rows of row_mats[i] and
+ * col_outs[i] = the kept groups' columns of col_mats[i], in kept order.
+ * The pointer arrays and the extent arrays are HOST arrays of n_row (n_col)
+ * entries, at most 8 each; the matrices, group_mag, kept_idx and outputs are
+ * contiguous device buffers that do not overlap.  Pass both output arrays or
+ * neither (rank only).  0 <= r < n_groups.
+ * ws_bytes >= prune_struct_groups_workspace_bytes(same extents).
+ */
+size_t prune_struct_groups_workspace_bytes(const int64_t *row_per, const int64_t *row_width, int n_row,
+                                           const int64_t *col_per, const int64_t *col_height, int n_col,
+                                           int64_t n_groups);
+int prune_struct_groups(const void *const *row_mats, const int64_t *row_per, const int64_t *row_width, int n_row,
+                        const void *const *col_mats, const int64_t *col_per, const int64_t *col_height, int n_col,
+                        int dtype, int64_t n_groups, uint32_t r, float *group_mag, int32_t *kept_idx,
+                        void *const *row_outs, void *const *col_outs, void *ws, size_t ws_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -41,6 +41,9 @@ Parity status of each function:
                                    "lowest-magnitude" groups); pinned by brute force and
                                    by the dense-equivalence invariant
   struct_compact                   pinned (dense-equivalence of the MLP, exact gather)
+  coupled_group_magnitude          PARITY UNPINNED against the paper (same gap as group_magnitude); pinned by
+                                   brute force and by reducing to group_magnitude for one-row / one-column groups
+  coupled_group_compact            pinned (dense-equivalence of grouped-query attention, exact gather)
 """
 from __future__ import annotations
 
@@ -243,6 +246,40 @@ def struct_compact(gate, up, down, kept_idx):
     return (np.asarray(gate)[kept_idx, :].copy(),
             np.asarray(up)[kept_idx, :].copy(),
             np.asarray(down)[:, kept_idx].copy())
+
+
+def coupled_group_magnitude(row_mats, row_per, col_mats, col_per, n_groups: int) -> np.ndarray:
+    """Magnitude of groups that span several matrices (attention heads, feed-forward channels).
+
+    Group g owns rows [g * row_per[i], (g + 1) * row_per[i]) of row_mats[i] and columns
+    [g * col_per[i], (g + 1) * col_per[i]) of col_mats[i]; its magnitude is the sum of squares of
+    all of them.  With one row per group in gate and up and one column in down this is
+    group_magnitude(); with grouped-query attention a group is one key/value head: its k and v
+    rows, the q rows of the query heads that share it, and the matching columns of o.
+    """
+    g = np.zeros(n_groups, dtype=np.float64)
+    for m, per in zip(row_mats, row_per):
+        m = _f64(m)
+        assert m.shape[0] == n_groups * per
+        g += (m * m).sum(axis=1).reshape(n_groups, per).sum(axis=1)
+    for m, per in zip(col_mats, col_per):
+        m = _f64(m)
+        assert m.shape[1] == n_groups * per
+        g += (m * m).sum(axis=0).reshape(n_groups, per).sum(axis=1)
+    return g
+
+
+def coupled_group_compact(row_mats, row_per, col_mats, col_per, kept_idx):
+    """Keep only what the kept groups own: their rows of every row matrix, their columns of every column matrix."""
+    kept_idx = np.asarray(kept_idx, dtype=np.int64)
+    rows_out, cols_out = [], []
+    for m, per in zip(row_mats, row_per):
+        idx = (kept_idx[:, None] * per + np.arange(per)[None, :]).reshape(-1)
+        rows_out.append(np.asarray(m)[idx, :].copy())
+    for m, per in zip(col_mats, col_per):
+        idx = (kept_idx[:, None] * per + np.arange(per)[None, :]).reshape(-1)
+        cols_out.append(np.asarray(m)[:, idx].copy())
+    return rows_out, cols_out
 
 
 # --------------------------------------------------------------------------- whole path

@@ -198,5 +198,6 @@ size_t score_workspace_bytes(int64_t rows, int64_t cols);
 size_t select_workspace_bytes(int64_t rows, int64_t cols);
 size_t struct_workspace_bytes(int64_t inter, int64_t hidden);
 size_t rank_batch_workspace_bytes();
+int launch_rank_groups(const float *group_mag, int64_t n, uint32_t r, int32_t *kept_idx, hipStream_t stream);
 
 }  // namespace mp

@@ -115,6 +115,17 @@ __global__ __launch_bounds__(kBlock) void gather_cols(const T *__restrict__ src,
     for (int64_t i = i0; i < i1; ++i) dst[i * n_kept + n] = src[i * src_cols + c];
 }
 
+}  // namespace
+
+// kept_idx = ascending indices of the n - r groups left after dropping the r lowest magnitudes
+int launch_rank_groups(const float *group_mag, int64_t n, uint32_t r, int32_t *kept_idx, hipStream_t stream) {
+    hipLaunchKernelGGL(rank_channels, dim3(1), dim3(kRankBlock), 0, stream, group_mag, n, r, index_bits_for(n),
+                       kept_idx, n - static_cast<int64_t>(r));
+    return launch_status();
+}
+
+namespace {
+
 template <typename T>
 int struct_dispatch(const T *gate, const T *up, const T *down, int64_t inter, int64_t hidden, uint32_t r,
                     float *group_mag, int32_t *kept_idx, T *gate_out, T *up_out, T *down_out, void *ws,
@@ -131,9 +142,7 @@ int struct_dispatch(const T *gate, const T *up, const T *down, int64_t inter, in
     int st = launch_colsum(down, dtype, hidden, inter, inter, group_mag, ws, stream);
     if (st != PRUNE_OK) return st;
 
-    hipLaunchKernelGGL(rank_channels, dim3(1), dim3(kRankBlock), 0, stream, group_mag, inter, r,
-                       index_bits_for(inter), kept_idx, inter - static_cast<int64_t>(r));
-    if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
+    if (launch_rank_groups(group_mag, inter, r, kept_idx, stream) != PRUNE_OK) return PRUNE_ERR_DEVICE;
     if (!gate_out) return PRUNE_OK;
 
     const int64_t n_kept = inter - r;

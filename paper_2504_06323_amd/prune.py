@@ -41,6 +41,9 @@ _SIGNATURES = {
     "prune_plan_sparsity": (_int, [_vp, _vp, _vp, _int, _int, _f64, _f64, _int, _vp, _vp, _vp]),
     "prune_select_mask": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _i64, _vp, _vp, _u32, _vp, _vp, _sz, _vp]),
     "prune_select_mask_batch": (_int, [_vp, _int, _int, _vp, _sz, _vp]),
+    "prune_struct_groups_workspace_bytes": (_sz, [_vp, _vp, _int, _vp, _vp, _int, _i64]),
+    "prune_struct_groups": (_int, [_vp, _vp, _vp, _int, _vp, _vp, _vp, _int, _int, _i64, _u32, _vp, _vp, _vp, _vp,
+                                   _vp, _sz, _vp]),
     "prune_struct_compact": (_int, [_vp, _vp, _vp, _int, _i64, _i64, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
 }
 
@@ -344,3 +347,52 @@ def struct_compact(gate: torch.Tensor, up: torch.Tensor, down: torch.Tensor, r: 
                                        hidden, int(r), _vector(group_mag, "group_mag", torch.float32, inter),
                                        _vector(kept_idx, "kept_idx", torch.int32, n_kept), outs[0], outs[1], outs[2],
                                        ws_ptr, ws_bytes, _stream(stream)))
+
+
+def struct_groups(row_mats: Sequence[torch.Tensor], row_per: Sequence[int], col_mats: Sequence[torch.Tensor],
+                  col_per: Sequence[int], n_groups: int, r: int, group_mag: torch.Tensor, kept_idx: torch.Tensor,
+                  row_outs: Optional[Sequence[torch.Tensor]] = None,
+                  col_outs: Optional[Sequence[torch.Tensor]] = None, ws: Optional[torch.Tensor] = None,
+                  stream=None) -> None:
+    """Rank coupled groups spanning several matrices, drop the r lowest, gather the rest (prune_struct_groups).
+
+    Group g owns row_per[i] consecutive rows of row_mats[i] and col_per[i] consecutive columns of col_mats[i]."""
+    mats = list(row_mats) + list(col_mats)
+    if not mats:
+        raise ValueError("need at least one matrix")
+    dt = mats[0].dtype
+    for t in mats:
+        if not (t.is_cuda and t.is_contiguous() and t.dim() == 2 and t.dtype == dt):
+            raise ValueError("matrices must be contiguous 2-D GPU tensors of one dtype")
+    n_row, n_col, n_kept = len(row_mats), len(col_mats), n_groups - int(r)
+    for t, per in zip(row_mats, row_per):
+        if t.shape[0] != n_groups * per:
+            raise ValueError("a row-grouped matrix needs n_groups * rows_per_group rows")
+    for t, per in zip(col_mats, col_per):
+        if t.shape[1] != n_groups * per:
+            raise ValueError("a column-grouped matrix needs n_groups * cols_per_group columns")
+    want_out = row_outs is not None or col_outs is not None
+    if want_out:
+        row_outs, col_outs = list(row_outs or []), list(col_outs or [])
+        if len(row_outs) != n_row or len(col_outs) != n_col:
+            raise ValueError("one output per matrix, or none at all")
+        for t, src, per in zip(row_outs, row_mats, row_per):
+            if not (t.is_cuda and t.is_contiguous() and t.dtype == dt and tuple(t.shape) == (n_kept * per, src.shape[1])):
+                raise ValueError("row output must be [kept groups * rows_per_group, width]")
+        for t, src, per in zip(col_outs, col_mats, col_per):
+            if not (t.is_cuda and t.is_contiguous() and t.dtype == dt and tuple(t.shape) == (src.shape[0], n_kept * per)):
+                raise ValueError("column output must be [height, kept groups * cols_per_group]")
+    ptrs = lambda ts: (_vp * max(len(ts), 1))(*[t.data_ptr() for t in ts])
+    ints = lambda vs: (_i64 * max(len(vs), 1))(*[int(v) for v in vs])
+    c_row_per, c_row_w = ints(row_per), ints([t.shape[1] for t in row_mats])
+    c_col_per, c_col_h = ints(col_per), ints([t.shape[0] for t in col_mats])
+    need = int(load().prune_struct_groups_workspace_bytes(c_row_per, c_row_w, n_row, c_col_per, c_col_h, n_col,
+                                                          n_groups))
+    ws_ptr, ws_bytes, _keep = _workspace(ws, need, mats[0].device)
+    _check("prune_struct_groups",
+           load().prune_struct_groups(ptrs(row_mats), c_row_per, c_row_w, n_row, ptrs(col_mats), c_col_per, c_col_h,
+                                      n_col, _dtype_code(mats[0]), n_groups, int(r),
+                                      _vector(group_mag, "group_mag", torch.float32, n_groups),
+                                      _vector(kept_idx, "kept_idx", torch.int32, n_kept),
+                                      ptrs(row_outs) if want_out else None, ptrs(col_outs) if want_out else None,
+                                      ws_ptr, ws_bytes, _stream(stream)))

@@ -129,6 +129,27 @@ def _run_layer(cfg_name, check_struct=True):
     wg, wu, wd = orc.struct_compact(masked["gate"], masked["up"], masked["down"], kept)
     assert np.array_equal(to_np(res.gate), wg) and np.array_equal(to_np(res.up), wu)
     assert np.array_equal(to_np(res.down), wd)
+    # attention block: one group per key/value head (head width 128) with the query heads that share it
+    d = 128
+    n_groups, m = cfg.kv_out // d, cfg.q_out // cfg.kv_out
+    r_att = max(1, int(cfg.struct_frac * n_groups))
+    print(f"[fullsize] {cfg_name}: removing {r_att} of {n_groups} key/value heads ({m} query heads each)", flush=True)
+    rows = [st.pruned["q"], st.pruned["k"], st.pruned["v"]]
+    row_per, cols, col_per = [m * d, d, d], [st.pruned["o"]], [m * d]
+    gm = torch.empty(n_groups, dtype=torch.float32, device=DEV)
+    kp = torch.empty(n_groups - r_att, dtype=torch.int32, device=DEV)
+    row_outs = [torch.empty(((n_groups - r_att) * p, t.shape[1]), dtype=t.dtype, device=DEV) for t, p in zip(rows, row_per)]
+    col_outs = [torch.empty((cols[0].shape[0], (n_groups - r_att) * m * d), dtype=cols[0].dtype, device=DEV)]
+    prune.struct_groups(rows, row_per, cols, col_per, n_groups, r_att, gm, kp, row_outs, col_outs)
+    torch.cuda.synchronize()
+    rm, cm = [to_np(t) for t in rows], [to_np(t) for t in cols]
+    want = orc.coupled_group_magnitude(rm, row_per, cm, col_per, n_groups)
+    assert rel_err(to_np(gm), want) < 1e-2 and rel_err(to_np(gm), want) < 5e-6
+    kept_att = orc.struct_rank(to_np(gm), r_att)
+    assert np.array_equal(to_np(kp), kept_att)
+    wr, wc = orc.coupled_group_compact(rm, row_per, cm, col_per, kept_att)
+    for got, ref in zip(row_outs + col_outs, wr + wc):
+        assert np.array_equal(to_np(got), ref)
 
 
 def test_llama7b_layer_bench_configuration(lib):

@@ -449,3 +449,67 @@ def test_layer_scope_outliers_vs_oracle(lib, dtype, aligned):
     prune.score_outlier_batch(ws_, norms, alpha, sums, per, outlier_scope=prune.OUTLIERS_PER_PROJECTION)
     _sync()
     assert per.tolist() != counts.tolist()                                     # the two rules really differ here
+
+
+# ----------------------------------------------------------------- coupled groups (attention heads, grouped queries)
+
+def _check_groups(row_mats, row_per, col_mats, col_per, n_groups, r, compact=True):
+    g = torch.empty(n_groups, dtype=torch.float32, device=DEV)
+    kept = torch.full((n_groups - r,), -1, dtype=torch.int32, device=DEV)
+    row_outs = col_outs = None
+    if compact:
+        row_outs = [torch.full(((n_groups - r) * p, m.shape[1]), 7.0, dtype=m.dtype, device=DEV)
+                    for m, p in zip(row_mats, row_per)]
+        col_outs = [torch.full((m.shape[0], (n_groups - r) * p), 7.0, dtype=m.dtype, device=DEV)
+                    for m, p in zip(col_mats, col_per)]
+    prune.struct_groups(row_mats, row_per, col_mats, col_per, n_groups, r, g, kept, row_outs, col_outs)
+    _sync()
+    rm, cm = [to_np(m) for m in row_mats], [to_np(m) for m in col_mats]
+    want_g = orc.coupled_group_magnitude(rm, row_per, cm, col_per, n_groups)
+    nz = want_g > 0
+    assert rel_err(to_np(g)[nz], want_g[nz]) < tol_for(row_mats[0].dtype if row_mats else col_mats[0].dtype)
+    assert rel_err(to_np(g)[nz], want_g[nz]) < 5e-6 and (to_np(g)[~nz] == 0).all()
+    want_kept = orc.struct_rank(to_np(g), r)                      # oracle ranking on the kernel's magnitudes
+    assert np.array_equal(to_np(kept), want_kept)
+    if compact:
+        wr, wc = orc.coupled_group_compact(rm, row_per, cm, col_per, want_kept)
+        for got, want in zip(row_outs + col_outs, wr + wc):
+            assert np.array_equal(to_np(got), want)
+    return to_np(g), to_np(kept)
+
+
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("case", ["gqa", "mha_ragged", "mlp", "rows_only", "cols_only"])
+def test_struct_groups_vs_oracle(lib, dtype, case):
+    mk = lambda r, c, s: synth.random_matrix(r, c, dtype, seed=s, device=DEV, scale=0.02, zero_frac=0.2)
+    if case == "gqa":            # 8 key/value heads, 4 query heads each, head width 16, hidden 256
+        n_groups, m, d, hidden = 8, 4, 16, 256
+        rows, row_per = [mk(n_groups * m * d, hidden, 1), mk(n_groups * d, hidden, 2), mk(n_groups * d, hidden, 3)], [m * d, d, d]
+        cols, col_per = [mk(hidden, n_groups * m * d, 4)], [m * d]
+    elif case == "mha_ragged":   # head width 5, hidden 37: nothing is packet-aligned
+        n_groups, d, hidden = 6, 5, 37
+        rows, row_per = [mk(n_groups * d, hidden, 5), mk(n_groups * d, hidden, 6), mk(n_groups * d, hidden, 7)], [d, d, d]
+        cols, col_per = [mk(hidden, n_groups * d, 8)], [d]
+    elif case == "mlp":          # one row / one column per group: the feed-forward channel case
+        n_groups, hidden = 688, 256
+        rows, row_per = [mk(n_groups, hidden, 9), mk(n_groups, hidden, 10)], [1, 1]
+        cols, col_per = [mk(hidden, n_groups, 11)], [1]
+    elif case == "rows_only":
+        n_groups = 10
+        rows, row_per, cols, col_per = [mk(n_groups * 3, 64, 12)], [3], [], []
+    else:
+        n_groups = 10
+        rows, row_per, cols, col_per = [], [], [mk(48, n_groups * 8, 13)], [8]
+    if rows:
+        rows[0][:row_per[0]] = 0     # make group 0 weaker so the ranking is not trivial
+    for r in sorted({0, 1, n_groups // 4, n_groups - 1}):
+        _check_groups(rows, row_per, cols, col_per, n_groups, r)
+    g1, k1 = _check_groups(rows, row_per, cols, col_per, n_groups, n_groups // 2, compact=False)
+    g2, k2 = _check_groups(rows, row_per, cols, col_per, n_groups, n_groups // 2, compact=False)
+    assert np.array_equal(g1.view(np.uint32), g2.view(np.uint32)) and np.array_equal(k1, k2)
+    if case == "mlp":            # the dedicated feed-forward entry point agrees with the generic one
+        gm = torch.empty(n_groups, dtype=torch.float32, device=DEV)
+        kp = torch.empty(n_groups - n_groups // 2, dtype=torch.int32, device=DEV)
+        prune.struct_compact(rows[0], rows[1], cols[0], n_groups // 2, gm, kp)
+        _sync()
+        assert np.array_equal(to_np(kp), k1) and rel_err(to_np(gm), g1) < 1e-6

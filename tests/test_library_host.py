@@ -113,6 +113,25 @@ def test_error_paths_return_before_any_launch(lib):
     assert st(fake, fake, fake, 1, 8, 8, 1, fake, fake, fake, None, None, fake, 1 << 20, None) == E["null"]  # 1 of 3 outs
     assert st(fake, fake, fake, 1, 8, 8, 1, fake, fake, None, None, None, fake, 0, None) == E["ws"]
     assert st(fake, fake, None, 1, 8, 8, 1, fake, fake, None, None, None, fake, 1 << 20, None) == E["null"]
+    sg = lib.prune_struct_groups
+    P = lambda *v: (ctypes.c_void_p * len(v))(*v)
+    I = lambda *v: (ctypes.c_int64 * len(v))(*v)
+    ok = dict(rm=P(0x1000), rp=I(2), rw=I(8), nr=1, cm=P(0x1000), cp=I(2), ch=I(8), nc=1)
+    call = lambda dt=1, ng=4, r=1, gm=fake, kp=fake, ro=None, co=None, w=fake, wb=1 << 20, **kw: sg(
+        *[{**ok, **kw}[k] for k in ("rm", "rp", "rw", "nr", "cm", "cp", "ch", "nc")], dt, ng, r, gm, kp, ro, co, w, wb,
+        None)
+    assert call(dt=6) == E["dtype"]
+    assert call(ng=0) == E["shape"]
+    assert call(nr=9) == E["shape"]
+    assert call(nr=0, nc=0) == E["shape"]
+    assert call(r=4) == E["rng"]
+    assert call(gm=None) == E["null"]
+    assert call(rm=P(None)) == E["null"]
+    assert call(rp=I(0)) == E["shape"]
+    assert call(ro=P(0x2000)) == E["null"]                                        # row outputs without column outputs
+    assert call(wb=16) == E["ws"]
+    assert lib.prune_struct_groups_workspace_bytes(I(2), I(8), 1, I(2), I(8), 1, 4) >= (8 + 8) * 4
+    assert lib.prune_struct_groups_workspace_bytes(I(0), I(8), 1, None, None, 0, 4) == 0
     with pytest.raises(prune.PruneError):
         prune.plan_sparsity([1], [10], 1, 1, 1.0, 0.08)                         # p must be < 1
     with pytest.raises(prune.PruneError):

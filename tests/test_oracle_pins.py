@@ -347,3 +347,65 @@ def test_composite_order_on_masked_weights():
     g_before = orc.group_magnitude(gate, up, down)
     assert (g_after <= g_before + 1e-15).all() and (g_after < g_before).any()
     assert (dm[:, 4] == 0).all()
+
+
+# ----------------------------------------------------------------- coupled groups (attention heads)
+
+def _gqa_attention(q, k, v, o, x, n_groups, heads_per_group, d):
+    """Grouped-query attention on a token sequence x [T, hidden] (float64, no masking)."""
+    t = x.shape[0]
+    out = np.zeros((t, o.shape[0]))
+    for g in range(n_groups):
+        kg, vg = x @ k[g * d:(g + 1) * d].T, x @ v[g * d:(g + 1) * d].T
+        for j in range(heads_per_group):
+            h = g * heads_per_group + j
+            qh = x @ q[h * d:(h + 1) * d].T
+            a = qh @ kg.T / math.sqrt(d)
+            a = np.exp(a - a.max(axis=1, keepdims=True))
+            a /= a.sum(axis=1, keepdims=True)
+            out += (a @ vg) @ o[:, h * d:(h + 1) * d].T
+    return out
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_coupled_groups_bruteforce_and_dense_equivalence(seed):
+    rng = np.random.default_rng(300 + seed)
+    n_groups, m, d, hidden = 4, 2, 3, 10                     # 4 key/value heads, 8 query heads of width 3
+    q = rng.standard_normal((n_groups * m * d, hidden))
+    k, v = rng.standard_normal((n_groups * d, hidden)), rng.standard_normal((n_groups * d, hidden))
+    o = rng.standard_normal((hidden, n_groups * m * d))
+    row_per, col_per = [m * d, d, d], [m * d]
+    g = orc.coupled_group_magnitude([q, k, v], row_per, [o], col_per, n_groups)
+    for grp in range(n_groups):
+        brute = 0.0
+        for mat, per in zip([q, k, v], row_per):
+            for i in range(grp * per, (grp + 1) * per):
+                brute += sum(float(val) ** 2 for val in mat[i])
+        for j in range(grp * m * d, (grp + 1) * m * d):
+            brute += sum(float(o[i, j]) ** 2 for i in range(hidden))
+        assert g[grp] == pytest.approx(brute, rel=1e-13)
+    r = 1
+    kept = orc.struct_rank(g, r)
+    removed = [grp for grp in range(n_groups) if grp not in kept.tolist()]
+    assert removed == [int(np.argmin(g))]
+    (q2, k2, v2), (o2,) = orc.coupled_group_compact([q, k, v], row_per, [o], col_per, kept)
+    assert q2.shape == ((n_groups - r) * m * d, hidden) and o2.shape == (hidden, (n_groups - r) * m * d)
+    # removing a key/value head with its query heads equals zeroing their o columns in the full block
+    oz = o.copy()
+    for grp in removed:
+        oz[:, grp * m * d:(grp + 1) * m * d] = 0
+    x = rng.standard_normal((5, hidden))
+    np.testing.assert_allclose(_gqa_attention(q2, k2, v2, o2, x, n_groups - r, m, d),
+                               _gqa_attention(q, k, v, oz, x, n_groups, m, d), rtol=1e-12, atol=1e-12)
+
+
+def test_coupled_groups_reduce_to_mlp_channels():
+    rng = np.random.default_rng(17)
+    inter, hidden = 13, 6
+    gate, up, down = rng.standard_normal((inter, hidden)), rng.standard_normal((inter, hidden)), rng.standard_normal((hidden, inter))
+    np.testing.assert_allclose(orc.coupled_group_magnitude([gate, up], [1, 1], [down], [1], inter),
+                               orc.group_magnitude(gate, up, down), rtol=1e-14)
+    kept = np.array([0, 3, 4, 12])
+    (g2, u2), (d2,) = orc.coupled_group_compact([gate, up], [1, 1], [down], [1], kept)
+    wg, wu, wd = orc.struct_compact(gate, up, down, kept)
+    assert np.array_equal(g2, wg) and np.array_equal(u2, wu) and np.array_equal(d2, wd)
