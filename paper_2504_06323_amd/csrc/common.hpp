@@ -57,6 +57,11 @@ struct Packet<bf16_t, 8> {
             raw[i] &= m;
         }
     }
+    // the same with one all-ones / all-zeros word per element
+    __device__ __forceinline__ void apply_keep_words(const uint32_t (&km)[8]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) raw[i] &= (km[2 * i] & 0x0000ffffu) | (km[2 * i + 1] & 0xffff0000u);
+    }
 };
 
 template <>
@@ -81,6 +86,10 @@ struct Packet<float, 8> {
 #pragma unroll
         for (int i = 0; i < 8; ++i)
             if (!((keep >> i) & 1u)) raw[i >> 2][i & 3] = 0u;
+    }
+    __device__ __forceinline__ void apply_keep_words(const uint32_t (&km)[8]) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) raw[i >> 2][i & 3] &= km[i];
     }
 };
 

@@ -21,31 +21,38 @@ __device__ __forceinline__ void select_one_row(const T *wrow, T *orow, uint32_t 
                                                uint32_t k, int idx_bits, uint8_t *__restrict__ mrow,
                                                uint32_t mask_row_bytes, SelectSmem<BLOCK> &sm) {
     const uint32_t tid = threadIdx.x;
+    // clear the histogram first: the stores overlap the latency of the row's loads below
+    if (k < cols)
+        for (int b = tid; b < kSelBins; b += BLOCK) sm.hist[b] = 0u;
+    // All loads of the row are issued before anything waits on them.  A packet past the end of a
+    // ragged row re-reads packet 0 (always valid) and is ignored later, so no load sits behind a branch.
     Packet<T, 8> pk[NCHUNK];
+#pragma unroll
+    for (int c = 0; c < NCHUNK; ++c) {
+        const uint32_t col0 = (c * BLOCK + tid) * 8;
+        pk[c].load(wrow + (col0 < cols ? col0 : 0u));
+    }
     uint32_t key[NCHUNK][8];
 #pragma unroll
     for (int c = 0; c < NCHUNK; ++c) {
         const uint32_t col0 = (c * BLOCK + tid) * 8;
-        if (col0 < cols) {
-            pk[c].template load<true>(wrow + col0);
-            float om[8];
-            if (FROM_SCORES) {
-                load_floats(srow + col0, om);
-            } else {
-                float v[8], nrm[8];
-                pk[c].to_float(v);
-                load_floats(norms + col0, nrm);
+        float aux[8];  // the norms of this packet's columns, or the row's precomputed scores
+        load_floats((FROM_SCORES ? srow : norms) + (col0 < cols ? col0 : 0u), aux);
+        if (FROM_SCORES) {
+            // scores handed in by a caller get the sign bit cleared
 #pragma unroll
-                for (int e = 0; e < 8; ++e) om[e] = metric(v[e], nrm[e]);
-            }
+            for (int e = 0; e < 8; ++e) key[c][e] = key_of(aux[e]);
+        } else {
+            // a metric recomputed here is |w| * norm: non-negative, its bits are the key
+            float v[8];
+            pk[c].to_float(v);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) key[c][e] = key_of(om[e]);
+            for (int e = 0; e < 8; ++e) key[c][e] = __float_as_uint(metric(v[e], aux[e]));
         }
     }
 
     SelectBound bound = {0xffffffffu, 0xffffffffu};  // k == cols: everything goes
     if (k < cols) {
-        for (int b = tid; b < kSelBins; b += BLOCK) sm.hist[b] = 0u;
         __syncthreads();
         bound = block_select_bound<BLOCK>(
             [&](auto f, uint32_t salt) {
@@ -62,19 +69,27 @@ __device__ __forceinline__ void select_one_row(const T *wrow, T *orow, uint32_t 
     }
 
     const bool whole_bins = bound.idx == 0xffffffffu;  // uniform: no tie to split by column
+    const bool everything = k >= cols;                  // uniform: the whole row goes
 #pragma unroll
     for (int c = 0; c < NCHUNK; ++c) {
         const uint32_t col0 = (c * BLOCK + tid) * 8;
         if (col0 < cols) {
             uint32_t keep = 0;
             if (whole_bins) {
+                // key > bound  <=>  bound - key is negative (keys and bound are below 2^31, or a NaN key
+                // with bit 31, which then counts as kept): the sign, spread over the word, is the mask
+                uint32_t km[8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) keep |= (key[c][e] > bound.key ? 1u : 0u) << e;
+                for (int e = 0; e < 8; ++e) {
+                    km[e] = everything ? 0u : static_cast<uint32_t>(static_cast<int32_t>(bound.key - key[c][e]) >> 31);
+                    keep |= km[e] & (1u << e);
+                }
+                pk[c].apply_keep_words(km);
             } else {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) keep |= (is_selected(key[c][e], col0 + e, bound) ? 0u : 1u) << e;
+                pk[c].apply_keep(keep);
             }
-            pk[c].apply_keep(keep);
             pk[c].store(orow + col0);
             if (mrow) {
                 mrow[col0 >> 3] = static_cast<uint8_t>(keep);
@@ -86,7 +101,7 @@ __device__ __forceinline__ void select_one_row(const T *wrow, T *orow, uint32_t 
 }
 
 template <typename T, int BLOCK, int NCHUNK, bool FROM_SCORES>
-__global__ __launch_bounds__(BLOCK, 4) void select_rows_vec(const T *w, T *w_out, uint32_t cols, int64_t ld,
+__global__ __launch_bounds__(BLOCK, (BLOCK == 64 ? 4 : NCHUNK <= 3 ? 8 : 6)) void select_rows_vec(const T *w, T *w_out, uint32_t cols, int64_t ld,
                                                             int64_t ld_out, const float *__restrict__ norms,
                                                             const float *__restrict__ scores, uint32_t k,
                                                             int idx_bits, uint8_t *__restrict__ mask_bytes,
@@ -119,7 +134,7 @@ struct SelectArgs {
 };
 
 template <typename T, int BLOCK, int NCHUNK>
-__global__ __launch_bounds__(BLOCK, 4) void select_rows_batch(const SelectArgs args) {
+__global__ __launch_bounds__(BLOCK, (BLOCK == 64 ? 4 : NCHUNK <= 3 ? 8 : 6)) void select_rows_batch(const SelectArgs args) {
     __shared__ SelectSmem<BLOCK> sm;
     int p = 0;
     for (int i = 1; i < args.n; ++i)
