@@ -101,6 +101,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="llama7b_layer")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--host-plan", action="store_true",
+                    help="run the projection planner on the host (the step then waits for the outlier counts)")
     ap.add_argument("--cpu-sample-den", type=int, default=2)
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the warm-up, run a plain float32 copy kernel (read N MiB, write N MiB) three "
@@ -163,8 +165,12 @@ def main():
                                   st.count, taus=st.tau, ws=st.ws)
         if record:
             marks[2].record()
-        counts = st.count.tolist()          # 7 integers cross to the host: the planner needs every ratio
-        _, ks, _ = pipeline.plan(counts, numels, cols, 1, len(shapes), cfg.p, cfg.lam)
+        if args.host_plan:
+            counts = st.count.tolist()      # 7 integers cross to the host, the step waits for them
+            _, ks, _ = pipeline.plan(counts, numels, cols, 1, len(shapes), cfg.p, cfg.lam)
+        else:
+            counts = ks = None              # the planner runs on the device, behind the ranking
+            pipeline.plan_device(st, cfg.p, cfg.lam)
         # phase 2: pruning
         pipeline.prune_layer(st, ks)
         if record:
@@ -191,6 +197,12 @@ def main():
         counts, ks = step(True)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+
+    if not args.host_plan:   # read the plan back once, after the clock has stopped, and hold it against the host planner
+        counts, ks = st.count.tolist(), st.ks_dev.tolist()
+        _, ks_host, _ = pipeline.plan(counts, numels, cols, 1, len(shapes), cfg.p, cfg.lam)
+        if ks != ks_host or st.plan_flags.tolist()[1] != 0:
+            raise RuntimeError(f"device plan {ks} differs from host plan {ks_host}")
 
     ms_per_step = 1e3 * elapsed / args.steps
     ab = algorithmic_bytes(cfg, shapes, act_shapes, r)

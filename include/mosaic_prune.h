@@ -181,6 +181,23 @@ int prune_plan_sparsity(const unsigned long long *counts, const unsigned long lo
                         uint32_t *zeros_per_row_out, int *clamped_out);
 
 /*
+ * prune_plan_sparsity computed on the device (same arithmetic, same order of
+ * operations, so the same bits), for callers that must not wait for the
+ * outlier counts on the host: the counts stay where prune_score_outlier_batch
+ * wrote them and the zeros-per-row land where prune_select_mask_batch can read
+ * them (prune_select_item.k_dev).
+ * DEVICE arrays of n_layers * n_proj entries: counts, numels (uint64), cols
+ * (int64, required), sparsity_out (double), zeros_per_row_out (uint32).
+ * flags_out: DEVICE int[2]; [0] = 1 iff some target was clamped, else 0;
+ * [1] = 1 iff an input was invalid (numel == 0, count > numel, cols <= 0), in
+ * which case the other outputs are unspecified, else 0.
+ * One small launch on `stream`; returns once it is enqueued.  n_layers * n_proj <= 1048576.
+ */
+int prune_plan_sparsity_device(const unsigned long long *counts, const unsigned long long *numels,
+                               const int64_t *cols, int n_layers, int n_proj, double p, double lambda, int scope,
+                               double *sparsity_out, uint32_t *zeros_per_row_out, int *flags_out, void *stream);
+
+/*
  * Unstructured projection pruning (Section 4.1.3, category 1: pruned
  * parameters are set to zero).  In every row the k entries with the smallest
  * omega are zeroed; among equal omega the lower column goes first, so the
@@ -196,7 +213,12 @@ int prune_select_mask(const void *w, void *w_out, int dtype, int64_t rows, int64
                       int64_t ld_out, const float *norms, const float *scores, uint32_t k, uint32_t *mask_bits, void *ws,
                       size_t ws_bytes, void *stream);
 
-/* One projection of a prune_select_mask_batch call; fields as the arguments of prune_select_mask. */
+/*
+ * One projection of a prune_select_mask_batch call; fields as the arguments of prune_select_mask.
+ * k_dev (nullable): DEVICE pointer to this projection's k, read by the kernels when they run (for
+ * example an element of prune_plan_sparsity_device's zeros_per_row_out); when set, the field k is
+ * ignored and a value above cols counts as cols.
+ */
 typedef struct {
     const void *w;
     void *w_out;
@@ -204,6 +226,7 @@ typedef struct {
     const float *norms;
     uint32_t k;
     uint32_t *mask_bits; /* nullable */
+    const uint32_t *k_dev; /* nullable */
 } prune_select_item;
 
 /*

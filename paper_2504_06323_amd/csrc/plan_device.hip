@@ -1,0 +1,129 @@
+// The projection planner (Algorithm 1's normalize(R_LLM) and the Projection
+// Planner of Section 3.3) as one small kernel, so that ranking, planning and
+// pruning can be enqueued back to back without the host ever reading the
+// outlier counts.  The arithmetic and its order are those of the host planner:
+// every per-projection expression is evaluated independently, the one sum (the
+// mean of the normalised ratios) is accumulated by a single thread in index
+// order, and min / max do not depend on order.
+#include "common.hpp"
+
+namespace mp {
+
+namespace {
+
+constexpr int kPlanBlock = 256;
+
+__device__ __forceinline__ double block_min_max(double v, bool take_max, double *scratch) {
+    const int tid = threadIdx.x;
+    scratch[tid] = v;
+    __syncthreads();
+    for (int s = kPlanBlock / 2; s > 0; s >>= 1) {
+        if (tid < s) {
+            const double a = scratch[tid], b = scratch[tid + s];
+            scratch[tid] = take_max ? fmax(a, b) : fmin(a, b);
+        }
+        __syncthreads();
+    }
+    const double out = scratch[0];
+    __syncthreads();
+    return out;
+}
+
+// One block.  Groups are the sets over which the ratios are normalised: all entries (n_groups == 1),
+// or, per projection type m, the entries l * n_proj + m (n_groups == n_proj).
+__global__ __launch_bounds__(kPlanBlock) void plan_kernel(const unsigned long long *__restrict__ counts,
+                                                          const unsigned long long *__restrict__ numels,
+                                                          const int64_t *__restrict__ cols, int n, int n_groups,
+                                                          double p, double lambda, double *__restrict__ sparsity,
+                                                          uint32_t *__restrict__ zeros_per_row,
+                                                          int *__restrict__ flags) {
+    __shared__ double scratch[kPlanBlock];
+    __shared__ double mean_sh;
+    __shared__ int clamped_sh, invalid_sh;
+    const int tid = threadIdx.x;
+    if (tid == 0) {
+        clamped_sh = 0;
+        invalid_sh = 0;
+    }
+    __syncthreads();
+    // R = O / C * 100, parked in the output array
+    for (int i = tid; i < n; i += kPlanBlock) {
+        const unsigned long long c = counts[i], e = numels[i];
+        if (e == 0 || c > e || cols[i] <= 0) invalid_sh = 1;
+        sparsity[i] = e ? 100.0 * static_cast<double>(c) / static_cast<double>(e) : 0.0;
+    }
+    __syncthreads();
+    const int per_group = n / n_groups;
+    for (int g = 0; g < n_groups; ++g) {
+        // entry j of group g sits at g + j * n_groups (n_groups == 1: all entries in order)
+        double lo = INFINITY, hi = -INFINITY;
+        for (int j = tid; j < per_group; j += kPlanBlock) {
+            const double r = sparsity[g + j * n_groups];
+            lo = fmin(lo, r);
+            hi = fmax(hi, r);
+        }
+        lo = block_min_max(lo, false, scratch);
+        hi = block_min_max(hi, true, scratch);
+        if (hi == lo) {
+            for (int j = tid; j < per_group; j += kPlanBlock) sparsity[g + j * n_groups] = p;
+            __syncthreads();
+            continue;
+        }
+        for (int j = tid; j < per_group; j += kPlanBlock) {
+            const int i = g + j * n_groups;
+            sparsity[i] = (sparsity[i] - lo) / (hi - lo);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            double mean_hat = 0.0;
+            for (int j = 0; j < per_group; ++j) mean_hat += sparsity[g + j * n_groups];
+            mean_sh = mean_hat / static_cast<double>(per_group);
+        }
+        __syncthreads();
+        const double mean_hat = mean_sh;
+        for (int j = tid; j < per_group; j += kPlanBlock) {
+            const int i = g + j * n_groups;
+            sparsity[i] = p + 2.0 * lambda * (mean_hat - sparsity[i]);
+        }
+        __syncthreads();
+    }
+    for (int i = tid; i < n; i += kPlanBlock) {
+        const double width = static_cast<double>(cols[i] > 0 ? cols[i] : 1);
+        const double hi = 1.0 - 1.0 / width;
+        const double s0 = sparsity[i];
+        double s = s0;
+        if (s < 0.0) s = 0.0;
+        if (s > hi) s = hi;
+        if (s != s0) clamped_sh = 1;
+        sparsity[i] = s;
+        zeros_per_row[i] = static_cast<uint32_t>(floor(s * width));
+    }
+    __syncthreads();
+    if (tid == 0) {
+        flags[0] = clamped_sh;
+        flags[1] = invalid_sh;
+    }
+}
+
+}  // namespace
+
+}  // namespace mp
+
+extern "C" int prune_plan_sparsity_device(const unsigned long long *counts, const unsigned long long *numels,
+                                          const int64_t *cols, int n_layers, int n_proj, double p, double lambda,
+                                          int scope, double *sparsity_out, uint32_t *zeros_per_row_out, int *flags_out,
+                                          void *stream_) {
+    using namespace mp;
+    if (!counts || !numels || !cols || !sparsity_out || !zeros_per_row_out || !flags_out) return PRUNE_ERR_NULL;
+    if (n_layers <= 0 || n_proj <= 0 || static_cast<int64_t>(n_layers) * n_proj > (1 << 20)) return PRUNE_ERR_SHAPE;
+    if (!(p >= 0.0 && p < 1.0) || !(lambda >= 0.0)) return PRUNE_ERR_RANGE;
+    if (scope != PRUNE_SCOPE_GLOBAL && scope != PRUNE_SCOPE_CATEGORY) return PRUNE_ERR_RANGE;
+    if (!aligned_to(counts, 8) || !aligned_to(numels, 8) || !aligned_to(cols, 8) || !aligned_to(sparsity_out, 8) ||
+        !aligned_to(zeros_per_row_out, 4) || !aligned_to(flags_out, 4))
+        return PRUNE_ERR_ALIGNMENT;
+    const int n = n_layers * n_proj;
+    const int n_groups = scope == PRUNE_SCOPE_GLOBAL ? 1 : n_proj;
+    hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanBlock), 0, static_cast<hipStream_t>(stream_), counts, numels,
+                       cols, n, n_groups, p, lambda, sparsity_out, zeros_per_row_out, flags_out);
+    return launch_status();
+}

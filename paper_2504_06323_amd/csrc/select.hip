@@ -21,8 +21,11 @@ __device__ __forceinline__ void select_one_row(const T *wrow, T *orow, uint32_t 
                                                uint32_t k, int idx_bits, uint8_t *__restrict__ mrow,
                                                uint32_t mask_row_bytes, SelectSmem<BLOCK> &sm) {
     const uint32_t tid = threadIdx.x;
+    const bool nothing = k == 0;       // uniform: no entry of the row goes
+    const bool everything = k >= cols;  // uniform: the whole row goes
+    const bool search = !nothing && !everything;
     // clear the histogram first: the stores overlap the latency of the row's loads below
-    if (k < cols)
+    if (search)
         for (int b = tid; b < kSelBins; b += BLOCK) sm.hist[b] = 0u;
     // All loads of the row are issued before anything waits on them.  A packet past the end of a
     // ragged row re-reads packet 0 (always valid) and is ignored later, so no load sits behind a branch.
@@ -51,8 +54,8 @@ __device__ __forceinline__ void select_one_row(const T *wrow, T *orow, uint32_t 
         }
     }
 
-    SelectBound bound = {0xffffffffu, 0xffffffffu};  // k == cols: everything goes
-    if (k < cols) {
+    SelectBound bound = {0xffffffffu, 0xffffffffu};  // no search: decided by the two flags alone
+    if (search) {
         __syncthreads();
         bound = block_select_bound<BLOCK>(
             [&](auto f, uint32_t salt) {
@@ -69,7 +72,7 @@ __device__ __forceinline__ void select_one_row(const T *wrow, T *orow, uint32_t 
     }
 
     const bool whole_bins = bound.idx == 0xffffffffu;  // uniform: no tie to split by column
-    const bool everything = k >= cols;                  // uniform: the whole row goes
+    const uint32_t force_keep = nothing ? 0xffffffffu : 0u;  // without a search the flags decide
 #pragma unroll
     for (int c = 0; c < NCHUNK; ++c) {
         const uint32_t col0 = (c * BLOCK + tid) * 8;
@@ -79,11 +82,16 @@ __device__ __forceinline__ void select_one_row(const T *wrow, T *orow, uint32_t 
                 // key > bound  <=>  bound - key is negative (keys and bound are below 2^31, or a NaN key
                 // with bit 31, which then counts as kept): the sign, spread over the word, is the mask
                 uint32_t km[8];
+                if (search) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    km[e] = everything ? 0u : static_cast<uint32_t>(static_cast<int32_t>(bound.key - key[c][e]) >> 31);
-                    keep |= km[e] & (1u << e);
+                    for (int e = 0; e < 8; ++e)
+                        km[e] = static_cast<uint32_t>(static_cast<int32_t>(bound.key - key[c][e]) >> 31);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) km[e] = force_keep;
                 }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) keep |= km[e] & (1u << e);
                 pk[c].apply_keep_words(km);
             } else {
 #pragma unroll
@@ -126,6 +134,7 @@ struct SelectItem {
     int64_t ld, ld_out;
     uint32_t cols, k, mask_row_bytes, row0;  // row0: first block of this projection
     int idx_bits, pad;
+    const uint32_t *k_dev;  // when set: k is read from here (and capped at cols)
 };
 
 struct SelectArgs {
@@ -141,9 +150,10 @@ __global__ __launch_bounds__(BLOCK, (BLOCK == 64 ? 4 : NCHUNK <= 3 ? 8 : 6)) voi
         if (blockIdx.x >= args.it[i].row0) p = i;
     const SelectItem &it = args.it[p];
     const int64_t row = blockIdx.x - it.row0;
+    const uint32_t k = it.k_dev ? *it.k_dev : it.k;
     select_one_row<T, BLOCK, NCHUNK, false>(static_cast<const T *>(it.w) + row * it.ld,
                                             static_cast<T *>(it.w_out) + row * it.ld_out, it.cols, it.norms, nullptr,
-                                            it.k, it.idx_bits,
+                                            k, it.idx_bits,
                                             it.mask_bytes ? it.mask_bytes + row * it.mask_row_bytes : nullptr,
                                             it.mask_row_bytes, sm);
 }
@@ -152,19 +162,21 @@ __global__ __launch_bounds__(BLOCK, (BLOCK == 64 ? 4 : NCHUNK <= 3 ? 8 : 6)) voi
 template <typename T, int BLOCK, bool FROM_SCORES>
 __global__ __launch_bounds__(BLOCK) void select_rows_generic(const T *w, T *w_out, int64_t cols, int64_t ld, int64_t ld_out,
                                                              const float *__restrict__ norms,
-                                                             const float *__restrict__ scores, uint32_t k,
-                                                             int idx_bits, uint32_t *__restrict__ mask_words,
-                                                             int64_t words_per_row) {
+                                                             const float *__restrict__ scores, uint32_t k_arg,
+                                                             const uint32_t *__restrict__ k_dev, int idx_bits,
+                                                             uint32_t *__restrict__ mask_words, int64_t words_per_row) {
     __shared__ SelectSmem<BLOCK> sm;
     const int64_t row = blockIdx.x;
     const int tid = threadIdx.x;
+    const uint32_t k = k_dev ? *k_dev : k_arg;
+    const bool nothing = k == 0;
     const T *wr = w + row * ld;
     auto key_at = [&](int64_t j) -> uint32_t {
         const float om = FROM_SCORES ? scores[row * cols + j] : metric(widen(wr[j]), norms[j]);
         return key_of(om);
     };
     SelectBound bound = {0xffffffffu, 0xffffffffu};
-    if (k < cols) {
+    if (k < cols && !nothing) {
         for (int b = tid; b < kSelBins; b += BLOCK) sm.hist[b] = 0u;
         __syncthreads();
         bound = block_select_bound<BLOCK>(
@@ -179,7 +191,7 @@ __global__ __launch_bounds__(BLOCK) void select_rows_generic(const T *w, T *w_ou
         for (int b = 0; b < 32; ++b) {
             const int64_t j = q * 32 + b;
             if (j < cols) {
-                const bool keep = !is_selected(key_at(j), static_cast<uint32_t>(j), bound);
+                const bool keep = nothing || !is_selected(key_at(j), static_cast<uint32_t>(j), bound);
                 const T v = wr[j];
                 orow[j] = keep ? v : T(0);
                 word |= (keep ? 1u : 0u) << b;
@@ -255,7 +267,8 @@ int launch_select(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld, 
     if (FROM_SCORES ? !aligned_to(scores, 16) : !aligned_to(norms, 16)) vec = false;
     if (!vec) {
         hipLaunchKernelGGL((select_rows_generic<T, 256, FROM_SCORES>), grid, dim3(256), 0, stream, w, w_out, cols,
-                           ld, ld_out, norms, scores, k, idx_bits, mask_bits, words);
+                           ld, ld_out, norms, scores, k, static_cast<const uint32_t *>(nullptr), idx_bits, mask_bits,
+                           words);
         return launch_status();
     }
     uint8_t *mb = reinterpret_cast<uint8_t *>(mask_bits);
@@ -279,6 +292,16 @@ int launch_select(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld, 
     else { MP_SELECT_BLOCK(512) }
 #undef MP_SELECT_BLOCK
 #undef MP_SELECT_CASE
+    return launch_status();
+}
+
+// a projection that cannot go through the packet kernels, with its k in device memory
+template <typename T>
+int launch_generic_device_k(const prune_select_item &q, hipStream_t stream) {
+    hipLaunchKernelGGL((select_rows_generic<T, 256, false>), dim3(static_cast<unsigned>(q.rows)), dim3(256), 0, stream,
+                       static_cast<const T *>(q.w), static_cast<T *>(q.w_out), q.cols, q.ld_w, q.ld_out, q.norms,
+                       static_cast<const float *>(nullptr), 0u, q.k_dev, index_bits_for(q.cols), q.mask_bits,
+                       ceil_div(q.cols, 32));
     return launch_status();
 }
 
@@ -358,9 +381,10 @@ extern "C" int prune_select_mask_batch(const prune_select_item *items, int n_ite
     if (!items) return PRUNE_ERR_NULL;
     for (int i = 0; i < n_items; ++i) {  // reject the whole batch before anything is launched
         const prune_select_item &q = items[i];
-        const int st = validate_select(q.w, q.w_out, dtype, q.rows, q.cols, q.ld_w, q.ld_out, q.norms, nullptr, q.k,
-                                       q.mask_bits);
+        const int st = validate_select(q.w, q.w_out, dtype, q.rows, q.cols, q.ld_w, q.ld_out, q.norms, nullptr,
+                                       q.k_dev ? 0u : q.k, q.mask_bits);
         if (st != PRUNE_OK) return st;
+        if (q.k_dev && !aligned_to(q.k_dev, 4)) return PRUNE_ERR_ALIGNMENT;
     }
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     // projections that share a kernel variant go into one launch; the rest take the single-projection path
@@ -370,10 +394,14 @@ extern "C" int prune_select_mask_batch(const prune_select_item *items, int n_ite
     for (int i = 0; i < n_items; ++i) {
         if (done[i]) continue;
         const prune_select_item &q = items[i];
-        const bool batchable = q.k > 0 && select_packets_ok(q.w, q.w_out, q.cols, q.ld_w, q.ld_out, q.norms);
-        if (!batchable) {
-            const int st = prune_select_mask(q.w, q.w_out, dtype, q.rows, q.cols, q.ld_w, q.ld_out, q.norms, nullptr,
-                                             q.k, q.mask_bits, ws, ws_bytes, stream_);
+        auto batchable_item = [](const prune_select_item &x) {
+            return (x.k_dev || x.k > 0) && select_packets_ok(x.w, x.w_out, x.cols, x.ld_w, x.ld_out, x.norms);
+        };
+        if (!batchable_item(q)) {
+            const int st = !q.k_dev ? prune_select_mask(q.w, q.w_out, dtype, q.rows, q.cols, q.ld_w, q.ld_out, q.norms,
+                                                        nullptr, q.k, q.mask_bits, ws, ws_bytes, stream_)
+                           : dtype == PRUNE_BF16 ? launch_generic_device_k<bf16_t>(q, stream)
+                                                 : launch_generic_device_k<float>(q, stream);
             if (st != PRUNE_OK) return st;
             done[i] = true;
             continue;
@@ -395,7 +423,7 @@ extern "C" int prune_select_mask_batch(const prune_select_item *items, int n_ite
         for (int j = i; j < n_items; ++j) {
             if (done[j]) continue;
             const prune_select_item &r = items[j];
-            if (!(r.k > 0 && select_packets_ok(r.w, r.w_out, r.cols, r.ld_w, r.ld_out, r.norms))) continue;
+            if (!batchable_item(r)) continue;
             int b2, c2;
             select_variant(r.cols, b2, c2);
             if (b2 != block || c2 != nchunk) continue;
@@ -416,6 +444,7 @@ extern "C" int prune_select_mask_batch(const prune_select_item *items, int n_ite
             it.row0 = static_cast<uint32_t>(total_rows);
             it.idx_bits = index_bits_for(r.cols);
             it.pad = 0;
+            it.k_dev = r.k_dev;
             total_rows += r.rows;
             done[j] = true;
         }

@@ -87,6 +87,85 @@ __global__ __launch_bounds__(kRankBlock) void rank_channels(const float *__restr
     }
 }
 
+// The same for up to Q * 4096 channels with the keys in registers, so no digit pass goes back to
+// memory.  In round q (of Q) thread t owns the four consecutive channels 4096 q + 4 t ... + 3: the
+// magnitudes are read as one 16-byte load per round when VEC_LOAD (g 16-byte aligned), and the ordered
+// compaction is one block-wide scan of the per-round kept counts, after which neighbouring threads
+// write neighbouring slots.
+template <int Q, bool VEC_LOAD>
+__global__ __launch_bounds__(kRankBlock) void rank_channels_owned(const float *__restrict__ g, uint32_t inter,
+                                                                  uint32_t r, int idx_bits,
+                                                                  int32_t *__restrict__ kept_idx, uint32_t n_kept) {
+    constexpr int NW = kRankBlock / kWave;
+    constexpr uint32_t kRound = 4 * kRankBlock;
+    __shared__ SelectSmem<kRankBlock> sm;
+    __shared__ uint32_t wave_cnt[Q][NW];
+    const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    uint32_t key[Q][4];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const uint32_t c0 = q * kRound + 4 * tid;
+        if (VEC_LOAD && c0 + 4 <= inter) {
+            const f32x4 v = *reinterpret_cast<const f32x4 *>(g + c0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) key[q][e] = key_of(v[e]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) key[q][e] = c0 + e < inter ? key_of(g[c0 + e]) : 0u;
+        }
+    }
+    SelectBound bound = {0u, 0u};
+    if (r > 0) {
+        for (int b = tid; b < kSelBins; b += kRankBlock) sm.hist[b] = 0u;
+        __syncthreads();
+        bound = block_select_bound<kRankBlock>(
+            [&](auto f, uint32_t salt) {
+#pragma unroll
+                for (int q = 0; q < Q; ++q) {
+                    const uint32_t c0 = q * kRound + 4 * (tid + salt);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (c0 + e < inter) f(key[q][e], c0 + e);
+                }
+            },
+            r, idx_bits, sm);
+    }
+    uint32_t keep[Q], before[Q];
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        const uint32_t c0 = q * kRound + 4 * tid;
+        keep[q] = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (c0 + e < inter && (r == 0 || !is_selected(key[q][e], c0 + e, bound))) keep[q] |= 1u << e;
+        const uint32_t mine = __popc(keep[q]);
+        const uint32_t incl = wave_inclusive_scan(mine);
+        if (lane == kWave - 1) wave_cnt[q][wv] = incl;
+        before[q] = incl - mine;
+    }
+    __syncthreads();
+    uint32_t base = 0;  // kept channels in earlier rounds, then in earlier waves of this round
+#pragma unroll
+    for (int q = 0; q < Q; ++q) {
+        uint32_t earlier_waves = 0, round_total = 0;
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            const uint32_t t = wave_cnt[q][i];
+            earlier_waves += static_cast<uint32_t>(i) < wv ? t : 0u;
+            round_total += t;
+        }
+        uint32_t slot = base + earlier_waves + before[q];
+        const uint32_t c0 = q * kRound + 4 * tid;
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if ((keep[q] >> e) & 1u) {
+                if (slot < n_kept) kept_idx[slot] = static_cast<int32_t>(c0 + e);
+                ++slot;
+            }
+        base += round_total;
+    }
+}
+
 // dst[n, :] = src[kept[n], :]
 template <typename T, int VEC>
 __global__ __launch_bounds__(kBlock) void gather_rows(const T *__restrict__ src, T *__restrict__ dst,
@@ -101,7 +180,8 @@ __global__ __launch_bounds__(kBlock) void gather_rows(const T *__restrict__ src,
     }
 }
 
-// dst[i, n] = src[i, kept[n]] ; lanes on adjacent output columns, blockIdx.y walks rows
+// dst[i, n] = src[i, kept[n]] ; lanes on adjacent output columns, blockIdx.y walks rows.
+// Any width and element type; two- or four-byte accesses.
 template <typename T>
 __global__ __launch_bounds__(kBlock) void gather_cols(const T *__restrict__ src, T *__restrict__ dst,
                                                       const int32_t *__restrict__ kept, int64_t n_rows,
@@ -115,16 +195,134 @@ __global__ __launch_bounds__(kBlock) void gather_cols(const T *__restrict__ src,
     for (int64_t i = i0; i < i1; ++i) dst[i * n_kept + n] = src[i * src_cols + c];
 }
 
+// The same gather with every HBM access 16 bytes wide.  A block walks rows i = blockIdx.x, += gridDim.x.
+// A source row is read with 128-bit loads into registers (the next row's loads are in flight while the
+// current one is gathered), parked in LDS, and gathered from there through a 16-bit copy of the kept
+// indices that also sits in LDS.  The compacted rows are dense, so a row starts at any element offset:
+// its first few elements up to the next 16-byte boundary and its last few are stored one by one, all
+// packets in between with 128-bit stores.
+// Needs src_cols <= 65535, 16-byte aligned source rows, src_cols <= kGatherBlock * kGatherPackets * VEC.
+constexpr int kGatherBlock = 512;
+constexpr int kGatherPackets = 4;
+constexpr size_t kGatherLdsMax = 64 * 1024;
+
+template <typename T>
+__global__ __launch_bounds__(kGatherBlock) void gather_cols_lds(const T *__restrict__ src, T *__restrict__ dst,
+                                                                const int32_t *__restrict__ kept, int64_t n_rows,
+                                                                uint32_t src_cols, uint32_t n_kept,
+                                                                uint32_t row_buf_bytes) {
+    constexpr int VEC = 16 / static_cast<int>(sizeof(T));
+    extern __shared__ __align__(16) unsigned char gather_smem[];
+    T *rowbuf = reinterpret_cast<T *>(gather_smem);
+    uint16_t *idx = reinterpret_cast<uint16_t *>(gather_smem + row_buf_bytes);
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t n = tid; n < n_kept; n += kGatherBlock) idx[n] = static_cast<uint16_t>(kept[n]);
+
+    u32x4 pk[kGatherPackets];
+    int64_t i = blockIdx.x;
+    if (i < n_rows) {
+#pragma unroll
+        for (int c = 0; c < kGatherPackets; ++c) {
+            const uint32_t col0 = (c * kGatherBlock + tid) * VEC;
+            pk[c] = __builtin_nontemporal_load(
+                reinterpret_cast<const u32x4 *>(src + i * src_cols + (col0 < src_cols ? col0 : 0u)));
+        }
+    }
+    for (; i < n_rows; i += gridDim.x) {
+#pragma unroll
+        for (int c = 0; c < kGatherPackets; ++c) {
+            const uint32_t col0 = (c * kGatherBlock + tid) * VEC;
+            if (col0 < src_cols) *reinterpret_cast<u32x4 *>(rowbuf + col0) = pk[c];
+        }
+        __syncthreads();  // the row (and, the first time, the index copy) is visible
+        const int64_t inext = i + gridDim.x;
+        if (inext < n_rows) {
+#pragma unroll
+            for (int c = 0; c < kGatherPackets; ++c) {
+                const uint32_t col0 = (c * kGatherBlock + tid) * VEC;
+                pk[c] = __builtin_nontemporal_load(
+                    reinterpret_cast<const u32x4 *>(src + inext * src_cols + (col0 < src_cols ? col0 : 0u)));
+            }
+        }
+        T *d = dst + i * n_kept;
+        uint32_t head = static_cast<uint32_t>((16u - (reinterpret_cast<uintptr_t>(d) & 15u)) & 15u) /
+                        static_cast<uint32_t>(sizeof(T));
+        if (head > n_kept) head = n_kept;
+        const uint32_t n_body = (n_kept - head) / VEC;
+        const uint32_t tail0 = head + n_body * VEC;
+        if (tid < head) d[tid] = rowbuf[idx[tid]];
+        for (uint32_t q = tid; q < n_body; q += kGatherBlock) {
+            const uint32_t base = head + q * VEC;
+            u32x4 out;
+            if constexpr (sizeof(T) == 2) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    out[e] = static_cast<uint32_t>(rowbuf[idx[base + 2 * e]]) |
+                             (static_cast<uint32_t>(rowbuf[idx[base + 2 * e + 1]]) << 16);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) out[e] = __float_as_uint(rowbuf[idx[base + e]]);
+            }
+            *reinterpret_cast<u32x4 *>(d + base) = out;
+        }
+        if (tid < n_kept - tail0) d[tail0 + tid] = rowbuf[idx[tail0 + tid]];
+        __syncthreads();  // everyone is done with the row before the next one replaces it
+    }
+}
+
 }  // namespace
 
 // kept_idx = ascending indices of the n - r groups left after dropping the r lowest magnitudes
 int launch_rank_groups(const float *group_mag, int64_t n, uint32_t r, int32_t *kept_idx, hipStream_t stream) {
-    hipLaunchKernelGGL(rank_channels, dim3(1), dim3(kRankBlock), 0, stream, group_mag, n, r, index_bits_for(n),
-                       kept_idx, n - static_cast<int64_t>(r));
+    const int bits = index_bits_for(n);
+    const int64_t n_kept = n - static_cast<int64_t>(r);
+    const dim3 one(1), block(kRankBlock);
+    const uint32_t n32 = static_cast<uint32_t>(n), kept32 = static_cast<uint32_t>(n_kept);
+    const bool vec = aligned_to(group_mag, 16);
+    if (n <= 4 * kRankBlock) {
+        if (vec)
+            hipLaunchKernelGGL((rank_channels_owned<1, true>), one, block, 0, stream, group_mag, n32, r, bits, kept_idx,
+                               kept32);
+        else
+            hipLaunchKernelGGL((rank_channels_owned<1, false>), one, block, 0, stream, group_mag, n32, r, bits, kept_idx,
+                               kept32);
+    } else if (n <= 16 * kRankBlock) {
+        if (vec)
+            hipLaunchKernelGGL((rank_channels_owned<4, true>), one, block, 0, stream, group_mag, n32, r, bits, kept_idx,
+                               kept32);
+        else
+            hipLaunchKernelGGL((rank_channels_owned<4, false>), one, block, 0, stream, group_mag, n32, r, bits, kept_idx,
+                               kept32);
+    }
+    else
+        hipLaunchKernelGGL(rank_channels, one, block, 0, stream, group_mag, n, r, bits, kept_idx, n_kept);
     return launch_status();
 }
 
 namespace {
+
+// down_out[i, n] = down[i, kept[n]] for a dense [n_rows, n_kept] result
+template <typename T>
+int launch_gather_cols(const T *src, T *dst, const int32_t *kept, int64_t n_rows, int64_t src_cols, int64_t n_kept,
+                       hipStream_t stream) {
+    constexpr int64_t vec = 16 / static_cast<int64_t>(sizeof(T));
+    const size_t row_buf_bytes = static_cast<size_t>(ceil_div(src_cols, vec) * 16);
+    const size_t lds_bytes = row_buf_bytes + static_cast<size_t>(n_kept) * 2;
+    if (src_cols <= 65535 && src_cols <= kGatherBlock * kGatherPackets * vec && lds_bytes <= kGatherLdsMax &&
+        packet_ok(src, src_cols, src_cols) && aligned_to(dst, sizeof(T))) {
+        const int64_t blocks = n_rows < 1024 ? n_rows : 1024;
+        hipLaunchKernelGGL(gather_cols_lds<T>, dim3(static_cast<unsigned>(blocks)), dim3(kGatherBlock), lds_bytes,
+                           stream, src, dst, kept, n_rows, static_cast<uint32_t>(src_cols),
+                           static_cast<uint32_t>(n_kept), static_cast<uint32_t>(row_buf_bytes));
+        return launch_status();
+    }
+    const int64_t rows_per_block = 16;
+    const dim3 cgrid(static_cast<unsigned>(ceil_div(n_kept, kBlock)),
+                     static_cast<unsigned>(ceil_div(n_rows, rows_per_block)));
+    hipLaunchKernelGGL(gather_cols<T>, cgrid, dim3(kBlock), 0, stream, src, dst, kept, n_rows, src_cols, n_kept,
+                       rows_per_block);
+    return launch_status();
+}
 
 template <typename T>
 int struct_dispatch(const T *gate, const T *up, const T *down, int64_t inter, int64_t hidden, uint32_t r,
@@ -156,12 +354,7 @@ int struct_dispatch(const T *gate, const T *up, const T *down, int64_t inter, in
         hipLaunchKernelGGL((gather_rows<T, 1>), ggrid, dim3(kBlock), 0, stream, up, up_out, kept_idx, hidden);
     }
     if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
-    const int64_t rows_per_block = 16;
-    const dim3 cgrid(static_cast<unsigned>(ceil_div(n_kept, kBlock)),
-                     static_cast<unsigned>(ceil_div(hidden, rows_per_block)));
-    hipLaunchKernelGGL(gather_cols<T>, cgrid, dim3(kBlock), 0, stream, down, down_out, kept_idx, hidden, inter, n_kept,
-                       rows_per_block);
-    return launch_status();
+    return launch_gather_cols(down, down_out, kept_idx, hidden, inter, n_kept, stream);
 }
 
 }  // namespace

@@ -5,7 +5,8 @@ Nothing is computed here.  The two phases mirror the paper's two controllers:
   rank_layer   Parameter Ranking Controller (Algorithm 1): activation norms per
                distinct projection input, then metric sum and outlier count per
                projection.  Independent of the pruning target p, so it runs once.
-  plan         Projection Planner (Section 3.3): counts -> zeros per row (host).
+  plan         Projection Planner (Section 3.3): counts -> zeros per row, on the host
+               (plan) or on the device without a host round trip (plan_device).
   prune_layer  Parameter Pruning Controller, unstructured category, then (for
                the composite category) structured removal of MLP channels on
                the masked weights.
@@ -38,6 +39,11 @@ class LayerState:
     mask_bits: Dict[str, torch.Tensor] = field(default_factory=dict)
     ws: torch.Tensor = None
     names: Tuple[str, ...] = ()
+    numels_dev: torch.Tensor = None     # [n_proj] int64, constant
+    cols_dev: torch.Tensor = None       # [n_proj] int64, constant
+    sparsity_dev: torch.Tensor = None   # [n_proj] float64, written by plan_device
+    ks_dev: torch.Tensor = None         # [n_proj] int32, written by plan_device
+    plan_flags: torch.Tensor = None     # [2] int32: clamped, invalid input
 
     @classmethod
     def create(cls, weights: Dict[str, torch.Tensor], proj_inputs: Dict[str, str],
@@ -52,6 +58,11 @@ class LayerState:
         st.score_sum = torch.zeros(n, dtype=torch.float64, device=dev)
         st.count = torch.zeros(n, dtype=torch.int64, device=dev)
         st.tau = torch.zeros(n, dtype=torch.float32, device=dev)
+        st.numels_dev = torch.tensor([weights[k].numel() for k in st.names], dtype=torch.int64, device=dev)
+        st.cols_dev = torch.tensor([weights[k].shape[1] for k in st.names], dtype=torch.int64, device=dev)
+        st.sparsity_dev = torch.zeros(n, dtype=torch.float64, device=dev)
+        st.ks_dev = torch.zeros(n, dtype=torch.int32, device=dev)
+        st.plan_flags = torch.zeros(2, dtype=torch.int32, device=dev)
         need = 256
         for a, ch in act_channels.items():
             need = max(need, prune.workspace_bytes(prune.OP_STATS, max(act_tokens, 1), ch))
@@ -97,12 +108,20 @@ def plan(counts: Sequence[int], numels: Sequence[int], cols: Sequence[int], n_la
     return prune.plan_sparsity(counts, numels, n_layers, n_proj, p, lam, scope, cols=cols)
 
 
-def prune_layer(st: LayerState, ks: Sequence[int], in_place: bool = False) -> None:
-    """Phase 2, unstructured: zero the k lowest-metric entries per row of every projection."""
+def plan_device(st: LayerState, p: float, lam: float, scope: int = prune.SCOPE_GLOBAL) -> None:
+    """The planner over this layer's counts, enqueued behind the ranking: st.count -> st.ks_dev, st.sparsity_dev."""
+    prune.plan_sparsity_device(st.count, st.numels_dev, st.cols_dev, 1, len(st.names), p, lam, st.sparsity_dev,
+                               st.ks_dev, st.plan_flags, scope=scope)
+
+
+def prune_layer(st: LayerState, ks: Optional[Sequence[int]], in_place: bool = False) -> None:
+    """Phase 2, unstructured: zero the k lowest-metric entries per row of every projection.
+    ks = None takes the zeros per row that plan_device left in st.ks_dev."""
     names = st.names
     prune.select_mask_batch([st.weights[n] for n in names], [st.norms[st.proj_inputs[n]] for n in names],
-                            [int(k) for k in ks], w_outs=None if in_place else [st.pruned[n] for n in names],
-                            mask_bits=[st.mask_bits.get(n) for n in names])
+                            None if ks is None else [int(k) for k in ks],
+                            w_outs=None if in_place else [st.pruned[n] for n in names],
+                            mask_bits=[st.mask_bits.get(n) for n in names], ks_dev=st.ks_dev if ks is None else None)
 
 
 @dataclass

@@ -41,6 +41,7 @@ _SIGNATURES = {
     "prune_plan_sparsity": (_int, [_vp, _vp, _vp, _int, _int, _f64, _f64, _int, _vp, _vp, _vp]),
     "prune_select_mask": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _i64, _vp, _vp, _u32, _vp, _vp, _sz, _vp]),
     "prune_select_mask_batch": (_int, [_vp, _int, _int, _vp, _sz, _vp]),
+    "prune_plan_sparsity_device": (_int, [_vp, _vp, _vp, _int, _int, _f64, _f64, _int, _vp, _vp, _vp, _vp]),
     "prune_struct_groups_workspace_bytes": (_sz, [_vp, _vp, _int, _vp, _vp, _int, _i64]),
     "prune_struct_groups": (_int, [_vp, _vp, _vp, _int, _vp, _vp, _vp, _int, _int, _i64, _u32, _vp, _vp, _vp, _vp,
                                    _vp, _sz, _vp]),
@@ -58,7 +59,7 @@ class SelectItem(ctypes.Structure):
     """Mirror of the C struct prune_select_item."""
 
     _fields_ = [("w", _vp), ("w_out", _vp), ("rows", _i64), ("cols", _i64), ("ld_w", _i64), ("ld_out", _i64),
-                ("norms", _vp), ("k", _u32), ("mask_bits", _vp)]
+                ("norms", _vp), ("k", _u32), ("mask_bits", _vp), ("k_dev", _vp)]
 
 
 class PruneError(RuntimeError):
@@ -266,6 +267,24 @@ def plan_sparsity(counts: Sequence[int], numels: Sequence[int], n_layers: int, n
     return list(out), (list(k_out) if k_out is not None else None), bool(clamped.value)
 
 
+def plan_sparsity_device(counts: torch.Tensor, numels: torch.Tensor, cols: torch.Tensor, n_layers: int, n_proj: int,
+                         p: float, lam: float, sparsity_out: torch.Tensor, zeros_per_row_out: torch.Tensor,
+                         flags_out: torch.Tensor, scope: int = SCOPE_GLOBAL, stream=None) -> None:
+    """The planner as one small launch on device-resident counts (prune_plan_sparsity_device).
+
+    counts, numels, cols: int64 GPU tensors; sparsity_out float64, zeros_per_row_out int32 / uint32,
+    each of n_layers * n_proj entries; flags_out: 2 x int32 (clamped, invalid input).
+    """
+    n = n_layers * n_proj
+    _check("prune_plan_sparsity_device",
+           load().prune_plan_sparsity_device(
+               _vector(counts, "counts", torch.int64, n), _vector(numels, "numels", torch.int64, n),
+               _vector(cols, "cols", torch.int64, n), n_layers, n_proj, float(p), float(lam), int(scope),
+               _vector(sparsity_out, "sparsity_out", torch.float64, n),
+               _vector(zeros_per_row_out, "zeros_per_row_out", zeros_per_row_out.dtype, n),
+               _vector(flags_out, "flags_out", torch.int32, 2), _stream(stream)))
+
+
 def select_mask(w: torch.Tensor, norms: Optional[torch.Tensor], k: int, w_out: Optional[torch.Tensor] = None,
                 mask_bits: Optional[torch.Tensor] = None, scores: Optional[torch.Tensor] = None,
                 ws: Optional[torch.Tensor] = None, stream=None) -> None:
@@ -290,14 +309,24 @@ def select_mask(w: torch.Tensor, norms: Optional[torch.Tensor], k: int, w_out: O
                                     0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)))
 
 
-def select_mask_batch(ws_: Sequence[torch.Tensor], norms: Sequence[torch.Tensor], ks: Sequence[int],
+def select_mask_batch(ws_: Sequence[torch.Tensor], norms: Sequence[torch.Tensor], ks: Optional[Sequence[int]],
                       w_outs: Optional[Sequence[Optional[torch.Tensor]]] = None,
-                      mask_bits: Optional[Sequence[Optional[torch.Tensor]]] = None, stream=None) -> None:
+                      mask_bits: Optional[Sequence[Optional[torch.Tensor]]] = None, stream=None,
+                      ks_dev: Optional[torch.Tensor] = None) -> None:
     """prune_select_mask for several projections, same-width projections sharing a launch
-    (prune_select_mask_batch).  In place where w_outs (or an entry of it) is None."""
+    (prune_select_mask_batch).  In place where w_outs (or an entry of it) is None.
+    The k of projection i is ks[i], or, when ks_dev (int32 / uint32 GPU tensor, one entry per
+    projection) is given, whatever ks_dev[i] holds when the kernels run."""
     n = len(ws_)
-    if n == 0 or len(norms) != n or len(ks) != n:
+    if (ks is None) == (ks_dev is None):
+        raise ValueError("give either ks or ks_dev")
+    if n == 0 or len(norms) != n or (ks is not None and len(ks) != n):
         raise ValueError("need one norm vector and one k per weight")
+    k_base = None
+    if ks_dev is not None:
+        if ks_dev.dtype not in (torch.int32, torch.uint32):
+            raise ValueError("ks_dev must be a 32-bit integer tensor")
+        k_base = _vector(ks_dev, "ks_dev", ks_dev.dtype, n)
     arr = (SelectItem * n)()
     code = _dtype_code(ws_[0])
     for i, w in enumerate(ws_):
@@ -315,8 +344,9 @@ def select_mask_batch(ws_: Sequence[torch.Tensor], norms: Sequence[torch.Tensor]
         if mb is not None and mb.dtype not in (torch.int32, torch.uint32):
             raise ValueError("mask_bits must be a 32-bit integer tensor")
         arr[i] = SelectItem(ptr, out_ptr, rows, cols, ld, ld_out, _vector(norms[i], "norms", torch.float32, cols),
-                            int(ks[i]),
-                            None if mb is None else _vector(mb, "mask_bits", mb.dtype, rows * ((cols + 31) // 32)))
+                            0 if ks is None else int(ks[i]),
+                            None if mb is None else _vector(mb, "mask_bits", mb.dtype, rows * ((cols + 31) // 32)),
+                            None if k_base is None else k_base + 4 * i)
     _check("prune_select_mask_batch", load().prune_select_mask_batch(arr, n, code, None, 0, _stream(stream)))
 
 

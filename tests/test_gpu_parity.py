@@ -329,8 +329,11 @@ def test_toy_layer_end_to_end(lib):
     want_s, _ = orc.plan_sparsity(np.array(ratios).reshape(1, -1), cfg.p, cfg.lam, "global")
     assert np.allclose(s, want_s.reshape(-1), atol=1e-13) and not clamped
     assert ks == [orc.zeros_per_row(v, c) for v, c in zip(s, cols)]
-    pipeline.prune_layer(st, ks)
+    pipeline.plan_device(st, cfg.p, cfg.lam)                 # the same plan without the host round trip
+    pipeline.prune_layer(st, None)                           # ... and the pruning takes its k from device memory
     _sync()
+    assert st.ks_dev.tolist() == ks and st.plan_flags.tolist() == [0, 0]
+    assert np.array_equal(to_np(st.sparsity_dev).view(np.uint64), np.array(s, dtype=np.float64).view(np.uint64))
     for i, (n, r, c, a) in enumerate(shapes):
         pruned = orc.select_smallest_per_row(to_np(scores[n]), ks[i])
         assert np.array_equal(to_np(st.pruned[n]), orc.apply_mask(to_np(weights[n]), pruned))
@@ -347,6 +350,46 @@ def test_toy_layer_end_to_end(lib):
     wg, wu, wd = orc.struct_compact(masked["gate"], masked["up"], masked["down"], kept)
     assert np.array_equal(to_np(res.gate), wg) and np.array_equal(to_np(res.up), wu)
     assert np.array_equal(to_np(res.down), wd)
+
+
+# ----------------------------------------------------------------- planner on the device
+
+@pytest.mark.parametrize("scope", ["global", "category"])
+@pytest.mark.parametrize("n_layers,n_proj", [(1, 7), (32, 7), (3, 300), (40, 7)])
+def test_plan_device_vs_host_and_oracle(lib, scope, n_layers, n_proj):
+    """Same bits as the host planner, same plan as the oracle; clamping, equal ratios and bad input flagged."""
+    rng = np.random.default_rng(n_layers * 1000 + n_proj)
+    n = n_layers * n_proj
+    cols = rng.choice([256, 688, 4096, 11008, 14336], size=n).astype(np.int64)
+    numels = cols * rng.integers(8, 4096, size=n)
+    counts = (numels * rng.uniform(0.001, 0.06, size=n)).astype(np.int64)
+    code = prune.SCOPE_GLOBAL if scope == "global" else prune.SCOPE_CATEGORY
+    dev = lambda a, dt: torch.tensor(np.asarray(a), dtype=dt, device=DEV)
+    for p, lam, cnt in ((0.5, 0.08, counts), (0.7, 0.08, counts), (0.05, 0.6, counts),      # the third clamps at 0
+                        (0.5, 0.08, numels // 16)):                                          # equal ratios: s == p
+        s_dev = torch.full((n,), -1.0, dtype=torch.float64, device=DEV)
+        k_dev = torch.full((n,), -1, dtype=torch.int32, device=DEV)
+        flags = torch.full((2,), -1, dtype=torch.int32, device=DEV)
+        prune.plan_sparsity_device(dev(cnt, torch.int64), dev(numels, torch.int64), dev(cols, torch.int64), n_layers,
+                                   n_proj, p, lam, s_dev, k_dev, flags, scope=code)
+        _sync()
+        s_host, k_host, clamped = prune.plan_sparsity(cnt.tolist(), numels.tolist(), n_layers, n_proj, p, lam, code,
+                                                      cols=cols.tolist())
+        assert np.array_equal(to_np(s_dev).view(np.uint64), np.array(s_host).view(np.uint64))
+        assert k_dev.tolist() == k_host and flags.tolist() == [int(clamped), 0]
+        ratios = (100.0 * cnt / numels).reshape(n_layers, n_proj)
+        want, want_clamped = orc.plan_sparsity(ratios, p, lam, scope, cols=cols.reshape(n_layers, n_proj))
+        assert np.allclose(to_np(s_dev), want.reshape(-1), atol=1e-12) and bool(want_clamped) == clamped
+        exact = [orc.zeros_per_row(v, c) for v, c in zip(want.reshape(-1), cols)]
+        near_integer = np.abs(want.reshape(-1) * cols - np.round(want.reshape(-1) * cols)) < 1e-6
+        assert all(a == b or t for a, b, t in zip(k_dev.tolist(), exact, near_integer))
+    assert np.all(to_np(s_dev) == 0.5)                                   # the last case: every ratio is 6.25
+    bad = counts.copy()
+    bad[n // 2] = numels[n // 2] + 1
+    prune.plan_sparsity_device(dev(bad, torch.int64), dev(numels, torch.int64), dev(cols, torch.int64), n_layers,
+                               n_proj, 0.5, 0.08, s_dev, k_dev, flags, scope=code)
+    _sync()
+    assert flags.tolist()[1] == 1
 
 
 # ----------------------------------------------------------------- batched ranking
@@ -390,9 +433,11 @@ def test_score_outlier_batch_vs_oracle(lib, dtype, case):
         assert abs(single.item() - sums[i].item()) <= 1e-7 * ref      # float32 groups of 32 vs 64 metrics before widening
 
 
+@pytest.mark.parametrize("k_source", ["host", "device"])
 @pytest.mark.parametrize("dtype", DTYPES)
-def test_select_mask_batch_vs_oracle(lib, dtype):
-    """Several projections per call: equal-width ones share a launch, odd ones take the single path."""
+def test_select_mask_batch_vs_oracle(lib, dtype, k_source):
+    """Several projections per call: equal-width ones share a launch, odd ones take the single path.
+    k comes from the host array or is read by the kernels from device memory (0, cols and beyond included)."""
     shapes = [(40, 1024), (16, 1024), (9, 688), (25, 1024), (7, 4104), (5, 130), (12, 1024), (3, 16392)] + \
              [(4 + i, 512) for i in range(20)]                     # more than one launch table of one width
     ws_, norms, ks, outs, masks = [], [], [], [], []
@@ -405,7 +450,12 @@ def test_select_mask_batch_vs_oracle(lib, dtype):
         masks.append(None if i % 3 == 2 else torch.full((rows, (cols + 31) // 32), -1, dtype=torch.int32, device=DEV))
     originals = [to_np(w).copy() for w in ws_]
     metrics = [host_metric_f32(w, n) for w, n in zip(ws_, norms)]
-    prune.select_mask_batch(ws_, norms, ks, w_outs=outs, mask_bits=masks)
+    if k_source == "host":
+        prune.select_mask_batch(ws_, norms, ks, w_outs=outs, mask_bits=masks)
+    else:
+        over = [k + 5 if k == c else k for k, (_, c) in zip(ks, shapes)]          # above cols counts as cols
+        ks_dev = torch.tensor(over, dtype=torch.int32, device=DEV)
+        prune.select_mask_batch(ws_, norms, None, w_outs=outs, mask_bits=masks, ks_dev=ks_dev)
     _sync()
     for i, (rows, cols) in enumerate(shapes):
         pruned = orc.select_smallest_per_row(metrics[i], ks[i])

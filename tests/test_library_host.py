@@ -106,8 +106,20 @@ def test_error_paths_return_before_any_launch(lib):
     assert smb(one(norms=None), 1, 1, None, 0, None) == E["null"]
     assert smb(one(ld_w=4), 1, 1, None, 0, None) == E["shape"]
     assert smb(one(w_out=0x1010), 1, 1, None, 0, None) == E["rng"]
+    assert smb(one(k_dev=0x1002), 1, 1, None, 0, None) == E["align"]     # k in device memory: a 4-byte pointer
     two = (prune.SelectItem * 2)(item(), item(w_out=None))          # a bad second item rejects the whole batch
     assert smb(two, 2, 1, None, 0, None) == E["null"]
+    pd = lib.prune_plan_sparsity_device
+    assert pd(None, fake, fake, 1, 7, 0.5, 0.08, 0, fake, fake, fake, None) == E["null"]
+    assert pd(fake, fake, None, 1, 7, 0.5, 0.08, 0, fake, fake, fake, None) == E["null"]      # cols are required here
+    assert pd(fake, fake, fake, 1, 7, 0.5, 0.08, 0, fake, fake, None, None) == E["null"]
+    assert pd(fake, fake, fake, 0, 7, 0.5, 0.08, 0, fake, fake, fake, None) == E["shape"]
+    assert pd(fake, fake, fake, 1 << 12, 1 << 12, 0.5, 0.08, 0, fake, fake, fake, None) == E["shape"]
+    assert pd(fake, fake, fake, 1, 7, 1.0, 0.08, 0, fake, fake, fake, None) == E["rng"]
+    assert pd(fake, fake, fake, 1, 7, 0.5, -1.0, 0, fake, fake, fake, None) == E["rng"]
+    assert pd(fake, fake, fake, 1, 7, 0.5, 0.08, 9, fake, fake, fake, None) == E["rng"]
+    assert pd(ctypes.c_void_p(0x1004), fake, fake, 1, 7, 0.5, 0.08, 0, fake, fake, fake, None) == E["align"]
+    assert pd(fake, fake, fake, 1, 7, 0.5, 0.08, 0, fake, odd, fake, None) == E["align"]
     st = lib.prune_struct_compact
     assert st(fake, fake, fake, 1, 8, 8, 8, fake, fake, None, None, None, fake, 1 << 20, None) == E["rng"]  # r >= inter
     assert st(fake, fake, fake, 1, 8, 8, 1, fake, fake, fake, None, None, fake, 1 << 20, None) == E["null"]  # 1 of 3 outs
