@@ -141,29 +141,32 @@ def main():
     cols = [c for _, _, c, _ in shapes]
     names = list(act_shapes)
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    stats_events = []   # (start, stop, bytes) around every statistics launch of the timed region
+    stats_events = []   # (start, stop, bytes, launches) around the statistics launches of every timed step
     pass_events = []    # per-step boundaries for the stderr breakdown
 
-    def step(record: bool):
-        # phase 1: ranking (independent of p)
-        marks = [ev() for _ in range(5)] if record else None
-        if record:
+    def step(record: bool, breakdown: bool = False):
+        """One pass of the whole path.  record: one HIP-event pair around the statistics launches (the
+        roofline figure).  breakdown: marks between the passes as well; each event costs the stream a few
+        microseconds, so these steps are run after the timed region, not inside it."""
+        marks = [ev() for _ in range(5)] if breakdown else None
+        if breakdown:
             marks[0].record()
-        for a in names:
-            x = acts[a]
-            if record:
-                e0, e1 = ev(), ev()
-                e0.record()
-            prune.stats_norms(x, st.sumsq[a], st.norms[a], ws=st.ws)
-            if record:
-                e1.record()
-                stats_events.append((e0, e1, x.numel() * x.element_size() + x.shape[1] * 8))
+        # phase 1: ranking (independent of p)
         if record:
+            e0, e1 = ev(), ev()
+            e0.record()
+        for a in names:
+            prune.stats_norms(acts[a], st.sumsq[a], st.norms[a], ws=st.ws)
+        if record:
+            e1.record()
+            stats_events.append((e0, e1, sum(acts[a].numel() * acts[a].element_size() + acts[a].shape[1] * 8
+                                             for a in names), len(names)))
+        if breakdown:
             marks[1].record()
         prune.score_outlier_batch([st.weights[n] for n in st.names],
                                   [st.norms[st.proj_inputs[n]] for n in st.names], cfg.alpha, st.score_sum,
                                   st.count, taus=st.tau, ws=st.ws)
-        if record:
+        if breakdown:
             marks[2].record()
         if args.host_plan:
             counts = st.count.tolist()      # 7 integers cross to the host, the step waits for them
@@ -173,10 +176,10 @@ def main():
             pipeline.plan_device(st, cfg.p, cfg.lam)
         # phase 2: pruning
         pipeline.prune_layer(st, ks)
-        if record:
+        if breakdown:
             marks[3].record()
         pipeline.struct_layer(st, r, res)
-        if record:
+        if breakdown:
             marks[4].record()
             pass_events.append(marks)
         return counts, ks
@@ -206,16 +209,18 @@ def main():
 
     ms_per_step = 1e3 * elapsed / args.steps
     ab = algorithmic_bytes(cfg, shapes, act_shapes, r)
-    stats_ms = [a.elapsed_time(b) for a, b, _ in stats_events]
-    stats_bytes = [n for _, _, n in stats_events]
-    avg_ms = sum(stats_ms) / len(stats_ms)
-    avg_bytes = sum(stats_bytes) / len(stats_bytes)
+    for _ in range(min(args.steps, 10)):     # the per-pass breakdown for stderr, outside the timed region
+        step(False, breakdown=True)
+    torch.cuda.synchronize()
+    n_launches = sum(n for _, _, _, n in stats_events)
+    avg_ms = sum(a.elapsed_time(b) for a, b, _, _ in stats_events) / n_launches
+    avg_bytes = sum(n for _, _, n, _ in stats_events) / n_launches
     achieved = avg_bytes / (avg_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "colsumsq_partial_vec (activation statistics)",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(cfg.name),
                 "avg_launch_ms": round(avg_ms, 4), "avg_launch_bytes": int(avg_bytes),
-                "launches": len(stats_ms)}
+                "launches": n_launches}
 
     seg = [[m[i].elapsed_time(m[i + 1]) for i in range(4)] for m in pass_events]
     mean = lambda j: sum(s[j] for s in seg) / len(seg)
