@@ -21,12 +21,6 @@ __device__ __forceinline__ void select_one_row(const T *wrow, T *orow, uint32_t 
                                                uint32_t k, int idx_bits, uint8_t *__restrict__ mrow,
                                                uint32_t mask_row_bytes, SelectSmem<BLOCK> &sm) {
     const uint32_t tid = threadIdx.x;
-    const bool nothing = k == 0;       // uniform: no entry of the row goes
-    const bool everything = k >= cols;  // uniform: the whole row goes
-    const bool search = !nothing && !everything;
-    // clear the histogram first: the stores overlap the latency of the row's loads below
-    if (search)
-        for (int b = tid; b < kSelBins; b += BLOCK) sm.hist[b] = 0u;
     // All loads of the row are issued before anything waits on them.  A packet past the end of a
     // ragged row re-reads packet 0 (always valid) and is ignored later, so no load sits behind a branch.
     Packet<T, 8> pk[NCHUNK];
@@ -35,6 +29,12 @@ __device__ __forceinline__ void select_one_row(const T *wrow, T *orow, uint32_t 
         const uint32_t col0 = (c * BLOCK + tid) * 8;
         pk[c].load(wrow + (col0 < cols ? col0 : 0u));
     }
+    // clear the histogram: the stores overlap the latency of the loads.  Nothing up to here depends on k,
+    // which may itself still be on its way from device memory.
+    for (int b = tid; b < kSelBins; b += BLOCK) sm.hist[b] = 0u;
+    const bool nothing = k == 0;        // uniform: no entry of the row goes
+    const bool everything = k >= cols;  // uniform: the whole row goes
+    const bool search = !nothing && !everything;
     uint32_t key[NCHUNK][8];
 #pragma unroll
     for (int c = 0; c < NCHUNK; ++c) {

@@ -163,21 +163,27 @@ __device__ __forceinline__ void locate_later_digit(const uint32_t *region, uint3
 // is what matters), the last key digit being 4 bits; index digits of 8 bits if a tie must be split.
 // The first digit leaves the histogram zeroed; each later digit counts into its own 256-bin slice of
 // it, so later digits need neither zeroing nor more than one barrier (at most 3 + 4 slices are used).
+//
+// A caller that knows that all its keys agree in the bits above bit first_shift + 10 passes those common
+// bits as hi_common (= key >> (first_shift + 11)) and a first_shift below 20: the first digit then starts
+// at the first bit where keys can differ, which keeps keys of nearly equal magnitude from piling into a
+// single bin (LDS atomics on one address are serialised).
 template <int BLOCK, class ForEach>
-__device__ SelectBound block_select_bound(ForEach for_each, uint32_t k, int idx_bits, SelectSmem<BLOCK> &sm) {
+__device__ SelectBound block_select_bound(ForEach for_each, uint32_t k, int idx_bits, SelectSmem<BLOCK> &sm,
+                                          int first_shift = 20, uint32_t hi_common = 0u) {
     uint32_t need = k, bin, before, count;
 
     // (the digit is masked so that a key with bit 31 set -- only a NaN metric can have it -- stays inside the
     // histogram; such a key matches no later digit and is never selected)
-    for_each([&](uint32_t key, uint32_t) { atomicAdd(&sm.hist[(key >> 20) & 0x7ffu], 1u); }, 0u);
+    for_each([&](uint32_t key, uint32_t) { atomicAdd(&sm.hist[(key >> first_shift) & 0x7ffu], 1u); }, 0u);
     __syncthreads();
     locate_first_digit<BLOCK>(sm, need, bin, before, count);
     need -= before;
-    uint32_t prefix = bin;  // key bits above `pos`
-    if (need == count) return {(prefix << 20) | 0xfffffu, 0xffffffffu};
+    uint32_t prefix = (hi_common << 11) | bin;  // key bits above `pos`
+    int pos = first_shift;
+    if (need == count) return {pos ? (((prefix + 1u) << pos) - 1u) : prefix, 0xffffffffu};
 
     uint32_t *region = sm.hist;  // next fresh 256-bin slice
-    int pos = 20;
 #pragma unroll 1
     while (pos > 0) {
         const int width = pos >= 8 ? 8 : pos;  // 8, 8, 4

@@ -100,6 +100,7 @@ __global__ __launch_bounds__(kRankBlock) void rank_channels_owned(const float *_
     constexpr uint32_t kRound = 4 * kRankBlock;
     __shared__ SelectSmem<kRankBlock> sm;
     __shared__ uint32_t wave_cnt[Q][NW];
+    __shared__ uint32_t wave_lo[NW], wave_hi[NW];
     const uint32_t tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     uint32_t key[Q][4];
 #pragma unroll
@@ -116,8 +117,37 @@ __global__ __launch_bounds__(kRankBlock) void rank_channels_owned(const float *_
     }
     SelectBound bound = {0u, 0u};
     if (r > 0) {
+        // Channel magnitudes of one layer are close to each other: most share their exponent and leading
+        // mantissa bits.  The first radix digit therefore starts at the highest bit in which the smallest
+        // and the largest key differ; the bits above it are common to all keys.
+        uint32_t lo = 0xffffffffu, hi = 0u;
+#pragma unroll
+        for (int q = 0; q < Q; ++q)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (q * kRound + 4 * tid + e < inter) {
+                    lo = min(lo, key[q][e]);
+                    hi = max(hi, key[q][e]);
+                }
+        for (int off = kWave / 2; off > 0; off >>= 1) {
+            lo = min(lo, static_cast<uint32_t>(__shfl_xor(static_cast<int>(lo), off)));
+            hi = max(hi, static_cast<uint32_t>(__shfl_xor(static_cast<int>(hi), off)));
+        }
+        if (lane == 0) {
+            wave_lo[wv] = lo;
+            wave_hi[wv] = hi;
+        }
         for (int b = tid; b < kSelBins; b += kRankBlock) sm.hist[b] = 0u;
         __syncthreads();
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            lo = min(lo, wave_lo[i]);
+            hi = max(hi, wave_hi[i]);
+        }
+        const uint32_t differ = lo ^ hi;
+        const int top = differ ? 31 - __clz(static_cast<int>(differ)) : 0;  // keys are below 2^31: top <= 30
+        const int first_shift = top > 10 ? top - 10 : 0;
+        const uint32_t hi_common = lo >> (first_shift + 11);
         bound = block_select_bound<kRankBlock>(
             [&](auto f, uint32_t salt) {
 #pragma unroll
@@ -128,7 +158,7 @@ __global__ __launch_bounds__(kRankBlock) void rank_channels_owned(const float *_
                         if (c0 + e < inter) f(key[q][e], c0 + e);
                 }
             },
-            r, idx_bits, sm);
+            r, idx_bits, sm, first_shift, hi_common);
     }
     uint32_t keep[Q], before[Q];
 #pragma unroll

@@ -301,6 +301,23 @@ def test_struct_vs_oracle(lib, dtype, shape):
     assert np.array_equal(g1.view(np.uint32), g2.view(np.uint32)) and np.array_equal(k1, k2)
 
 
+@pytest.mark.parametrize("dtype", DTYPES)
+@pytest.mark.parametrize("shape", [(700, 64), (4104, 64), (9000, 32)])
+def test_struct_rank_close_and_equal_magnitudes(lib, dtype, shape):
+    """Channel magnitudes that share their leading bits, and magnitudes that are all the same (ties by index)."""
+    inter, hidden = shape
+    rng = np.random.default_rng(inter)
+    sign = lambda *sh: torch.tensor(rng.choice([-0.5, 0.5], size=sh), dtype=dtype, device=DEV)
+    gate, up, down = sign(inter, hidden), sign(inter, hidden), sign(hidden, inter)
+    for r in (1, inter // 3, inter - 1):                    # every magnitude is 3 * hidden / 4: lowest indices go
+        g, kept = _check_struct(gate, up, down, r, compact=False)
+        assert np.all(g == 0.75 * hidden) and np.array_equal(kept, np.arange(r, inter))
+    bump = torch.tensor(rng.choice([0.5, 0.53125, 0.5625, 0.625], size=inter), dtype=dtype, device=DEV)
+    gate[:, 0] = bump                                       # now a handful of distinct, close values with many ties
+    for r in (1, inter // 3, inter // 2, inter - 1):
+        _check_struct(gate, up, down, r, compact=(r == inter // 3))
+
+
 # ----------------------------------------------------------------- whole toy layer (configs[0])
 
 def test_toy_layer_end_to_end(lib):
