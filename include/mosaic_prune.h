@@ -287,6 +287,26 @@ int prune_struct_groups(const void *const *row_mats, const int64_t *row_per, con
                         int dtype, int64_t n_groups, uint32_t r, float *group_mag, int32_t *kept_idx,
                         void *const *row_outs, void *const *col_outs, void *ws, size_t ws_bytes, void *stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * The Hessian-based one-shot pruner that the paper's experiments run with the planner's targets
+ * (Section 4.1.3 "Pruning Methods": the lowest-ranking parameters are pruned "using the inverse
+ * Hessian matrix and a subsequent weight update"; Section 4.1.4 "Calibration": the same 128 samples
+ * give the Hessian).  Built in stages; each stage is an entry point of its own.
+ * ------------------------------------------------------------------------------------------------ */
+
+/*
+ * Hessian of the layer-wise reconstruction problem of one projection input:
+ *   h[i, j] += sum_t x[t, i] * x[t, j]          0 <= i, j < channels
+ * x: DEVICE [n_tokens, channels] of dtype, pitch ld_x (elements).  h: DEVICE fp32 [channels, channels],
+ * pitch ld_h, in/out: zero it before the first chunk of tokens; both triangles are written and stay
+ * bitwise symmetric.  Products are exact for bf16 input, sums are fp32 within a block's share of the
+ * tokens and double across shares, in a fixed order (reproducible bit for bit).
+ * ws_bytes >= prune_hessian_workspace_bytes(n_tokens, channels).  n_tokens == 0 is a no-op.
+ */
+size_t prune_hessian_workspace_bytes(int64_t n_tokens, int64_t channels);
+int prune_hessian_accumulate(const void *x, int dtype, int64_t n_tokens, int64_t channels, int64_t ld_x, float *h,
+                             int64_t ld_h, void *ws, size_t ws_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -41,6 +41,8 @@ _SIGNATURES = {
     "prune_plan_sparsity": (_int, [_vp, _vp, _vp, _int, _int, _f64, _f64, _int, _vp, _vp, _vp]),
     "prune_select_mask": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _i64, _vp, _vp, _u32, _vp, _vp, _sz, _vp]),
     "prune_select_mask_batch": (_int, [_vp, _int, _int, _vp, _sz, _vp]),
+    "prune_hessian_workspace_bytes": (_sz, [_i64, _i64]),
+    "prune_hessian_accumulate": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _i64, _vp, _sz, _vp]),
     "prune_plan_sparsity_device": (_int, [_vp, _vp, _vp, _int, _int, _f64, _f64, _int, _vp, _vp, _vp, _vp]),
     "prune_struct_groups_workspace_bytes": (_sz, [_vp, _vp, _int, _vp, _vp, _int, _i64]),
     "prune_struct_groups": (_int, [_vp, _vp, _vp, _int, _vp, _vp, _vp, _int, _int, _i64, _u32, _vp, _vp, _vp, _vp,
@@ -348,6 +350,23 @@ def select_mask_batch(ws_: Sequence[torch.Tensor], norms: Sequence[torch.Tensor]
                             None if mb is None else _vector(mb, "mask_bits", mb.dtype, rows * ((cols + 31) // 32)),
                             None if k_base is None else k_base + 4 * i)
     _check("prune_select_mask_batch", load().prune_select_mask_batch(arr, n, code, None, 0, _stream(stream)))
+
+
+def hessian_workspace_bytes(n_tokens: int, channels: int) -> int:
+    return int(load().prune_hessian_workspace_bytes(int(n_tokens), int(channels)))
+
+
+def hessian_accumulate(x: torch.Tensor, h: torch.Tensor, ws: Optional[torch.Tensor] = None, stream=None) -> None:
+    """h += x^T x over the tokens of x (prune_hessian_accumulate).  h: fp32 [channels, channels], zeroed by the caller."""
+    ptr, n_tokens, channels, ld = _matrix(x, "x")
+    if not (h.is_cuda and h.dtype == torch.float32 and h.dim() == 2 and tuple(h.shape) == (channels, channels)
+            and h.stride(1) == 1):
+        raise ValueError("h must be a float32 GPU matrix [channels, channels] with unit column stride")
+    need = hessian_workspace_bytes(n_tokens, channels)
+    ws_ptr, ws_bytes, keep = _workspace(ws, need, x.device)
+    _check("prune_hessian_accumulate",
+           load().prune_hessian_accumulate(ptr, _dtype_code(x), n_tokens, channels, ld, h.data_ptr(), h.stride(0),
+                                           ws_ptr, ws_bytes, _stream(stream)))
 
 
 def struct_compact(gate: torch.Tensor, up: torch.Tensor, down: torch.Tensor, r: int, group_mag: torch.Tensor,

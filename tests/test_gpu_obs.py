@@ -1,0 +1,84 @@
+"""GPU parity of the Hessian-based pruner's stages against oracle/obs_oracle.py, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mosaic_oracle as orc
+from oracle import obs_oracle as obs
+from paper_2504_06323_amd import prune, synth
+from util import to_np
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _sync():
+    torch.cuda.synchronize()
+
+
+def _acts(tokens, channels, dtype, seed):
+    x = synth.random_matrix(tokens, channels, dtype, seed=seed, device=DEV, scale=1.0)
+    if channels >= 8:
+        x[:, 3] *= 20.0                                    # an outlier channel, as in the synthetic activations
+    return x
+
+
+def _scaled_err(got, want):
+    """max |got - want| / sqrt(H_ii H_jj): the natural scale of entry (i, j) (Cauchy-Schwarz bounds |H_ij| by it)."""
+    d = np.sqrt(np.maximum(np.diag(want), 1e-300))
+    return float(np.max(np.abs(got - want) / np.outer(d, d))) if want.size else 0.0
+
+
+# fp32 sums of exact products over at most 64 k-steps of 16 tokens per share of the tokens here: the worst-case
+# bound is (64 + 16) * 2^-24 = 5e-6 of sum |x_i x_j| <= sqrt(H_ii H_jj); fp32 input adds one rounding per product
+HESSIAN_TOL = {torch.bfloat16: 5e-6, torch.float32: 2e-5}
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("shape", [(1000, 512), (300, 688), (70, 100), (33, 8), (2050, 256), (5, 1048)])
+def test_hessian_vs_oracle(lib, dtype, shape):
+    tokens, channels = shape
+    x = _acts(tokens, channels, dtype, seed=tokens + channels)
+    h = torch.zeros((channels, channels), dtype=torch.float32, device=DEV)
+    prune.hessian_accumulate(x, h)
+    _sync()
+    want = obs.gram_matrix(to_np(x))
+    got = to_np(h).astype(np.float64)
+    assert _scaled_err(got, want) < HESSIAN_TOL[dtype]
+    assert np.array_equal(to_np(h), to_np(h).T)                               # bitwise symmetric
+    h2 = torch.zeros_like(h)
+    prune.hessian_accumulate(x, h2)
+    _sync()
+    assert np.array_equal(to_np(h).view(np.uint32), to_np(h2).view(np.uint32))   # reproducible
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_hessian_chunks_pitch_and_empty(lib, dtype):
+    tokens, channels = 777, 520
+    wide = _acts(tokens, channels + 24, dtype, seed=9)
+    x = wide[:, 8:8 + channels]                                               # a view with a pitch: still 16-byte aligned
+    h = torch.zeros((channels, channels + 40), dtype=torch.float32, device=DEV)[:, :channels]   # pitched output
+    prune.hessian_accumulate(x[:300], h)
+    prune.hessian_accumulate(x[300:300], h)                                   # zero tokens: nothing happens
+    prune.hessian_accumulate(x[300:], h)
+    _sync()
+    want = obs.gram_matrix(to_np(x))
+    assert _scaled_err(to_np(h).astype(np.float64), want) < HESSIAN_TOL[dtype]
+    odd = wide[:, 3:3 + channels]                                             # not 16-byte aligned: the plain kernel
+    h3 = torch.zeros((channels, channels), dtype=torch.float32, device=DEV)
+    prune.hessian_accumulate(odd, h3)
+    _sync()
+    assert _scaled_err(to_np(h3).astype(np.float64), obs.gram_matrix(to_np(odd))) < 2e-5
+
+
+def test_hessian_diagonal_is_the_metric_path_statistic(lib):
+    """diag(H) is the sum of squares that the weight metric's norms come from: both paths must agree."""
+    x = _acts(4096, 768, torch.bfloat16, seed=11)
+    h = torch.zeros((768, 768), dtype=torch.float32, device=DEV)
+    prune.hessian_accumulate(x, h)
+    sumsq = torch.zeros(768, dtype=torch.float32, device=DEV)
+    prune.stats_accumulate(x, sumsq)
+    _sync()
+    want = orc.column_sumsq(to_np(x))
+    assert np.max(np.abs(to_np(h).diagonal() - want) / want) < 1e-5
+    assert np.max(np.abs(to_np(sumsq) - want) / want) < 1e-5

@@ -120,6 +120,19 @@ def test_error_paths_return_before_any_launch(lib):
     assert pd(fake, fake, fake, 1, 7, 0.5, 0.08, 9, fake, fake, fake, None) == E["rng"]
     assert pd(ctypes.c_void_p(0x1004), fake, fake, 1, 7, 0.5, 0.08, 0, fake, fake, fake, None) == E["align"]
     assert pd(fake, fake, fake, 1, 7, 0.5, 0.08, 0, fake, odd, fake, None) == E["align"]
+    ha = lib.prune_hessian_accumulate
+    assert ha(fake, 9, 8, 8, 8, fake, 8, fake, 1 << 30, None) == E["dtype"]
+    assert ha(fake, 1, 8, 0, 8, fake, 8, fake, 1 << 30, None) == E["shape"]
+    assert ha(fake, 1, 8, 16, 8, fake, 16, fake, 1 << 30, None) == E["shape"]     # ld_x < channels
+    assert ha(fake, 1, 8, 16, 16, fake, 8, fake, 1 << 30, None) == E["shape"]     # ld_h < channels
+    assert ha(fake, 1, 8, 8, 8, None, 8, fake, 1 << 30, None) == E["null"]
+    assert ha(None, 1, 8, 8, 8, fake, 8, fake, 1 << 30, None) == E["null"]
+    assert ha(odd, 1, 8, 8, 8, fake, 8, fake, 1 << 30, None) == E["align"]
+    assert ha(fake, 1, 8, 8, 8, fake, 8, fake, 16, None) == E["ws"]               # bf16, aligned: the tiled path needs room
+    assert ha(fake, 1, 8, 8, 8, fake, 8, None, 0, None) == E["null"]
+    assert ha(None, 1, 0, 8, 8, fake, 8, None, 0, None) == 0                      # zero tokens: valid no-op
+    assert lib.prune_hessian_workspace_bytes(262144, 4096) >= 136 * 256 * 256 * 4
+    assert lib.prune_hessian_workspace_bytes(0, 4096) == 0
     st = lib.prune_struct_compact
     assert st(fake, fake, fake, 1, 8, 8, 8, fake, fake, None, None, None, fake, 1 << 20, None) == E["rng"]  # r >= inter
     assert st(fake, fake, fake, 1, 8, 8, 1, fake, fake, fake, None, None, fake, 1 << 20, None) == E["null"]  # 1 of 3 outs
