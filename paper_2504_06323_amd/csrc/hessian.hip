@@ -28,20 +28,46 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kTile = 256;        // output tile edge (channels)
 constexpr int kStep = 32;         // tokens per LDS stage
+constexpr int kSets = 3;          // register sets for loads in flight
 constexpr int kPitch = 288;       // bf16 elements per LDS row: 576 bytes, so that four consecutive rows start 64 bytes
                                   // apart modulo 256 and the transpose reads of a half wave fall into distinct banks
 constexpr int kGramBlock = 256;
-constexpr int kTargetBlocks = 2048;
 constexpr int kMaxSplits = 64;
 
-// tile pair p (0-based, row by row over the upper triangle) -> (mt, nt), mt <= nt
+// Tile pairs (mt, nt), mt <= nt, are numbered patch by patch: a patch is 4 tile rows by 8 tile columns of the
+// upper triangle (32 pairs that need only 12 of the 256-channel slabs of X), patches are walked row band by
+// row band.  Pairs that are neighbours in this order share slabs.
+constexpr int kPatchRows = 4, kPatchCols = 8, kChunk = 32, kXcds = 8;
+
 __device__ __forceinline__ void pair_of(int p, int n_tiles, int &mt, int &nt) {
-    mt = 0;
-    while (p >= n_tiles - mt) {
-        p -= n_tiles - mt;
-        ++mt;
+    mt = nt = 0;
+    for (int r0 = 0; r0 < n_tiles; r0 += kPatchRows) {
+        const int r1 = r0 + kPatchRows < n_tiles ? r0 + kPatchRows : n_tiles;
+        for (int c0 = r0; c0 < n_tiles; c0 += kPatchCols) {
+            const int c1 = c0 + kPatchCols < n_tiles ? c0 + kPatchCols : n_tiles;
+            for (int r = r0; r < r1; ++r) {
+                const int lo = c0 > r ? c0 : r;
+                const int width = c1 - lo;
+                if (width <= 0) continue;
+                if (p < width) {
+                    mt = r;
+                    nt = lo + p;
+                    return;
+                }
+                p -= width;
+            }
+        }
     }
-    nt = mt + p;
+}
+
+// Work item (token split, tile pair) of a block.  Workgroups go to the chip's eight dies round robin, each
+// die has its own L2, and a die runs 32 of these blocks at a time: so die x takes items in chunks of 32
+// consecutive ones (one patch of one split, more or less), and the blocks that share an L2 share slabs.
+// Returns false for the padding blocks at the end of the grid.
+__device__ __forceinline__ bool item_of_block(int block, int n_items, int &item) {
+    const int die = block % kXcds, j = block / kXcds;
+    item = ((j / kChunk) * kXcds + die) * kChunk + j % kChunk;
+    return item < n_items;
 }
 
 // Eight consecutive tokens (k16 + 8 * (lane / 32) ...) of channel ch_base + lane % 32, as the MFMA wants them,
@@ -60,11 +86,13 @@ __device__ __forceinline__ bf16x8 operand_from_slab(const bf16_t *slab, int k16,
 
 __global__ __launch_bounds__(kGramBlock, 1) void gram_tiles_bf16(const bf16_t *__restrict__ x, int64_t n_tokens,
                                                                  int channels, int64_t ld, int n_tiles, int n_pairs,
-                                                                 int64_t tokens_per_split,
+                                                                 int n_splits, int64_t tokens_per_split,
                                                                  float *__restrict__ partials) {
     __shared__ __attribute__((aligned(16))) bf16_t slab[2][2][kStep * kPitch];  // [stage][operand]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
-    const int pair = blockIdx.x % n_pairs, split = blockIdx.x / n_pairs;
+    int item;
+    if (!item_of_block(blockIdx.x, n_pairs * n_splits, item)) return;  // the whole block, before any barrier
+    const int pair = item % n_pairs, split = item / n_pairs;
     int mt, nt;
     pair_of(pair, n_tiles, mt, nt);
     const int m0 = mt * kTile, n0 = nt * kTile;
@@ -72,30 +100,51 @@ __global__ __launch_bounds__(kGramBlock, 1) void gram_tiles_bf16(const bf16_t *_
     int64_t t_end = t_begin + tokens_per_split;
     if (t_end > n_tokens) t_end = n_tokens;
 
-    // staging: pass p moves token rows 8 p + tid / 32, channel packet tid % 32 of both slabs
+    // staging: pass p moves token rows 8 p + tid / 32, channel packet tid % 32 of both slabs.  Three register
+    // sets: the loads of a stage are issued three stages ahead of its use (memory latency under this load is
+    // more than one stage of matrix-core work), and a set is free again once it has been parked in LDS.
+    // Loads are unconditional (a load behind a branch would make every later wait a wait for all loads in
+    // flight): a packet outside the matrix is fetched from a clamped, valid address instead.  Channels past
+    // the edge only feed outputs that are never stored; token rows past the end of the range are replaced by
+    // zeros when the stage is parked.
     const int srow = tid >> 5, spkt = tid & 31;
-    const int cha = m0 + spkt * 8, chb = n0 + spkt * 8;
-    const bool a_ok = cha < channels, b_ok = chb < channels;
-    u32x4 ra[4], rb[4];
-    auto fetch = [&](int64_t t0) {
+    const int cha = m0 + spkt * 8 < channels ? m0 + spkt * 8 : 0;
+    const int chb = n0 + spkt * 8 < channels ? n0 + spkt * 8 : 0;
+    constexpr int kPasses = kStep / 8;
+    u32x4 ra[kSets][kPasses], rb[kSets][kPasses];
+    // byte offsets of this thread's packets from the first token row of a stage; the stage base is uniform
+    const uint32_t offa = static_cast<uint32_t>((srow * ld + cha) * 2), offb = static_cast<uint32_t>((srow * ld + chb) * 2);
+    const uint32_t pass_bytes = static_cast<uint32_t>(8 * ld * 2);
+    const char *xb = reinterpret_cast<const char *>(x);
+    auto fetch_inside = [&](int set, int64_t stage_index) {  // every token row of the stage exists
+        const char *base = xb + (t_begin + stage_index * kStep) * ld * 2;
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            const int64_t t = t0 + srow + 8 * p;
-            const bool in = t < t_end;
-            const u32x4 zero = {0u, 0u, 0u, 0u};
-            ra[p] = (in && a_ok) ? *reinterpret_cast<const u32x4 *>(x + t * ld + cha) : zero;
-            rb[p] = (in && b_ok) ? *reinterpret_cast<const u32x4 *>(x + t * ld + chb) : zero;
+        for (int p = 0; p < kPasses; ++p) {
+            ra[set][p] = *reinterpret_cast<const u32x4 *>(base + (offa + p * pass_bytes));
+            rb[set][p] = *reinterpret_cast<const u32x4 *>(base + (offb + p * pass_bytes));
         }
     };
-    auto park = [&](int stage) {
+    auto fetch_clamped = [&](int set, int64_t stage_index) {  // rows past the last token re-read the last one
+        const int64_t t0 = t_begin + stage_index * kStep + srow;
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
+        for (int p = 0; p < kPasses; ++p) {
+            int64_t t = t0 + 8 * p;
+            t = t < n_tokens ? t : n_tokens - 1;
+            ra[set][p] = *reinterpret_cast<const u32x4 *>(x + t * ld + cha);
+            rb[set][p] = *reinterpret_cast<const u32x4 *>(x + t * ld + chb);
+        }
+    };
+    auto park = [&](int set, int buffer, int64_t stage_index, bool ragged) {
+        const int64_t t0 = t_begin + stage_index * kStep + srow;
+#pragma unroll
+        for (int p = 0; p < kPasses; ++p) {
             const int off = (srow + 8 * p) * kPitch + spkt * 8;
-            *reinterpret_cast<u32x4 *>(&slab[stage][0][off]) = ra[p];
-            *reinterpret_cast<u32x4 *>(&slab[stage][1][off]) = rb[p];
+            const u32x4 zero = {0u, 0u, 0u, 0u};
+            const bool in = !ragged || t0 + 8 * p < t_end;
+            *reinterpret_cast<u32x4 *>(&slab[buffer][0][off]) = in ? ra[set][p] : zero;
+            *reinterpret_cast<u32x4 *>(&slab[buffer][1][off]) = in ? rb[set][p] : zero;
         }
     };
-
     f32x16 acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -104,32 +153,73 @@ __global__ __launch_bounds__(kGramBlock, 1) void gram_tiles_bf16(const bf16_t *_
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    const int64_t n_steps = (t_end - t_begin + kStep - 1) / kStep;
-    if (n_steps > 0) {
-        fetch(t_begin);
-        park(0);
-    }
-    __syncthreads();
-    for (int64_t it = 0; it < n_steps; ++it) {
-        const int cur = static_cast<int>(it & 1);
-        const bool more = it + 1 < n_steps;
-        if (more) fetch(t_begin + (it + 1) * kStep);  // in flight while the matrix cores work on this stage
+    // MFMA operands: set 0 holds tokens 0..15 of the current stage, set 1 tokens 16..31.  Every LDS read is
+    // issued at least eight MFMAs (256 cycles) before its first use, and the issue order is pinned: a wave
+    // has its SIMD to itself, so whatever latency the schedule exposes is lost.
+    bf16x8 a[2][4], b[2][4];
+    auto read_a = [&](int set, int buffer, int k16) {
 #pragma unroll
-        for (int k16 = 0; k16 < kStep; k16 += 16) {
-            bf16x8 a[4], b[4];
+        for (int i = 0; i < 4; ++i) a[set][i] = operand_from_slab(slab[buffer][0], k16, wm * 128 + 32 * i, lane);
+    };
+    auto read_b = [&](int set, int buffer, int k16) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                a[i] = operand_from_slab(slab[cur][0], k16, wm * 128 + 32 * i, lane);
-                b[i] = operand_from_slab(slab[cur][1], k16, wn * 128 + 32 * i, lane);
-            }
+        for (int i = 0; i < 4; ++i) b[set][i] = operand_from_slab(slab[buffer][1], k16, wn * 128 + 32 * i, lane);
+    };
+    auto mfma_rows = [&](int set, int i0) {
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+        for (int i = i0; i < i0 + 2; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-        }
-        if (more) park(cur ^ 1);
+            for (int j = 0; j < 4; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[set][i], b[set][j], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // Stage s travels in register set s % 3 and is used from LDS buffer s % 2.  One trip of the body:
+    //   reads of the second half of stage s | 8 MFMAs | park stage s + 1, fetch stage s + 4, more reads | 8 MFMAs |
+    //   barrier | reads of the first half of stage s + 1 | 8 MFMAs | more reads | 8 MFMAs
+    const int64_t n_stages = (t_end - t_begin + kStep - 1) / kStep;
+    const int64_t n_whole = (t_end - t_begin) / kStep;  // stages without a ragged end
+    auto body = [&](int u, int64_t s, bool steady) {
+        const int cur = u % 2, nxt = (u + 1) % 2, set = (u + 1) % 3;
+        const bool has_next = steady || s + 1 < n_stages;
+        read_a(1, cur, 16);
+        mfma_rows(0, 0);
+        if (has_next) park(set, nxt, s + 1, !steady);
+        if (steady)
+            fetch_inside(set, s + 4);
+        else
+            fetch_clamped(set, s + 4);
+        read_b(1, cur, 16);
+        mfma_rows(0, 2);
         __syncthreads();
+        if (has_next) read_a(0, nxt, 0);
+        mfma_rows(1, 0);
+        if (has_next) read_b(0, nxt, 0);
+        mfma_rows(1, 2);
+    };
+    fetch_clamped(0, 0);
+    fetch_clamped(1, 1);
+    fetch_clamped(2, 2);
+    park(0, 0, 0, true);
+    fetch_clamped(0, 3);
+    __syncthreads();
+    if (n_stages > 0) {
+        read_a(0, 0, 0);
+        read_b(0, 0, 0);
+    }
+    // Six stages per trip so that set and buffer indices are constants.  The steady state has no branches:
+    // with loads behind control flow the compiler can no longer tell how many newer loads may stay in flight
+    // at a park and waits for all of them.  It runs while stage s + 4 is still a whole one.
+    int64_t s0 = 0;
+    for (; s0 + 6 + 4 <= n_whole; s0 += 6) {
+#pragma unroll
+        for (int u = 0; u < 6; ++u) body(u, s0 + u, true);
+    }
+    for (; s0 < n_stages; s0 += 6) {  // the last trips
+#pragma unroll
+        for (int u = 0; u < 6; ++u)
+            if (s0 + u < n_stages) body(u, s0 + u, false);
     }
 
     // accumulator element v of lane l sits at row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32 of its 32 x 32 tile
@@ -146,42 +236,61 @@ __global__ __launch_bounds__(kGramBlock, 1) void gram_tiles_bf16(const bf16_t *_
             }
 }
 
-// h[tile] += sum over splits (in split order, in double) of the partial tile; the mirror image goes below the diagonal
+// h[tile] += sum over splits (in split order, in double) of the partial tile; the mirror image goes below the
+// diagonal.  A block takes 32 rows of a tile: 16-byte loads along the rows of the partials, and the transposed
+// copy goes through LDS so that it is written in 128-byte runs as well.
 __global__ __launch_bounds__(256) void gram_reduce(const float *__restrict__ partials, int n_splits, int n_pairs,
                                                    int n_tiles, int channels, float *__restrict__ h, int64_t ld_h) {
-    __shared__ float flip[32][33];
+    __shared__ float flip[32][kTile + 1];
     const int pair = blockIdx.x;
     int mt, nt;
     pair_of(pair, n_tiles, mt, nt);
     const int m0 = mt * kTile, n0 = nt * kTile;
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
-    // blockIdx.y walks the 8 x 8 sub-tiles of 32 x 32
-    const int sr = (blockIdx.y >> 3) * 32, sc = (blockIdx.y & 7) * 32;
+    const int r0 = blockIdx.y * 32;                           // first tile row of this block
+    const int c4 = (threadIdx.x & 63) * 4, rr = threadIdx.x >> 6;  // 4 columns, row rr + 4 q
+    const bool vec_ok = (ld_h % 4 == 0) && (reinterpret_cast<uintptr_t>(h) % 16 == 0);
+#pragma unroll 2
+    for (int q = 0; q < 8; ++q) {
+        const int row = r0 + rr + 4 * q;
+        double s[4] = {0.0, 0.0, 0.0, 0.0};
+        for (int sp = 0; sp < n_splits; ++sp) {
+            const f32x4 v = *reinterpret_cast<const f32x4 *>(
+                partials + (static_cast<int64_t>(sp) * n_pairs + pair) * (kTile * kTile) + row * kTile + c4);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int row = sr + ty + 8 * q, col = sc + tx;
-        double s = 0.0;
-        for (int sp = 0; sp < n_splits; ++sp)
-            s += static_cast<double>(
-                partials[(static_cast<int64_t>(sp) * n_pairs + pair) * (kTile * kTile) + row * kTile + col]);
-        const float add = static_cast<float>(s);
-        flip[ty + 8 * q][tx] = add;
-        const int gi = m0 + row, gj = n0 + col;
-        if (gi < channels && gj < channels) {  // (the rounded sum is what both triangles receive: h stays symmetric)
+            for (int e = 0; e < 4; ++e) s[e] += static_cast<double>(v[e]);
+        }
+        float add[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            add[e] = static_cast<float>(s[e]);  // the rounded sum is what both triangles receive: h stays symmetric
+            flip[rr + 4 * q][c4 + e] = add[e];
+        }
+        const int gi = m0 + row, gj = n0 + c4;
+        if (gi < channels) {
             float *dst = h + static_cast<int64_t>(gi) * ld_h + gj;
-            *dst = static_cast<float>(static_cast<double>(*dst) + static_cast<double>(add));
+            if (vec_ok && gj + 4 <= channels) {
+                f32x4 old = *reinterpret_cast<f32x4 *>(dst);
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    old[e] = static_cast<float>(static_cast<double>(old[e]) + static_cast<double>(add[e]));
+                *reinterpret_cast<f32x4 *>(dst) = old;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (gj + e < channels)
+                        dst[e] = static_cast<float>(static_cast<double>(dst[e]) + static_cast<double>(add[e]));
+            }
         }
     }
     if (mt == nt) return;  // a diagonal tile holds both of its triangles already
     __syncthreads();
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        // element (row, col) of the tile goes to h[n0 + col][m0 + row]: read the sub-tile transposed
-        const int col = sc + ty + 8 * q, row = sr + tx;
-        const int gi = n0 + col, gj = m0 + row;
+    // element (row, col) of the tile goes to h[n0 + col][m0 + row]: 32 consecutive rows make one 128-byte run
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int col = ty; col < kTile; col += 8) {
+        const int gi = n0 + col, gj = m0 + r0 + tx;
         if (gi < channels && gj < channels) {
             float *dst = h + static_cast<int64_t>(gi) * ld_h + gj;
-            *dst = static_cast<float>(static_cast<double>(*dst) + static_cast<double>(flip[tx][ty + 8 * q]));
+            *dst = static_cast<float>(static_cast<double>(*dst) + static_cast<double>(flip[tx][col]));
         }
     }
 }
@@ -227,6 +336,28 @@ __global__ __launch_bounds__(256) void gram_generic(const T *__restrict__ x, int
         }
 }
 
+// Tokens per block.  The grid is (token splits) x (tile pairs) blocks of equal work on 256 compute units, one
+// block each: the fewest splits that give at least four full rounds and leave the last round at least 97 %
+// full (else the fullest last round), in whole stages.
+int64_t tokens_per_split_for(int64_t n_tokens, int64_t n_pairs) {
+    const int64_t max_splits = ceil_div(n_tokens, kStep) < kMaxSplits ? ceil_div(n_tokens, kStep) : kMaxSplits;
+    int64_t best = 1;
+    double best_fill = 0.0;
+    for (int64_t sp = 1; sp <= max_splits; ++sp) {
+        const double rounds = static_cast<double>(sp * n_pairs) / 256.0;
+        const double fill = rounds / static_cast<double>(ceil_div(sp * n_pairs, 256));
+        if (sp * n_pairs >= 4 * 256 && fill >= 0.97) {
+            best = sp;
+            break;
+        }
+        if (fill > best_fill + 1e-9) {
+            best_fill = fill;
+            best = sp;
+        }
+    }
+    return ceil_div(ceil_div(n_tokens, best), kStep) * kStep;
+}
+
 struct GramPlan {
     bool mfma;
     int n_tiles, n_pairs, n_splits;
@@ -235,13 +366,11 @@ struct GramPlan {
 
 GramPlan plan_gram(const void *x, int dtype, int64_t n_tokens, int64_t channels, int64_t ld) {
     GramPlan g = {};
-    g.mfma = dtype == PRUNE_BF16 && packet_ok(x, channels, ld) && channels <= 65536 && n_tokens > 0;
+    g.mfma = dtype == PRUNE_BF16 && packet_ok(x, channels, ld) && channels <= 65536 && ld <= (1 << 24) && n_tokens > 0;
     if (!g.mfma) return g;
     g.n_tiles = static_cast<int>(ceil_div(channels, kTile));
     g.n_pairs = g.n_tiles * (g.n_tiles + 1) / 2;
-    int64_t want = ceil_div(kTargetBlocks, g.n_pairs);
-    if (want > kMaxSplits) want = kMaxSplits;
-    int64_t per = ceil_div(ceil_div(n_tokens, want), kStep) * kStep;
+    const int64_t per = tokens_per_split_for(n_tokens, g.n_pairs);
     g.tokens_per_split = per;
     g.n_splits = static_cast<int>(ceil_div(n_tokens, per));
     return g;
@@ -253,9 +382,7 @@ size_t hessian_workspace_bytes(int64_t n_tokens, int64_t channels) {
     // sized for the matrix-core path whether or not a particular call can take it
     if (n_tokens <= 0 || channels <= 0) return 0;
     const int64_t n_tiles = ceil_div(channels, kTile), n_pairs = n_tiles * (n_tiles + 1) / 2;
-    int64_t want = ceil_div(kTargetBlocks, n_pairs);
-    if (want > kMaxSplits) want = kMaxSplits;
-    const int64_t per = ceil_div(ceil_div(n_tokens, want), kStep) * kStep;
+    const int64_t per = tokens_per_split_for(n_tokens, n_pairs);
     const int64_t n_splits = ceil_div(n_tokens, per);
     return static_cast<size_t>(n_splits * n_pairs) * kTile * kTile * sizeof(float);
 }
@@ -284,11 +411,12 @@ extern "C" int prune_hessian_accumulate(const void *x, int dtype, int64_t n_toke
         if (!ws) return PRUNE_ERR_NULL;
         if (ws_bytes < need) return PRUNE_ERR_WORKSPACE;
         float *partials = static_cast<float *>(ws);
-        hipLaunchKernelGGL(gram_tiles_bf16, dim3(static_cast<unsigned>(g.n_splits * g.n_pairs)), dim3(kGramBlock), 0,
+        const int64_t n_chunks = ceil_div(ceil_div(static_cast<int64_t>(g.n_splits) * g.n_pairs, kChunk), kXcds) * kXcds;
+        hipLaunchKernelGGL(gram_tiles_bf16, dim3(static_cast<unsigned>(n_chunks * kChunk)), dim3(kGramBlock), 0,
                            stream, static_cast<const bf16_t *>(x), n_tokens, static_cast<int>(channels), ld_x,
-                           g.n_tiles, g.n_pairs, g.tokens_per_split, partials);
+                           g.n_tiles, g.n_pairs, g.n_splits, g.tokens_per_split, partials);
         if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
-        hipLaunchKernelGGL(gram_reduce, dim3(static_cast<unsigned>(g.n_pairs), 64), dim3(256), 0, stream, partials,
+        hipLaunchKernelGGL(gram_reduce, dim3(static_cast<unsigned>(g.n_pairs), kTile / 32), dim3(256), 0, stream, partials,
                            g.n_splits, g.n_pairs, g.n_tiles, static_cast<int>(channels), h, ld_h);
         return launch_status();
     }

@@ -82,3 +82,38 @@ def test_hessian_diagonal_is_the_metric_path_statistic(lib):
     want = orc.column_sumsq(to_np(x))
     assert np.max(np.abs(to_np(h).diagonal() - want) / want) < 1e-5
     assert np.max(np.abs(to_np(sumsq) - want) / want) < 1e-5
+
+
+# ----------------------------------------------------------------- full size (the benchmark's launch configuration)
+
+@pytest.mark.parametrize("act", ["attn_in", "down_in"])
+def test_hessian_fullsize_sampled(lib, act):
+    """One activation tensor of the LLaMA-7B-shaped layer (262144 tokens x 4096 or 11008 channels): sampled
+    rows of H against the oracle (whole rows would need teraflops on the host), symmetry over the whole matrix,
+    and the diagonal against the metric path's sums of squares."""
+    cfg = synth.CONFIGS["llama7b_layer"]
+    x = synth.make_activation(cfg, 0, act, DEV)
+    tokens, channels = x.shape
+    h = torch.zeros((channels, channels), dtype=torch.float32, device=DEV)
+    ws = torch.empty(prune.hessian_workspace_bytes(tokens, channels), dtype=torch.uint8, device=DEV)
+    prune.hessian_accumulate(x, h, ws=ws)
+    _sync()
+    assert bool(torch.equal(h, h.t()))
+    rng = np.random.default_rng(channels)
+    hot = torch.argsort(torch.diagonal(h))[-2:].cpu().numpy()                 # planted outlier channels
+    rows = np.unique(np.concatenate([rng.choice(channels, size=6, replace=False), hot, [0, 255, 256, channels - 1]]))
+    cols = np.unique(np.concatenate([rng.choice(channels, size=40, replace=False), rows]))
+    xr = to_np(x[:, torch.as_tensor(rows, device=DEV)]).astype(np.float64)
+    xc = to_np(x[:, torch.as_tensor(cols, device=DEV)]).astype(np.float64)
+    want = xr.T @ xc                                                          # the oracle's definition on the sample
+    got = to_np(h)[np.ix_(rows, cols)].astype(np.float64)
+    diag = to_np(torch.diagonal(h)).astype(np.float64)
+    scale = np.sqrt(np.outer(diag[rows], diag[cols]))
+    # worst case for fp32 sums over a split of the tokens: (k-steps per split + 16) * 2^-24 of sum |x_i x_j|;
+    # 262144 tokens in >= 4 splits of <= 4096 k-steps: 2.5e-4; the sums behave like random walks, far below that
+    assert np.max(np.abs(got - want) / scale) < 2.5e-4
+    assert np.max(np.abs(got - want) / scale) < 5e-6
+    sumsq = torch.zeros(channels, dtype=torch.float32, device=DEV)
+    prune.stats_accumulate(x, sumsq)
+    _sync()
+    assert np.max(np.abs(diag / to_np(sumsq).astype(np.float64) - 1.0)) < 1e-5
