@@ -94,8 +94,79 @@ def cpu_baseline(cfg, shapes, weights, acts, frac_den=8):
                       f"NumPy float64, {dt:.1f} s"}
 
 
+def run_hessian_stage(args):
+    """--stage hessian: the matrix-core stage of the Hessian-based pruner on the workload's activation tensors.
+
+    A step is H += X^T X for each of the layer's four distinct projection inputs.  Prints its own JSON line."""
+    import numpy as np
+    import torch
+    from paper_2504_06323_amd import prune, synth
+
+    prune.load()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.workload]
+    act_shapes = synth.activation_shapes(cfg)
+    acts = {a: synth.make_activation(cfg, 0, a, dev) for a in act_shapes}
+    hs = {a: torch.zeros((c, c), dtype=torch.float32, device=dev) for a, c in act_shapes.items()}
+    need = max(prune.hessian_workspace_bytes(x.shape[0], x.shape[1]) for x in acts.values())
+    ws = torch.empty(need, dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    flops = {a: x.shape[0] * x.shape[1] * (x.shape[1] + 1) for a, x in acts.items()}   # the upper triangle, 2 per MAC
+    big = max(act_shapes, key=lambda a: act_shapes[a])
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    events = []
+
+    def step(record):
+        for a, x in acts.items():
+            if record and a == big:
+                e0, e1 = ev(), ev()
+                e0.record()
+            prune.hessian_accumulate(x, hs[a], ws=ws)
+            if record and a == big:
+                e1.record()
+                events.append((e0, e1))
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms = 1e3 * elapsed / args.steps
+    launch_ms = sum(a.elapsed_time(b) for a, b in events) / len(events)
+    achieved = flops[big] / (launch_ms * 1e-3) / 1e12
+    out = {"metric": "Hessian accumulation H += X^T X for the four projection inputs of a layer (algorithmic TFLOP/s)",
+           "value": sum(flops.values()) / (ms * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"{cfg.name}: activation tensors {[list(x.shape) for x in acts.values()]}, bf16, "
+                                  f"fp32 accumulation, symmetric: T * C * (C + 1) flops per tensor"},
+           "roofline": {"bound": "mfma", "kernel": f"gram_tiles_bf16 + gram_reduce on [{acts[big].shape[0]}, {acts[big].shape[1]}]",
+                        "achieved": round(achieved, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                        "frac": round(achieved / 2500.0, 4), "traffic": None,
+                        "avg_launch_ms": round(launch_ms, 4), "launches": len(events)}}
+    if not args.no_cpu_baseline:
+        from oracle import obs_oracle as obs
+        sample = acts[big][:2048].detach().cpu().to(torch.float32).numpy()
+        t0 = time.perf_counter()
+        obs.gram_matrix(sample)
+        dt = time.perf_counter() - t0
+        c = sample.shape[1]
+        out["cpu_baseline"] = {"value": sample.shape[0] * c * (c + 1) / dt / 1e12, "unit": "TFLOP/s",
+                               "cores": len(os.sched_getaffinity(0)), "kind": "oracle",
+                               "sample": f"2048 tokens of the [{acts[big].shape[0]}, {c}] tensor, NumPy float64 matmul, {dt:.1f} s"}
+    log(f"hessian stage: {ms:.3f} ms per layer; {big} {launch_ms:.3f} ms = {achieved:.0f} TFLOP/s algorithmic")
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
+    ap.add_argument("--stage", default="prune", choices=["prune", "hessian"],
+                    help="prune (default): the scoring / masking / structured path the headline metric is quoted on; "
+                         "hessian: the matrix-core stage of the Hessian-based pruner, its own JSON line")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
@@ -112,6 +183,10 @@ def main():
         log("bench.py measures one GPU: every box of this build has one MI355X and the path has no "
             "multi-GPU leg. Run with --gpus 1.")
         sys.exit(2)
+
+    if args.stage == "hessian":
+        run_hessian_stage(args)
+        return
 
     import torch
     from paper_2504_06323_amd import pipeline, prune, synth
