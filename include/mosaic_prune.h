@@ -307,6 +307,22 @@ size_t prune_hessian_workspace_bytes(int64_t n_tokens, int64_t channels);
 int prune_hessian_accumulate(const void *x, int dtype, int64_t n_tokens, int64_t channels, int64_t ld_x, float *h,
                              int64_t ld_h, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * Factor of the damped Hessian.  In place on h (DEVICE fp32 [n, n], pitch ld_h, symmetric, as left by
+ * prune_hessian_accumulate):
+ *   1. dead[j] = (h[j, j] == 0) (DEVICE uint8 [n], nullable); such channels get h[j, j] = 1
+ *   2. h[j, j] += damp * mean_j(h[j, j])
+ *   3. the upper triangle of h (diagonal included) becomes R, upper triangular with positive diagonal and
+ *      R R^T = h; R is the inverse of the upper Cholesky factor U of h^-1 (h^-1 = U^T U) that the published
+ *      pruner is written with.  The strictly lower triangle is left unspecified.
+ * info (DEVICE int, nullable): 0, or the 1-based index of a pivot that was not positive (the factor then
+ * holds NaNs).  n and ld_h must be multiples of 4, h 16-byte aligned.
+ * ws_bytes >= prune_hessian_factor_workspace_bytes(n).  fp32 throughout.
+ */
+size_t prune_hessian_factor_workspace_bytes(int64_t n);
+int prune_hessian_factor(float *h, int64_t n, int64_t ld_h, double damp, uint8_t *dead, int *info, void *ws,
+                         size_t ws_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

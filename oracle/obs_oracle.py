@@ -33,6 +33,7 @@ Parity status:
   gram_matrix          pinned (brute-force loops, diagonal = column sums of squares, rank-1 closed form)
   damped_hessian       PARITY UNPINNED against the paper (it states no damping); pinned by hand example
   inverse_factor       pinned (U^T U H = I, triangular with positive diagonal, hand-worked 2 x 2)
+  reverse_factor       pinned (R R^T = H, triangular, equals the Cholesky factor of the reversed matrix)
   select_block         pinned (brute-force sort)
   obs_sweep            pinned: identity Hessian reduces it to magnitude pruning without update; a single
                        pruned weight gives the closed-form Optimal Brain Surgeon update; for any mask the
@@ -70,6 +71,11 @@ def damped_hessian(h, damp: float = DAMP):
 def inverse_factor(h) -> np.ndarray:
     """Upper triangular U with positive diagonal and U^T U = H^-1."""
     return np.linalg.cholesky(np.linalg.inv(_f64(h))).T
+
+
+def reverse_factor(h) -> np.ndarray:
+    """Upper triangular R with positive diagonal and R R^T = H: the inverse of inverse_factor(h)."""
+    return np.linalg.inv(inverse_factor(h))
 
 
 def block_saliency(w_block, u_diag) -> np.ndarray:

@@ -1,0 +1,131 @@
+// fp32 matrix product on the matrix cores, the workhorse of the Hessian factorisation and of the
+// compensated sweep:   C = beta * C + alpha * A * op(B)
+// A [M, K] row-major; op(B) = B for B [K, N] row-major (kBKN) or B^T for B [N, K] row-major (kBNK);
+// C [M, N] row-major.  K and every leading dimension are multiples of 4 and all bases 16-byte aligned
+// (checked by the callers), M and N are arbitrary.  A block of four waves owns a 128 x 128 tile of C
+// (64 x 64 per wave, four 32 x 32 x 2 MFMA accumulators), K is walked 16 at a time through LDS with both
+// operands stored k-major so that a wave reads 32 consecutive floats per MFMA operand.  One owner per
+// output element and a fixed order over K: results are reproducible.  C may be the same memory as A when N <= 128
+// (a block then reads all of its rows of A before it writes them).
+#pragma once
+
+#include "common.hpp"
+
+namespace mp {
+
+enum GemmB { kBKN = 0, kBNK = 1 };
+
+namespace gemm_detail {
+
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+constexpr int kTileMN = 128, kTileK = 16, kPitch = kTileMN + 4;
+
+template <int BL>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, float alpha, const float *A, int64_t lda,
+                                                       const float *B, int64_t ldb, float beta, float *C,
+                                                       int64_t ldc,
+                                                       int upper_tiles_only) {
+    __shared__ float sa[kTileK][kPitch], sb[kTileK][kPitch];
+    const int m0 = blockIdx.y * kTileMN, n0 = blockIdx.x * kTileMN;
+    if (upper_tiles_only && n0 + kTileMN <= m0) return;  // tile strictly below the diagonal: not needed
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    for (int k0 = 0; k0 < K; k0 += kTileK) {
+        // A tile: rows m0 .. m0 + 127, four consecutive k per thread and pass
+#pragma unroll
+        for (int p = 0; p < 2; ++p) {
+            const int r = (tid >> 2) + 64 * p, kk = (tid & 3) * 4;
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (m0 + r < M && k0 + kk < K) v = *reinterpret_cast<const f32x4 *>(A + (m0 + r) * lda + k0 + kk);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sa[kk + e][r] = v[e];
+        }
+        if (BL == kBNK) {
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const int r = (tid >> 2) + 64 * p, kk = (tid & 3) * 4;
+                f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                if (n0 + r < N && k0 + kk < K) v = *reinterpret_cast<const f32x4 *>(B + (n0 + r) * ldb + k0 + kk);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) sb[kk + e][r] = v[e];
+            }
+        } else {
+#pragma unroll
+            for (int p = 0; p < 2; ++p) {
+                const int kk = (tid >> 5) + 8 * p, c = (tid & 31) * 4;
+                f32x4 v = {0.f, 0.f, 0.f, 0.f};
+                if (k0 + kk < K) {
+                    const float *src = B + (k0 + kk) * ldb + n0 + c;
+                    if (n0 + c + 4 <= N) {
+                        v = *reinterpret_cast<const f32x4 *>(src);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (n0 + c + e < N) v[e] = src[e];
+                    }
+                }
+                *reinterpret_cast<f32x4 *>(&sb[kk][c]) = v;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < kTileK; kk += 2) {
+            const int k = kk + (lane >> 5), c = lane & 31;
+            float a[2], b[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                a[i] = sa[k][wm + 32 * i + c];
+                b[i] = sb[k][wn + 32 * i + c];
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+    // accumulator element v of lane l: row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32 of its 32 x 32 tile
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = m0 + wm + 32 * i + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                const int col = n0 + wn + 32 * j + (lane & 31);
+                if (row < M && col < N) {
+                    float *dst = C + row * ldc + col;
+                    const float prod = alpha * acc[i][j][v];
+                    *dst = beta == 0.f ? prod : beta * *dst + prod;
+                }
+            }
+}
+
+}  // namespace gemm_detail
+
+inline bool gemm_operands_ok(const void *a, int64_t lda, const void *b, int64_t ldb, const void *c, int64_t K) {
+    return aligned_to(a, 16) && aligned_to(b, 16) && aligned_to(c, 4) && lda % 4 == 0 && ldb % 4 == 0 && K % 4 == 0;
+}
+
+// C = beta * C + alpha * A * op(B) on `stream`; upper_tiles_only skips the 128 x 128 tiles strictly below
+// the diagonal of C (for symmetric updates of which only the upper triangle is used).  M, N < 2^31 / 128.
+template <int BL>
+inline int launch_gemm_f32(int M, int N, int K, float alpha, const float *A, int64_t lda, const float *B, int64_t ldb,
+                           float beta, float *C, int64_t ldc, bool upper_tiles_only, hipStream_t stream) {
+    if (M <= 0 || N <= 0) return PRUNE_OK;
+    const dim3 grid(static_cast<unsigned>(ceil_div(N, gemm_detail::kTileMN)),
+                    static_cast<unsigned>(ceil_div(M, gemm_detail::kTileMN)));
+    if (grid.y > 65535) return PRUNE_ERR_SHAPE;
+    hipLaunchKernelGGL(gemm_detail::gemm_f32_kernel<BL>, grid, dim3(256), 0, stream, M, N, K, alpha, A, lda, B, ldb,
+                       beta, C, ldc, upper_tiles_only ? 1 : 0);
+    return launch_status();
+}
+
+}  // namespace mp

@@ -43,6 +43,8 @@ _SIGNATURES = {
     "prune_select_mask_batch": (_int, [_vp, _int, _int, _vp, _sz, _vp]),
     "prune_hessian_workspace_bytes": (_sz, [_i64, _i64]),
     "prune_hessian_accumulate": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _i64, _vp, _sz, _vp]),
+    "prune_hessian_factor_workspace_bytes": (_sz, [_i64]),
+    "prune_hessian_factor": (_int, [_vp, _i64, _i64, _f64, _vp, _vp, _vp, _sz, _vp]),
     "prune_plan_sparsity_device": (_int, [_vp, _vp, _vp, _int, _int, _f64, _f64, _int, _vp, _vp, _vp, _vp]),
     "prune_struct_groups_workspace_bytes": (_sz, [_vp, _vp, _int, _vp, _vp, _int, _i64]),
     "prune_struct_groups": (_int, [_vp, _vp, _vp, _int, _vp, _vp, _vp, _int, _int, _i64, _u32, _vp, _vp, _vp, _vp,
@@ -367,6 +369,20 @@ def hessian_accumulate(x: torch.Tensor, h: torch.Tensor, ws: Optional[torch.Tens
     _check("prune_hessian_accumulate",
            load().prune_hessian_accumulate(ptr, _dtype_code(x), n_tokens, channels, ld, h.data_ptr(), h.stride(0),
                                            ws_ptr, ws_bytes, _stream(stream)))
+
+
+def hessian_factor(h: torch.Tensor, damp: float = 0.01, dead: Optional[torch.Tensor] = None,
+                   info: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None, stream=None) -> None:
+    """Damp h and replace its upper triangle by R with R R^T = h (prune_hessian_factor).
+    dead: uint8 [n] (out), info: int32 [1] (out)."""
+    if not (h.is_cuda and h.dtype == torch.float32 and h.dim() == 2 and h.shape[0] == h.shape[1] and h.stride(1) == 1):
+        raise ValueError("h must be a square float32 GPU matrix with unit column stride")
+    n = h.shape[0]
+    need = int(load().prune_hessian_factor_workspace_bytes(n))
+    ws_ptr, ws_bytes, keep = _workspace(ws, need, h.device)
+    _check("prune_hessian_factor",
+           load().prune_hessian_factor(h.data_ptr(), n, h.stride(0), float(damp), _vector(dead, "dead", torch.uint8, n),
+                                       _vector(info, "info", torch.int32, 1), ws_ptr, ws_bytes, _stream(stream)))
 
 
 def struct_compact(gate: torch.Tensor, up: torch.Tensor, down: torch.Tensor, r: int, group_mag: torch.Tensor,

@@ -117,3 +117,49 @@ def test_hessian_fullsize_sampled(lib, act):
     prune.stats_accumulate(x, sumsq)
     _sync()
     assert np.max(np.abs(diag / to_np(sumsq).astype(np.float64) - 1.0)) < 1e-5
+
+
+# ----------------------------------------------------------------- damping and factorisation
+
+def _factor_err(r_gpu, r_ref):
+    """max |R_gpu - R_ref| over the upper triangle, relative to the largest entry of R."""
+    iu = np.triu_indices_from(r_ref)
+    return float(np.max(np.abs(r_gpu[iu] - r_ref[iu])) / np.max(np.abs(r_ref)))
+
+
+@pytest.mark.parametrize("n,tokens,dead_cols", [(256, 1024, ()), (688, 2048, (5, 300)), (132, 400, ()), (1540, 4096, (0,)),
+                                                (8, 32, ())])
+def test_factor_vs_oracle(lib, n, tokens, dead_cols):
+    """Damped Hessian and its factor R (R R^T = H', R = U^-1 with U the oracle's inverse factor)."""
+    x = _acts(tokens, n, torch.bfloat16, seed=n)
+    for c in dead_cols:
+        x[:, c] = 0
+    h = torch.zeros((n, n), dtype=torch.float32, device=DEV)
+    prune.hessian_accumulate(x, h)
+    _sync()
+    h0 = to_np(h).astype(np.float64)                        # the factorisation is checked on the kernel's own Hessian
+    dead = torch.full((n,), 7, dtype=torch.uint8, device=DEV)
+    info = torch.full((1,), -1, dtype=torch.int32, device=DEV)
+    prune.hessian_factor(h, 0.01, dead=dead, info=info)
+    _sync()
+    want_h, want_dead = obs.damped_hessian(h0, 0.01)
+    assert info.item() == 0 and np.array_equal(to_np(dead).astype(bool), want_dead)
+    assert sorted(np.nonzero(want_dead)[0].tolist()) == sorted(dead_cols)
+    r_gpu = np.triu(to_np(h).astype(np.float64))
+    r_ref = obs.reverse_factor(want_h)
+    # fp32 factorisation of a matrix with condition number about 40 here (the x20 outlier channel squared over the
+    # damped bulk): errors of a few 2^-24 * condition * sqrt(n)
+    assert _factor_err(r_gpu, r_ref) < 2e-5
+    assert np.max(np.abs(r_gpu @ r_gpu.T - want_h)) / np.max(np.abs(want_h)) < 1e-5
+    u_ref = obs.inverse_factor(want_h)
+    assert np.max(np.abs(np.linalg.inv(r_gpu) - u_ref)) / np.max(np.abs(u_ref)) < 1e-4
+    assert (np.diag(r_gpu) > 0).all()
+
+
+def test_factor_reports_a_bad_pivot(lib):
+    h = torch.eye(64, dtype=torch.float32, device=DEV)
+    h[40, 40] = -3.0                                        # not positive definite (and the damping cannot fix it)
+    info = torch.zeros(1, dtype=torch.int32, device=DEV)
+    prune.hessian_factor(h, 0.01, info=info)
+    _sync()
+    assert info.item() == 41

@@ -133,6 +133,16 @@ def test_error_paths_return_before_any_launch(lib):
     assert ha(None, 1, 0, 8, 8, fake, 8, None, 0, None) == 0                      # zero tokens: valid no-op
     assert lib.prune_hessian_workspace_bytes(262144, 4096) >= 136 * 256 * 256 * 4
     assert lib.prune_hessian_workspace_bytes(0, 4096) == 0
+    hf = lib.prune_hessian_factor
+    assert hf(fake, 0, 8, 0.01, None, None, fake, 1 << 20, None) == E["shape"]
+    assert hf(fake, 8, 4, 0.01, None, None, fake, 1 << 20, None) == E["shape"]       # ld_h < n
+    assert hf(fake, 6, 8, 0.01, None, None, fake, 1 << 20, None) == E["shape"]       # n must be a multiple of 4
+    assert hf(None, 8, 8, 0.01, None, None, fake, 1 << 20, None) == E["null"]
+    assert hf(fake, 8, 8, 0.01, None, None, None, 0, None) == E["null"]
+    assert hf(fake, 8, 8, -1.0, None, None, fake, 1 << 20, None) == E["rng"]
+    assert hf(ctypes.c_void_p(0x1004), 8, 8, 0.01, None, None, fake, 1 << 20, None) == E["align"]
+    assert hf(fake, 8, 8, 0.01, None, None, fake, 16, None) == E["ws"]
+    assert lib.prune_hessian_factor_workspace_bytes(4096) >= 128 * 128 * 4
     st = lib.prune_struct_compact
     assert st(fake, fake, fake, 1, 8, 8, 8, fake, fake, None, None, None, fake, 1 << 20, None) == E["rng"]  # r >= inter
     assert st(fake, fake, fake, 1, 8, 8, 1, fake, fake, fake, None, None, fake, 1 << 20, None) == E["null"]  # 1 of 3 outs

@@ -54,6 +54,8 @@ def test_inverse_factor_hand_example_and_identities():
     rev = np.linalg.cholesky(h[::-1, ::-1])[::-1, ::-1]
     assert np.allclose(rev, np.triu(rev)) and np.allclose(rev @ rev.T, h, rtol=1e-12)
     assert np.allclose(u, np.linalg.inv(rev), rtol=1e-9, atol=1e-12)
+    r = obs.reverse_factor(h)
+    assert np.allclose(r, rev, rtol=1e-9, atol=1e-12) and np.allclose(r @ r.T, h, rtol=1e-10)
     assert np.allclose(obs.inverse_factor(4.0 * np.eye(3)), 0.5 * np.eye(3))
 
 
