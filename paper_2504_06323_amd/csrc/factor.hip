@@ -53,42 +53,162 @@ __global__ __launch_bounds__(256) void factor_diagonal_block(float *__restrict__
                                                              float *__restrict__ dinv, int *__restrict__ info) {
     __shared__ float d[kNB][kDiagPitch];
     __shared__ float u[kNB][kDiagPitch];
-    const int tid = threadIdx.x;
-    for (int e = tid; e < kNB * kNB; e += 256) {
-        const int i = e / kNB, k = e % kNB;
-        d[i][k] = (i < sz && k < sz && i <= k) ? h[(c0 + i) * ld + c0 + k] : 0.f;
-        u[i][k] = 0.f;
-    }
-    __syncthreads();
-    // last column first: r_jj = sqrt(d_jj); R[i][j] = d[i][j] / r_jj (i < j); d[i][k] -= R[i][j] R[k][j] (i <= k < j)
-    for (int j = sz - 1; j >= 0; --j) {
-        const float pivot = d[j][j];
-        if (tid == 0 && !(pivot > 0.f) && info) atomicMax(info, static_cast<int>(c0) + j + 1);
-        const float rjj = sqrtf(pivot);
-        __syncthreads();
-        for (int i = tid; i < j; i += 256) d[i][j] = d[i][j] / rjj;
-        if (tid == 0) d[j][j] = rjj;
-        __syncthreads();
-        // the j (j + 1) / 2 entries (i <= k < j) of the leading triangle, row by row
-        for (int e = tid; e < j * j; e += 256) {
-            const int i = e / j, k = e % j;
-            if (i <= k) d[i][k] = fmaf(-d[i][j], d[k][j], d[i][k]);
+    __shared__ float col[kNB];
+    __shared__ float piv;
+    const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+    // The factorisation keeps the block in registers: thread (ty, tx) of a 16 x 16 grid owns the entries
+    // (ty + 16 a, tx + 16 b), a, b = 0..7; only the scaled column of a step travels through LDS, so no step waits
+    // on a read-modify-write of LDS.
+    float t[8][8];
+#pragma unroll
+    for (int a = 0; a < 8; ++a)
+#pragma unroll
+        for (int b2 = 0; b2 < 8; ++b2) {
+            const int i = ty + 16 * a, k = tx + 16 * b2;
+            t[a][b2] = (i < sz && k < sz && i <= k) ? h[(c0 + i) * ld + c0 + k] : 0.f;
         }
-        __syncthreads();
+    for (int e = tid; e < kNB * kDiagPitch; e += 256) {
+        (&d[0][0])[e] = 0.f;
+        (&u[0][0])[e] = 0.f;
     }
-    for (int e = tid; e < kNB * kNB; e += 256) {
-        const int i = e / kNB, k = e % kNB;
-        if (i < sz && k < sz && i <= k) h[(c0 + i) * ld + c0 + k] = d[i][k];
+    if (tid < kNB) col[tid] = 0.f;
+    __syncthreads();
+    // last column first: r_jj = sqrt(d_jj); R[i][j] = d[i][j] / r_jj (i < j); d[i][k] -= R[i][j] R[k][j] (i <= k < j).
+    // The 16-wide group jb of column j is a compile-time constant of the unrolled outer loop, so every register
+    // of t is addressed statically; jt = j % 16 runs inside.
+    const int last = sz - 1;
+#pragma unroll
+    for (int jb = 7; jb >= 0; --jb) {
+        if (jb > (last >> 4)) continue;  // uniform: groups past the live part
+        for (int jt = (jb == (last >> 4) ? (last & 15) : 15); jt >= 0; --jt) {
+            const int j = 16 * jb + jt;
+            if (ty == jt && tx == jt) {
+                const float pivot = t[jb][jb];
+                if (!(pivot > 0.f) && info) atomicMax(info, static_cast<int>(c0) + j + 1);
+                piv = sqrtf(pivot);
+            }
+            __syncthreads();
+            const float rjj = piv;
+            if (tx == jt) {
+#pragma unroll
+                for (int a = 0; a <= jb; ++a) {
+                    const int i = ty + 16 * a;
+                    if (i < j) t[a][jb] = t[a][jb] / rjj;
+                    if (i == j) t[a][jb] = rjj;
+                    if (i <= j) col[i] = t[a][jb];
+                }
+            }
+            __syncthreads();
+            // Entries (i <= k < j) must be downdated.  Entries below the diagonal are never read, so they may be
+            // updated along with the rest (with whatever col holds for them); the one condition left is k < j in
+            // the column group of j itself.
+            float ci[8], ck[8];
+#pragma unroll
+            for (int a = 0; a <= jb; ++a) {
+                ci[a] = col[ty + 16 * a];
+                ck[a] = col[tx + 16 * a];
+            }
+            ck[jb] = tx < jt ? ck[jb] : 0.f;
+#pragma unroll
+            for (int b2 = 0; b2 <= jb; ++b2)
+#pragma unroll
+                for (int a = 0; a <= jb; ++a) t[a][b2] = fmaf(-ci[a], ck[b2], t[a][b2]);
+            // (the next step's writes to col and piv come after its first barrier, which every thread reaches only
+            // after these reads)
+        }
     }
-    // inverse of the triangle, one column per thread: u_jj = 1 / r_jj, u_ij = -(sum_{k = i+1..j} r_ik u_kj) / r_ii
-    if (tid < sz) {
-        const int j = tid;
+#pragma unroll
+    for (int a = 0; a < 8; ++a)
+#pragma unroll
+        for (int b2 = 0; b2 < 8; ++b2) {
+            const int i = ty + 16 * a, k = tx + 16 * b2;
+            if (i < sz && k < sz && i <= k) {
+                h[(c0 + i) * ld + c0 + k] = t[a][b2];
+                d[i][k] = t[a][b2];
+            }
+        }
+    __syncthreads();
+    // Inverse of the triangle by doubling.  The eight 16 x 16 diagonal blocks are inverted directly, one column
+    // per thread (u_jj = 1 / r_jj, u_ij = -(sum_{k = i+1..j} r_ik u_kj) / r_ii); then blocks are merged pairwise:
+    //   inv [A B; 0 D] = [inv A, -inv A * B * inv D; 0, inv D]
+    // with the intermediate B * inv D parked in the unused lower triangle of d.  Rows and columns past sz carry a
+    // unit diagonal, which leaves the live part unchanged.
+    if (tid < kNB && tid >= sz) d[tid][tid] = 1.f;
+    __syncthreads();
+    if (tid < kNB) {
+        const int j = tid, lo = j & ~15;
         u[j][j] = 1.f / d[j][j];
-        for (int i = j - 1; i >= 0; --i) {
+        for (int i = j - 1; i >= lo; --i) {
             float acc = 0.f;
             for (int k = i + 1; k <= j; ++k) acc = fmaf(d[i][k], u[k][j], acc);
             u[i][j] = -acc / d[i][i];
         }
+    }
+    __syncthreads();
+    for (int s = 16, ls = 4; s < kNB; s *= 2, ++ls) {
+        // Every pair of this level is an s x s product, cut into 4 x 4 micro-tiles: (kNB / 2s) (s / 4)^2 = 8 s
+        // micro-tiles, one per thread (s = 64 uses all 256).  Zeros below the diagonals of inv(A) and inv(D)
+        // make the plain products right.
+        const int q4 = ls - 2;                       // log2 of micro-tiles per row of a pair
+        const bool active = tid < 8 * s;
+        const int pair = tid >> (2 * q4), tr = (tid >> q4) & ((1 << q4) - 1), tc = tid & ((1 << q4) - 1);
+        const int p = 2 * s * pair, r0 = 4 * tr, cc0 = 4 * tc;
+        float acc[4][4];
+        // T = B * inv(D): element (r, c) -> d[p + s + r][p + c]
+        if (active) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) acc[i][jj] = 0.f;
+#pragma unroll 4
+            for (int k = 0; k < s; ++k) {
+                float av[4], bv[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    av[i] = d[p + r0 + i][p + s + k];
+                    bv[i] = u[p + s + k][p + s + cc0 + i];
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) acc[i][jj] = fmaf(av[i], bv[jj], acc[i][jj]);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) d[p + s + r0 + i][p + cc0 + jj] = acc[i][jj];
+        }
+        __syncthreads();
+        // inv(B-part) = -inv(A) * T
+        if (active) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) acc[i][jj] = 0.f;
+#pragma unroll 4
+            for (int k = 0; k < s; ++k) {
+                float av[4], bv[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    av[i] = u[p + r0 + i][p + k];
+                    bv[i] = d[p + s + k][p + cc0 + i];
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int jj = 0; jj < 4; ++jj) acc[i][jj] = fmaf(av[i], bv[jj], acc[i][jj]);
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) u[p + r0 + i][p + s + cc0 + jj] = -acc[i][jj];
+        }
+        __syncthreads();
+    }
+    // only the live sz x sz part is handed on; the rest of dinv is zero
+    for (int e = tid; e < kNB * kNB; e += 256) {
+        const int i = e / kNB, k = e % kNB;
+        if (i >= sz || k >= sz) u[i][k] = 0.f;
     }
     __syncthreads();
     for (int e = tid; e < kNB * kNB; e += 256) dinv[e] = u[e / kNB][e % kNB];
