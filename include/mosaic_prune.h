@@ -323,6 +323,31 @@ size_t prune_hessian_factor_workspace_bytes(int64_t n);
 int prune_hessian_factor(float *h, int64_t n, int64_t ld_h, double damp, uint8_t *dead, int *info, void *ws,
                          size_t ws_bytes, void *stream);
 
+/*
+ * The compensated sweep of the one-shot pruner over one projection, with the sparsity target the planner
+ * assigned to it.  Columns are processed left to right in blocks of 128.  When a block starts, the saliency of
+ * entry (i, j) is (current w[i, j] / U[j, j])^2 with U = R^-1; the floor(sparsity * rows * width) entries of the
+ * block with the smallest saliency are pruned (all rows compete together; equal saliencies go by row-major
+ * position in the block); column by column a pruned entry becomes 0, a kept one keeps its current value, and the
+ * error is spread over all later columns so that the layer's output on the calibration data changes least.
+ *   w, w_out: DEVICE [rows, cols] of dtype, pitches ld_w / ld_out; w_out may equal w (then ld_out == ld_w).
+ *   r: DEVICE fp32, the factor left by prune_hessian_factor in the upper triangle of [cols, cols], pitch ld_r.
+ *   dead: DEVICE uint8 [cols], nullable: columns whose weights count as zero (from prune_hessian_factor).
+ *   first_block, n_blocks: the range of 128-column blocks to process in this call (n_blocks < 0: all the rest).
+ *     A projection may be swept in several calls, in order, starting at block 0, as long as v (or, when v is
+ *     NULL, the workspace) is left untouched in between.
+ *   v: DEVICE fp32 [rows, cols] contiguous, nullable: the working matrix.  For every column j not yet processed it
+ *     holds (current w[:, j]) * R[j, j] (so its square is the saliency); given by callers that want to look at it.
+ *   mask_bits: nullable, uint32 [rows, ceil(cols / 32)] keep-bits as written by prune_select_mask (only the words
+ *     of the processed blocks are written).
+ * cols and ld_r must be multiples of 4; r 16-byte, ws 256-byte aligned.  fp32 arithmetic throughout.
+ * ws_bytes >= prune_obs_sweep_workspace_bytes(rows, cols, v == NULL).
+ */
+size_t prune_obs_sweep_workspace_bytes(int64_t rows, int64_t cols, int own_v);
+int prune_obs_sweep(const void *w, void *w_out, int dtype, int64_t rows, int64_t cols, int64_t ld_w, int64_t ld_out,
+                    const float *r, int64_t ld_r, const uint8_t *dead, double sparsity, int64_t first_block,
+                    int64_t n_blocks, float *v, uint32_t *mask_bits, void *ws, size_t ws_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -1,0 +1,386 @@
+// The compensated left-to-right sweep of the Hessian-based one-shot pruner (Section 4.1.3, "Pruning Methods":
+// the lowest-ranking parameters are pruned "using the inverse Hessian matrix and a subsequent weight update"),
+// with the sparsity target that the Projection Planner gives the projection (Section 3.3).
+//
+// The published algorithm is written with U, the upper Cholesky factor of H^-1: in column j the error
+// e = (w_j - w'_j) / U_jj is spread to the right with row j of U.  Here it runs on R = U^-1 (H = R R^T, from
+// prune_hessian_factor), which needs no n x n inverse.  Summing the updates, W - W' = E U, hence E = (W - W') R:
+// with D = W - W' (the change of every finished column) and g_j = sum_{i<j} D_i R_ij, the current value of
+// column j is w_j + g_j / R_jj and U_jj = 1 / R_jj.  So the working matrix is
+//     V_j = w_j R_jj + g_j      (= current weight / U_jj: its square is the saliency),
+// a kept entry becomes w' = V_j / R_jj, a pruned one 0, and finishing column j adds D_j R_j,j' to every later V_j'.
+// Per block of 128 columns: (1) the floor(s * rows * width) smallest V^2 of the block are found exactly by a
+// radix search over all rows together (ties by row-major position); (2) one wave per row walks the 128
+// columns in order, the block of R in LDS; (3) one fp32 matrix-core product adds D_block R[block, later] to V.
+#include "gemm_f32.hpp"
+
+namespace mp {
+
+namespace {
+
+constexpr int kSB = 128;  // columns per block
+constexpr int kSBPitch = kSB + 1;
+constexpr int kHistBins = 2048;
+
+struct SweepState {
+    uint32_t prefix, need, key, need_eq, count_eq, pad0, pad1, pad2;
+};
+
+__device__ __forceinline__ uint32_t saliency_key(float v) { return __float_as_uint(__fmul_rn(v, v)) & 0x7fffffffu; }
+
+__device__ __forceinline__ bf16_t narrow_bf16(float f) {  // round to nearest, ties to even
+    const uint32_t b = __float_as_uint(f);
+    if ((b & 0x7fffffffu) > 0x7f800000u) return static_cast<bf16_t>(0x7fc0u);
+    return static_cast<bf16_t>((b + 0x7fffu + ((b >> 16) & 1u)) >> 16);
+}
+__device__ __forceinline__ void store_as(bf16_t *p, float f) { *p = narrow_bf16(f); }
+__device__ __forceinline__ void store_as(float *p, float f) { *p = f; }
+
+// V = W * diag(R), zero in dead columns
+template <typename T>
+__global__ __launch_bounds__(256) void sweep_init(const T *__restrict__ w, int64_t ld_w, const float *__restrict__ r,
+                                                  int64_t ld_r, const uint8_t *__restrict__ dead, int64_t rows,
+                                                  int64_t cols, float *__restrict__ v) {
+    const int64_t n = rows * cols;
+    for (int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; e < n;
+         e += static_cast<int64_t>(gridDim.x) * 256) {
+        const int64_t i = e / cols, j = e - i * cols;
+        const bool off = dead && dead[j];
+        v[e] = off ? 0.f : __fmul_rn(widen(w[i * ld_w + j]), r[j * ld_r + j]);
+    }
+}
+
+__global__ __launch_bounds__(1024) void select_begin(SweepState *state, uint32_t *hist, uint32_t k) {
+    for (int b = threadIdx.x; b < kHistBins; b += 1024) hist[b] = 0u;
+    if (threadIdx.x == 0) {
+        state->prefix = 0u;
+        state->need = k;
+        state->key = 0u;
+        state->need_eq = 0u;
+        state->count_eq = 0u;
+    }
+}
+
+// digits of the 31-bit key: bits 30..20, 19..10, 9..0
+template <int PASS>
+__global__ __launch_bounds__(256) void select_hist(const float *__restrict__ v, int64_t ldv, int64_t c0, int width,
+                                                   int64_t rows, const SweepState *__restrict__ state,
+                                                   uint32_t *__restrict__ hist) {
+    constexpr int kBins = PASS == 0 ? 2048 : 1024;
+    __shared__ uint32_t h[kBins];
+    const int tid = threadIdx.x;
+    for (int b = tid; b < kBins; b += 256) h[b] = 0u;
+    const uint32_t prefix = state->prefix;
+    __syncthreads();
+    const int64_t r0 = static_cast<int64_t>(blockIdx.x) * 16;
+    for (int e = tid; e < 16 * kSB; e += 256) {
+        const int64_t row = r0 + (e >> 7);
+        const int col = e & (kSB - 1);
+        if (row < rows && col < width) {
+            const uint32_t key = saliency_key(v[row * ldv + c0 + col]);
+            if (PASS == 0)
+                atomicAdd(&h[key >> 20], 1u);
+            else if (PASS == 1) {
+                if ((key >> 20) == prefix) atomicAdd(&h[(key >> 10) & 1023u], 1u);
+            } else {
+                if ((key >> 10) == prefix) atomicAdd(&h[key & 1023u], 1u);
+            }
+        }
+    }
+    __syncthreads();
+    for (int b = tid; b < kBins; b += 256)
+        if (h[b]) atomicAdd(&hist[b], h[b]);
+}
+
+// One block: find the bin of the `need`-th smallest key, extend the prefix, clear the histogram.
+template <int PASS>
+__global__ __launch_bounds__(1024) void select_locate(SweepState *state, uint32_t *hist) {
+    constexpr int kBins = PASS == 0 ? 2048 : 1024;
+    constexpr int kPer = kBins / 1024;
+    constexpr int kBits = PASS == 0 ? 11 : 10;
+    __shared__ uint32_t wave_tot[16];
+    __shared__ uint32_t found[3];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const uint32_t need = state->need, prefix = state->prefix;
+    uint32_t mine[kPer], s = 0;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        mine[i] = hist[tid * kPer + i];
+        s += mine[i];
+    }
+    const uint32_t incl = wave_inclusive_scan(s);
+    if (lane == 63) wave_tot[wv] = incl;
+    __syncthreads();
+    uint32_t excl = incl - s;
+    for (int i = 0; i < wv; ++i) excl += wave_tot[i];
+    if (excl < need && need <= excl + s) {
+        uint32_t run = excl;
+#pragma unroll
+        for (int i = 0; i < kPer; ++i) {
+            if (run < need && need <= run + mine[i]) {
+                found[0] = static_cast<uint32_t>(tid * kPer + i);
+                found[1] = run;
+                found[2] = mine[i];
+            }
+            run += mine[i];
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) hist[tid * kPer + i] = 0u;
+    __syncthreads();
+    if (tid == 0) {
+        const uint32_t np = (prefix << kBits) | found[0], nn = need - found[1];
+        state->prefix = np;
+        state->need = nn;
+        if (PASS == 2) {
+            state->key = np;
+            state->need_eq = nn;
+            state->count_eq = found[2];
+        }
+    }
+}
+
+// number of entries of each row of the block that carry the threshold key (only needed when not all of them go)
+__global__ __launch_bounds__(256) void tie_count(const float *__restrict__ v, int64_t ldv, int64_t c0, int width,
+                                                 int64_t rows, const SweepState *__restrict__ state,
+                                                 uint32_t *__restrict__ row_eq) {
+    if (state->need_eq == state->count_eq) return;
+    const int lane = threadIdx.x & 63;
+    const uint32_t skey = state->key;
+    for (int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6); row < rows;
+         row += static_cast<int64_t>(gridDim.x) * 4) {
+        uint32_t n = 0;
+        for (int col = lane; col < width; col += 64) n += saliency_key(v[row * ldv + c0 + col]) == skey ? 1u : 0u;
+        n = wave_sum(n);
+        if (lane == 0) row_eq[row] = n;
+    }
+}
+
+// row_before[i] = sum of row_eq over rows before i (one block)
+__global__ __launch_bounds__(1024) void tie_scan(const uint32_t *__restrict__ row_eq, uint32_t *__restrict__ row_before,
+                                                 int64_t rows, const SweepState *__restrict__ state) {
+    if (state->need_eq == state->count_eq) return;
+    __shared__ uint32_t wave_tot[16];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int64_t per = (rows + 1023) / 1024, lo = tid * per < rows ? tid * per : rows, hi = lo + per < rows ? lo + per : rows;
+    uint32_t s = 0;
+    for (int64_t i = lo; i < hi; ++i) s += row_eq[i];
+    const uint32_t incl = wave_inclusive_scan(s);
+    if (lane == 63) wave_tot[wv] = incl;
+    __syncthreads();
+    uint32_t run = incl - s;
+    for (int i = 0; i < wv; ++i) run += wave_tot[i];
+    for (int64_t i = lo; i < hi; ++i) {
+        row_before[i] = run;
+        run += row_eq[i];
+    }
+}
+
+__device__ __forceinline__ float lane_value(float x, int lane) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), lane));
+}
+
+// One wave per row walks the columns of the block in order.  mode: 0 nothing is pruned, 1 by the searched
+// threshold, 2 everything.  Lane l owns columns l and l + 64 of the block.
+template <typename T>
+__global__ __launch_bounds__(256) void sweep_block(const T *w, int64_t ld_w, T *w_out, int64_t ld_out,
+                                                   const float *__restrict__ r, int64_t ld_r,
+                                                   const uint8_t *__restrict__ dead, float *__restrict__ v, int64_t ldv,
+                                                   int64_t rows, int64_t c0, int width, int mode,
+                                                   const SweepState *__restrict__ state,
+                                                   const uint32_t *__restrict__ row_before, float *__restrict__ dblk,
+                                                   uint32_t *__restrict__ mask_bits, int64_t words_per_row,
+                                                   int64_t cols) {
+    __shared__ float rb[kSB][kSBPitch];
+    const int tid = threadIdx.x, lane = tid & 63;
+    for (int e = tid; e < kSB * kSB; e += 256) {
+        const int i = e >> 7, k = e & (kSB - 1);
+        rb[i][k] = (i <= k && k < width) ? r[(c0 + i) * ld_r + c0 + k] : 0.f;
+    }
+    __syncthreads();
+    uint32_t skey = 0u, need_eq = 0u;
+    bool all_eq = true;
+    if (mode == 1) {
+        skey = state->key;
+        need_eq = state->need_eq;
+        all_eq = need_eq == state->count_eq;
+    }
+    const bool valid0 = lane < width, valid1 = lane + 64 < width;
+    const bool dead0 = valid0 && dead && dead[c0 + lane], dead1 = valid1 && dead && dead[c0 + lane + 64];
+    const int n0 = width < 64 ? width : 64;
+    for (int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (tid >> 6); row < rows;
+         row += static_cast<int64_t>(gridDim.x) * 4) {
+        float v0 = valid0 ? v[row * ldv + c0 + lane] : 0.f;
+        float v1 = valid1 ? v[row * ldv + c0 + lane + 64] : 0.f;
+        const float w0 = (valid0 && !dead0) ? widen(w[row * ld_w + c0 + lane]) : 0.f;
+        const float w1 = (valid1 && !dead1) ? widen(w[row * ld_w + c0 + lane + 64]) : 0.f;
+        bool p0 = mode == 2 && valid0, p1 = mode == 2 && valid1;
+        if (mode == 1) {
+            const uint32_t k0 = valid0 ? saliency_key(v0) : 0xffffffffu, k1 = valid1 ? saliency_key(v1) : 0xffffffffu;
+            const bool e0 = k0 == skey, e1 = k1 == skey;
+            if (all_eq) {
+                p0 = k0 <= skey;
+                p1 = k1 <= skey;
+            } else {  // of the entries with the threshold key, the first need_eq in row-major order go
+                const unsigned long long b0 = __ballot(e0), b1 = __ballot(e1);
+                const unsigned long long below = (1ull << lane) - 1ull;
+                const uint32_t before = row_before[row];
+                const uint32_t rank0 = before + __popcll(b0 & below);
+                const uint32_t rank1 = before + __popcll(b0) + __popcll(b1 & below);
+                p0 = k0 < skey || (e0 && rank0 < need_eq);
+                p1 = k1 < skey || (e1 && rank1 < need_eq);
+            }
+        }
+        float o0 = 0.f, o1 = 0.f, d0 = 0.f, d1 = 0.f;
+        for (int j = 0; j < n0; ++j) {  // columns 0..63 of the block
+            const float vj = lane_value(v0, j), wj = lane_value(w0, j);
+            const bool pj = __builtin_amdgcn_readlane(p0 ? 1 : 0, j) != 0;
+            const float wnew = pj ? 0.f : vj / rb[j][j];
+            const float dj = wj - wnew;
+            if (lane == j) {
+                o0 = wnew;
+                d0 = dj;
+            }
+            if (lane > j) v0 = fmaf(dj, rb[j][lane], v0);
+            v1 = fmaf(dj, rb[j][lane + 64], v1);
+        }
+        for (int j = 64; j < width; ++j) {  // columns 64..127
+            const float vj = lane_value(v1, j - 64), wj = lane_value(w1, j - 64);
+            const bool pj = __builtin_amdgcn_readlane(p1 ? 1 : 0, j - 64) != 0;
+            const float wnew = pj ? 0.f : vj / rb[j][j];
+            const float dj = wj - wnew;
+            if (lane + 64 == j) {
+                o1 = wnew;
+                d1 = dj;
+            }
+            if (lane + 64 > j) v1 = fmaf(dj, rb[j][lane + 64], v1);
+        }
+        if (valid0) store_as(w_out + row * ld_out + c0 + lane, o0);
+        if (valid1) store_as(w_out + row * ld_out + c0 + lane + 64, o1);
+        dblk[row * kSB + lane] = d0;
+        dblk[row * kSB + lane + 64] = d1;
+        if (mask_bits) {  // keep-bits of the block's four words (bit set = kept); bits past the last column stay 0
+            const unsigned long long keep0 = __ballot(valid0 && !p0), keep1 = __ballot(valid1 && !p1);
+            if (lane < 4) {
+                const int64_t word = c0 / 32 + lane;
+                if (word * 32 < cols) {
+                    const unsigned long long src = lane < 2 ? keep0 : keep1;
+                    mask_bits[row * words_per_row + word] = static_cast<uint32_t>(src >> (32 * (lane & 1)));
+                }
+            }
+        }
+    }
+}
+
+struct SweepLayout {
+    size_t v, d, hist, state, row_eq, row_before, total;
+};
+
+SweepLayout sweep_layout(int64_t rows, int64_t cols, bool own_v) {
+    auto up = [](size_t n) { return (n + 255) / 256 * 256; };
+    SweepLayout l;
+    size_t at = 0;
+    l.v = at;
+    at += own_v ? up(static_cast<size_t>(rows) * cols * 4) : 0;
+    l.d = at;
+    at += up(static_cast<size_t>(rows) * kSB * 4);
+    l.hist = at;
+    at += up(kHistBins * 4);
+    l.state = at;
+    at += up(sizeof(SweepState));
+    l.row_eq = at;
+    at += up(static_cast<size_t>(rows) * 4);
+    l.row_before = at;
+    at += up(static_cast<size_t>(rows) * 4);
+    l.total = at;
+    return l;
+}
+
+template <typename T>
+int sweep_run(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld_w, int64_t ld_out, const float *r,
+              int64_t ld_r, const uint8_t *dead, double sparsity, int64_t first_block, int64_t n_blocks, float *v,
+              uint32_t *mask_bits, char *ws, const SweepLayout &l, hipStream_t stream) {
+    float *dblk = reinterpret_cast<float *>(ws + l.d);
+    uint32_t *hist = reinterpret_cast<uint32_t *>(ws + l.hist);
+    SweepState *state = reinterpret_cast<SweepState *>(ws + l.state);
+    uint32_t *row_eq = reinterpret_cast<uint32_t *>(ws + l.row_eq);
+    uint32_t *row_before = reinterpret_cast<uint32_t *>(ws + l.row_before);
+    const int64_t words = ceil_div(cols, 32);
+    if (first_block == 0) {
+        hipLaunchKernelGGL(sweep_init<T>, dim3(2048), dim3(256), 0, stream, w, ld_w, r, ld_r, dead, rows, cols, v);
+        if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
+    }
+    const unsigned row_tiles = static_cast<unsigned>(ceil_div(rows, 16));
+    const unsigned row_quads = static_cast<unsigned>(ceil_div(rows, 4) < 512 ? ceil_div(rows, 4) : 512);
+    for (int64_t b = first_block; b < first_block + n_blocks; ++b) {
+        const int64_t c0 = b * kSB;
+        const int width = static_cast<int>(cols - c0 < kSB ? cols - c0 : kSB);
+        const double quota = floor(sparsity * static_cast<double>(rows) * static_cast<double>(width));
+        const int64_t n_el = rows * width;
+        const int64_t k = quota < 0 ? 0 : static_cast<int64_t>(quota);
+        const int mode = k <= 0 ? 0 : k >= n_el ? 2 : 1;
+        if (mode == 1) {
+            hipLaunchKernelGGL(select_begin, dim3(1), dim3(1024), 0, stream, state, hist, static_cast<uint32_t>(k));
+            hipLaunchKernelGGL(select_hist<0>, dim3(row_tiles), dim3(256), 0, stream, v, cols, c0, width, rows, state, hist);
+            hipLaunchKernelGGL(select_locate<0>, dim3(1), dim3(1024), 0, stream, state, hist);
+            hipLaunchKernelGGL(select_hist<1>, dim3(row_tiles), dim3(256), 0, stream, v, cols, c0, width, rows, state, hist);
+            hipLaunchKernelGGL(select_locate<1>, dim3(1), dim3(1024), 0, stream, state, hist);
+            hipLaunchKernelGGL(select_hist<2>, dim3(row_tiles), dim3(256), 0, stream, v, cols, c0, width, rows, state, hist);
+            hipLaunchKernelGGL(select_locate<2>, dim3(1), dim3(1024), 0, stream, state, hist);
+            hipLaunchKernelGGL(tie_count, dim3(row_quads), dim3(256), 0, stream, v, cols, c0, width, rows, state, row_eq);
+            hipLaunchKernelGGL(tie_scan, dim3(1), dim3(1024), 0, stream, row_eq, row_before, rows, state);
+            if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
+        }
+        hipLaunchKernelGGL(sweep_block<T>, dim3(row_quads), dim3(256), 0, stream, w, ld_w, w_out, ld_out, r, ld_r, dead,
+                           v, cols, rows, c0, width, mode, state, row_before, dblk, mask_bits, words, cols);
+        if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
+        const int64_t c1 = c0 + width;
+        if (c1 < cols) {
+            const int st = launch_gemm_f32<kBKN>(static_cast<int>(rows), static_cast<int>(cols - c1), width, 1.f, dblk,
+                                                 kSB, r + c0 * ld_r + c1, ld_r, 1.f, v + c1, cols, false, stream);
+            if (st != PRUNE_OK) return st;
+        }
+    }
+    return PRUNE_OK;
+}
+
+}  // namespace
+
+}  // namespace mp
+
+extern "C" size_t prune_obs_sweep_workspace_bytes(int64_t rows, int64_t cols, int own_v) {
+    if (rows <= 0 || cols <= 0) return 0;
+    return mp::sweep_layout(rows, cols, own_v != 0).total;
+}
+
+extern "C" int prune_obs_sweep(const void *w, void *w_out, int dtype, int64_t rows, int64_t cols, int64_t ld_w,
+                               int64_t ld_out, const float *r, int64_t ld_r, const uint8_t *dead, double sparsity,
+                               int64_t first_block, int64_t n_blocks, float *v, uint32_t *mask_bits, void *ws,
+                               size_t ws_bytes, void *stream_) {
+    using namespace mp;
+    if (!valid_dtype(dtype)) return PRUNE_ERR_DTYPE;
+    if (rows <= 0 || cols <= 0 || ld_w < cols || ld_out < cols || ld_r < cols || rows > (int64_t(1) << 22) ||
+        cols > (int64_t(1) << 20) || rows * kSB >= (int64_t(1) << 32))
+        return PRUNE_ERR_SHAPE;
+    if (cols % 4 != 0 || ld_r % 4 != 0) return PRUNE_ERR_SHAPE;
+    if (w_out == w && ld_out != ld_w) return PRUNE_ERR_SHAPE;
+    if (!w || !w_out || !r || !ws) return PRUNE_ERR_NULL;
+    if (!(sparsity >= 0.0 && sparsity < 1.0)) return PRUNE_ERR_RANGE;
+    const int64_t total_blocks = ceil_div(cols, kSB);
+    if (n_blocks < 0) n_blocks = total_blocks - first_block;
+    if (first_block < 0 || n_blocks < 0 || first_block + n_blocks > total_blocks) return PRUNE_ERR_RANGE;
+    const size_t es = elem_size(dtype);
+    if (!aligned_to(w, es) || !aligned_to(w_out, es) || !aligned_to(r, 16) || !aligned_to(ws, 256) ||
+        (v && !aligned_to(v, 16)) || (mask_bits && !aligned_to(mask_bits, 4)))
+        return PRUNE_ERR_ALIGNMENT;
+    const SweepLayout l = sweep_layout(rows, cols, v == nullptr);
+    if (ws_bytes < l.total) return PRUNE_ERR_WORKSPACE;
+    char *base = static_cast<char *>(ws);
+    float *vv = v ? v : reinterpret_cast<float *>(base + l.v);
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (dtype == PRUNE_BF16)
+        return sweep_run(static_cast<const bf16_t *>(w), static_cast<bf16_t *>(w_out), rows, cols, ld_w, ld_out, r, ld_r,
+                         dead, sparsity, first_block, n_blocks, vv, mask_bits, base, l, stream);
+    return sweep_run(static_cast<const float *>(w), static_cast<float *>(w_out), rows, cols, ld_w, ld_out, r, ld_r, dead,
+                     sparsity, first_block, n_blocks, vv, mask_bits, base, l, stream);
+}

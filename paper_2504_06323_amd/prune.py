@@ -45,6 +45,9 @@ _SIGNATURES = {
     "prune_hessian_accumulate": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _i64, _vp, _sz, _vp]),
     "prune_hessian_factor_workspace_bytes": (_sz, [_i64]),
     "prune_hessian_factor": (_int, [_vp, _i64, _i64, _f64, _vp, _vp, _vp, _sz, _vp]),
+    "prune_obs_sweep_workspace_bytes": (_sz, [_i64, _i64, _int]),
+    "prune_obs_sweep": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _i64, _vp, _i64, _vp, _f64, _i64, _i64, _vp, _vp, _vp,
+                               _sz, _vp]),
     "prune_plan_sparsity_device": (_int, [_vp, _vp, _vp, _int, _int, _f64, _f64, _int, _vp, _vp, _vp, _vp]),
     "prune_struct_groups_workspace_bytes": (_sz, [_vp, _vp, _int, _vp, _vp, _int, _i64]),
     "prune_struct_groups": (_int, [_vp, _vp, _vp, _int, _vp, _vp, _vp, _int, _int, _i64, _u32, _vp, _vp, _vp, _vp,
@@ -383,6 +386,36 @@ def hessian_factor(h: torch.Tensor, damp: float = 0.01, dead: Optional[torch.Ten
     _check("prune_hessian_factor",
            load().prune_hessian_factor(h.data_ptr(), n, h.stride(0), float(damp), _vector(dead, "dead", torch.uint8, n),
                                        _vector(info, "info", torch.int32, 1), ws_ptr, ws_bytes, _stream(stream)))
+
+
+def obs_sweep(w: torch.Tensor, r: torch.Tensor, sparsity: float, w_out: Optional[torch.Tensor] = None,
+              dead: Optional[torch.Tensor] = None, first_block: int = 0, n_blocks: int = -1,
+              v: Optional[torch.Tensor] = None, mask_bits: Optional[torch.Tensor] = None,
+              ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Compensated pruning sweep of one projection (prune_obs_sweep).  In place when w_out is None.
+    Returns the workspace, which a caller sweeping in several calls hands back in."""
+    ptr, rows, cols, ld = _matrix(w, "w")
+    if w_out is None:
+        out_ptr, ld_out = ptr, ld
+    else:
+        out_ptr, orows, ocols, ld_out = _matrix(w_out, "w_out")
+        if (orows, ocols) != (rows, cols) or w_out.dtype != w.dtype:
+            raise ValueError("w_out must match w in shape and dtype")
+    if not (r.is_cuda and r.dtype == torch.float32 and r.dim() == 2 and tuple(r.shape) == (cols, cols) and r.stride(1) == 1):
+        raise ValueError("r must be a float32 GPU matrix [cols, cols] with unit column stride")
+    if mask_bits is not None and mask_bits.dtype not in (torch.int32, torch.uint32):
+        raise ValueError("mask_bits must be a 32-bit integer tensor")
+    need = int(load().prune_obs_sweep_workspace_bytes(rows, cols, 1 if v is None else 0))
+    if ws is None:
+        ws = torch.empty(max(need, 256), dtype=torch.uint8, device=w.device)
+    _check("prune_obs_sweep",
+           load().prune_obs_sweep(ptr, out_ptr, _dtype_code(w), rows, cols, ld, ld_out, r.data_ptr(), r.stride(0),
+                                  _vector(dead, "dead", torch.uint8, cols), float(sparsity), int(first_block),
+                                  int(n_blocks), _vector(v, "v", torch.float32, rows * cols),
+                                  None if mask_bits is None else _vector(mask_bits, "mask_bits", mask_bits.dtype,
+                                                                         rows * ((cols + 31) // 32)),
+                                  ws.data_ptr(), ws.numel(), _stream(stream)))
+    return ws
 
 
 def struct_compact(gate: torch.Tensor, up: torch.Tensor, down: torch.Tensor, r: int, group_mag: torch.Tensor,

@@ -163,3 +163,83 @@ def test_factor_reports_a_bad_pivot(lib):
     prune.hessian_factor(h, 0.01, info=info)
     _sync()
     assert info.item() == 41
+
+
+# ----------------------------------------------------------------- compensated sweep
+
+def _sweep_case(rows, cols, tokens, dtype, sparsity, seed, zero_frac=0.0, dead_cols=()):
+    """Run the sweep one 128-column block at a time, looking at the working matrix before every block.
+
+    The selection is an integer decision taken on fp32 saliencies, so the oracle takes it on the very saliencies
+    the kernel saw (the square, in fp32, of the working matrix at the start of the block); everything else of the
+    oracle runs in float64 on the factor the kernel was given."""
+    x = _acts(tokens, cols, torch.bfloat16, seed=seed)
+    for c in dead_cols:
+        x[:, c] = 0
+    w = synth.random_matrix(rows, cols, dtype, seed=seed + 1, device=DEV, scale=0.05, zero_frac=zero_frac)
+    h = torch.zeros((cols, cols), dtype=torch.float32, device=DEV)
+    prune.hessian_accumulate(x, h)
+    dead = torch.zeros(cols, dtype=torch.uint8, device=DEV)
+    info = torch.zeros(1, dtype=torch.int32, device=DEV)
+    prune.hessian_factor(h, 0.01, dead=dead, info=info)
+    _sync()
+    assert info.item() == 0 and sorted(np.nonzero(to_np(dead))[0].tolist()) == sorted(dead_cols)
+    r64 = np.triu(to_np(h).astype(np.float64))
+    v = torch.full((rows, cols), float("nan"), dtype=torch.float32, device=DEV)
+    w_out = torch.full_like(w, 7.0)
+    bits = torch.full((rows, (cols + 31) // 32), -1, dtype=torch.int32, device=DEV)
+    n_blocks = (cols + 127) // 128
+    w0 = to_np(w).astype(np.float64)
+    w0[:, to_np(dead).astype(bool)] = 0.0
+    seen = []                                           # fp32 saliencies the kernel's selection saw, per block
+    ws = None
+    for b in range(n_blocks):
+        c0, c1 = 128 * b, min(128 * b + 128, cols)
+        if b == 0:                                      # the working matrix starts as w * diag(R), one fp32 product
+            vb = w0[:, c0:c1].astype(np.float32) * np.diag(r64)[c0:c1].astype(np.float32)[None, :]
+        else:
+            vb = to_np(v[:, c0:c1])
+        seen.append(vb.astype(np.float32) * vb.astype(np.float32))
+        ws = prune.obs_sweep(w, h, sparsity, w_out=w_out, dead=dead, first_block=b, n_blocks=1, v=v, mask_bits=bits,
+                             ws=ws)
+        _sync()
+    calls = iter(seen)
+    want_w, want_pruned = obs.obs_sweep(w0, np.linalg.inv(r64), sparsity, block=128,
+                                        saliency_fn=lambda wb, ud: next(calls))
+    got_w = to_np(w_out).astype(np.float64)
+    assert np.array_equal(to_np(bits).view(np.uint32), orc.pack_keep_bits(want_pruned))      # the same entries go
+    assert (got_w[want_pruned] == 0).all()
+    quota = sum(obs.block_quota(sparsity, rows, min(128, cols - c)) for c in range(0, cols, 128))
+    assert want_pruned.sum() == quota
+    scale = np.max(np.abs(w0))
+    err = np.max(np.abs(got_w - want_w)) / scale
+    # fp32 sweep against float64 on the same masks; bf16 storage adds half an ulp (2^-9) of the largest weights
+    assert err < (6e-3 if dtype == torch.bfloat16 else 2e-4), err
+    # one call for all blocks, in place, gives the same bits as the block-by-block run
+    w2 = w.clone()
+    prune.obs_sweep(w2, h, sparsity, dead=dead)
+    _sync()
+    assert np.array_equal(to_np(w2).view(np.uint16 if dtype == torch.bfloat16 else np.uint32),
+                          to_np(w_out).view(np.uint16 if dtype == torch.bfloat16 else np.uint32))
+    return w0, got_w, want_w, r64
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("rows,cols,tokens,sparsity", [(64, 256, 1024, 0.5), (37, 200, 800, 0.3), (130, 388, 2000, 0.7),
+                                                       (16, 128, 512, 0.0), (5, 8, 64, 0.5)])
+def test_sweep_vs_oracle(lib, dtype, rows, cols, tokens, sparsity):
+    _sweep_case(rows, cols, tokens, dtype, sparsity, seed=rows + cols)
+
+
+def test_sweep_ties_dead_channels_and_compensation(lib):
+    """Many exact zeros (equal saliencies, split by position), channels that never fire, and the point of it all:
+    the compensated weights reproduce the layer output better than the same mask without compensation."""
+    w0, got_w, _, _ = _sweep_case(48, 384, 1500, torch.float32, 0.5, seed=77, zero_frac=0.6, dead_cols=(9, 200))
+    assert (got_w[:, [9, 200]] == 0).all()
+    first = slice(0, 128)                                                  # in the first block the quota falls inside the zeros:
+    assert (got_w[:, first][w0[:, first] != 0] != 0).all()                 # equal saliencies are split and no weight is lost
+    w0, got_w, want_w, r64 = _sweep_case(48, 384, 1500, torch.float32, 0.5, seed=78, zero_frac=0.2, dead_cols=(17,))
+    h = r64 @ r64.T
+    plain = np.where(got_w == 0, 0.0, w0)
+    assert obs.reconstruction_error(w0, got_w, h) < 0.97 * obs.reconstruction_error(w0, plain, h)   # (nearly independent channels: a few percent)
+    assert obs.reconstruction_error(w0, got_w, h) <= 1.001 * obs.reconstruction_error(w0, want_w, h)

@@ -143,6 +143,26 @@ def test_error_paths_return_before_any_launch(lib):
     assert hf(ctypes.c_void_p(0x1004), 8, 8, 0.01, None, None, fake, 1 << 20, None) == E["align"]
     assert hf(fake, 8, 8, 0.01, None, None, fake, 16, None) == E["ws"]
     assert lib.prune_hessian_factor_workspace_bytes(4096) >= 128 * 128 * 4
+    sw = lib.prune_obs_sweep
+    big = ctypes.c_void_p(0x10000)
+    ok = lambda **kw: sw(*[{**dict(w=big, o=big, dt=1, rows=8, cols=8, ldw=8, ldo=8, r=big, ldr=8, dead=None, s=0.5, fb=0,
+                                  nb=-1, v=None, mb=None, ws=big, wsb=1 << 30, st=None), **kw}[k]
+                           for k in ("w", "o", "dt", "rows", "cols", "ldw", "ldo", "r", "ldr", "dead", "s", "fb", "nb", "v",
+                                     "mb", "ws", "wsb", "st")])
+    assert ok(dt=5) == E["dtype"]
+    assert ok(rows=0) == E["shape"]
+    assert ok(cols=6, ldw=6, ldo=6) == E["shape"]                                  # cols must be a multiple of 4
+    assert ok(ldr=4) == E["shape"]
+    assert ok(r=None) == E["null"]
+    assert ok(ws=None) == E["null"]
+    assert ok(s=1.0) == E["rng"]
+    assert ok(fb=2) == E["rng"]                                                    # only one block of columns
+    assert ok(fb=1) == 0                                                           # an empty range of blocks: nothing to do
+    assert ok(nb=2) == E["rng"]
+    assert ok(r=ctypes.c_void_p(0x10004)) == E["align"]
+    assert ok(wsb=64) == E["ws"]
+    assert lib.prune_obs_sweep_workspace_bytes(4096, 4096, 1) >= 4096 * 4096 * 4 + 4096 * 128 * 4
+    assert lib.prune_obs_sweep_workspace_bytes(4096, 4096, 0) < 4096 * 4096 * 4
     st = lib.prune_struct_compact
     assert st(fake, fake, fake, 1, 8, 8, 8, fake, fake, None, None, None, fake, 1 << 20, None) == E["rng"]  # r >= inter
     assert st(fake, fake, fake, 1, 8, 8, 1, fake, fake, fake, None, None, fake, 1 << 20, None) == E["null"]  # 1 of 3 outs
