@@ -162,11 +162,95 @@ def run_hessian_stage(args):
     print(json.dumps(out), flush=True)
 
 
+def run_obs_stage(args):
+    """--stage obs: the whole Hessian-based path on the workload's layer, with the planner's targets.
+
+    A step is: activation statistics, metric sums and outlier counts, planner (host), then one Hessian and one
+    factor per distinct projection input and one compensated sweep per projection.  Prints its own JSON line."""
+    import torch
+    from paper_2504_06323_amd import pipeline, prune, synth
+
+    prune.load()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.workload]
+    shapes = synth.projection_shapes(cfg)
+    act_shapes = synth.activation_shapes(cfg)
+    weights = {n: synth.make_weight(cfg, 0, n, dev) for n, _, _, _ in shapes}
+    acts = {a: synth.make_activation(cfg, 0, a, dev) for a in act_shapes}
+    st = pipeline.LayerState.create(weights, {n: a for n, _, _, a in shapes}, act_shapes, cfg.n_tokens)
+    ob = pipeline.ObsState.create(st, act_shapes, cfg.n_tokens)
+    numels = [rw * c for _, rw, c, _ in shapes]
+    cols = [c for _, _, c, _ in shapes]
+    big = max(act_shapes, key=lambda a: act_shapes[a])
+    flops_big = acts[big].shape[0] * acts[big].shape[1] * (acts[big].shape[1] + 1)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    marks_all, gram_events = [], []
+
+    def step(record):
+        m = [ev() for _ in range(4)] if record else None
+        if record:
+            m[0].record()
+        pipeline.rank_layer(st, acts, cfg.alpha)
+        s, _, _ = pipeline.plan(st.count.tolist(), numels, cols, 1, len(shapes), cfg.p, cfg.lam)
+        if record:
+            m[1].record()
+        for i, (a, x) in enumerate(acts.items()):
+            ob.hessian[a].zero_()
+            if record and a == big:
+                e0, e1 = ev(), ev()
+                e0.record()
+            prune.hessian_accumulate(x, ob.hessian[a], ws=ob.ws)
+            if record and a == big:
+                e1.record()
+                gram_events.append((e0, e1))
+            prune.hessian_factor(ob.hessian[a], 0.01, dead=ob.dead[a], info=ob.info[i:i + 1], ws=ob.ws)
+        if record:
+            m[2].record()
+        pipeline.obs_prune_layer(st, ob, s)
+        if record:
+            m[3].record()
+            marks_all.append(m)
+        return s
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        s = step(True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    if ob.info.tolist() != [0] * len(acts):
+        raise RuntimeError(f"a Hessian factorisation met a pivot that was not positive: {ob.info.tolist()}")
+    ms = 1e3 * elapsed / args.steps
+    seg = [sum(m[i].elapsed_time(m[i + 1]) for m in marks_all) / len(marks_all) for i in range(3)]
+    launch_ms = sum(a.elapsed_time(b) for a, b in gram_events) / len(gram_events)
+    achieved = flops_big / (launch_ms * 1e-3) / 1e12
+    numel = synth.layer_numel(cfg)
+    zeros = sum(int((st.pruned[n] == 0).sum().item()) for n in st.names)
+    out = {"metric": "projection weights pruned/s through the Hessian-based pruner with per-projection targets, 1 GPU",
+           "value": numel / (ms * 1e-3), "unit": "weights/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"{cfg.name}: one layer, {numel} weights in bf16, {cfg.n_tokens} calibration tokens, "
+                                  f"target sparsity {cfg.p}, planner targets {[round(v, 4) for v in s]}, "
+                                  f"achieved sparsity {zeros / numel:.4f}"},
+           "ms_rank_and_plan": round(seg[0], 3), "ms_hessians_and_factors": round(seg[1], 3), "ms_sweeps": round(seg[2], 3),
+           "roofline": {"bound": "mfma", "kernel": f"gram_tiles_bf16 + gram_reduce on [{acts[big].shape[0]}, {acts[big].shape[1]}]",
+                        "achieved": round(achieved, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                        "frac": round(achieved / 2500.0, 4), "traffic": None, "avg_launch_ms": round(launch_ms, 4),
+                        "launches": len(gram_events)}}
+    log(f"obs stage: {ms:.2f} ms per layer | rank+plan {seg[0]:.2f} | hessians+factors {seg[1]:.2f} | sweeps {seg[2]:.2f}")
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--stage", default="prune", choices=["prune", "hessian"],
+    ap.add_argument("--stage", default="prune", choices=["prune", "hessian", "obs"],
                     help="prune (default): the scoring / masking / structured path the headline metric is quoted on; "
-                         "hessian: the matrix-core stage of the Hessian-based pruner, its own JSON line")
+                         "hessian: the matrix-core stage of the Hessian-based pruner, its own JSON line; "
+                         "obs: the whole Hessian-based path of one layer, its own JSON line")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
@@ -186,6 +270,9 @@ def main():
 
     if args.stage == "hessian":
         run_hessian_stage(args)
+        return
+    if args.stage == "obs":
+        run_obs_stage(args)
         return
 
     import torch

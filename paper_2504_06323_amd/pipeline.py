@@ -149,3 +149,47 @@ def struct_layer(st: LayerState, r: int, out: StructResult, masked: bool = True)
     src = st.pruned if masked else st.weights
     prune.struct_compact(src["gate"], src["up"], src["down"], r, out.group_mag, out.kept_idx,
                          out.gate, out.up, out.down, ws=st.ws)
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# The Hessian-based pruner the paper's experiments run with the planner's targets (Section 4.1.3, "Pruning
+# Methods"): one Hessian and one factor per distinct projection input, one compensated sweep per projection.
+
+@dataclass
+class ObsState:
+    """Device buffers of the Hessian-based path of one layer (on top of a LayerState)."""
+
+    hessian: Dict[str, torch.Tensor]        # per activation: [C, C] float32; after factor_layer its upper triangle is R
+    dead: Dict[str, torch.Tensor]           # per activation: [C] uint8
+    info: torch.Tensor                      # [n_activations] int32, 0 = factorisation went through
+    ws: torch.Tensor
+
+    @classmethod
+    def create(cls, st: LayerState, act_channels: Dict[str, int], act_tokens: int) -> "ObsState":
+        dev = st.device
+        need = 256
+        for a, ch in act_channels.items():
+            need = max(need, prune.hessian_workspace_bytes(act_tokens, ch),
+                       int(prune.load().prune_hessian_factor_workspace_bytes(ch)))
+        for name, w in st.weights.items():
+            need = max(need, int(prune.load().prune_obs_sweep_workspace_bytes(w.shape[0], w.shape[1], 1)))
+        return cls(hessian={a: torch.zeros((ch, ch), dtype=torch.float32, device=dev) for a, ch in act_channels.items()},
+                   dead={a: torch.zeros(ch, dtype=torch.uint8, device=dev) for a, ch in act_channels.items()},
+                   info=torch.zeros(len(act_channels), dtype=torch.int32, device=dev),
+                   ws=torch.empty(need, dtype=torch.uint8, device=dev))
+
+
+def hessian_layer(ob: ObsState, acts: Dict[str, torch.Tensor], damp: float = 0.01) -> None:
+    """H = X^T X for every distinct projection input, then damping and factorisation in place."""
+    for i, (a, x) in enumerate(acts.items()):
+        ob.hessian[a].zero_()
+        prune.hessian_accumulate(x, ob.hessian[a], ws=ob.ws)
+        prune.hessian_factor(ob.hessian[a], damp, dead=ob.dead[a], info=ob.info[i:i + 1], ws=ob.ws)
+
+
+def obs_prune_layer(st: LayerState, ob: ObsState, sparsities: Sequence[float], in_place: bool = False) -> None:
+    """Compensated sweep of every projection with its own sparsity target (the planner's p_{n,m})."""
+    for name, s in zip(st.names, sparsities):
+        a = st.proj_inputs[name]
+        prune.obs_sweep(st.weights[name], ob.hessian[a], float(s), w_out=None if in_place else st.pruned[name],
+                        dead=ob.dead[a], mask_bits=st.mask_bits.get(name), ws=ob.ws)

@@ -243,3 +243,79 @@ def test_sweep_ties_dead_channels_and_compensation(lib):
     plain = np.where(got_w == 0, 0.0, w0)
     assert obs.reconstruction_error(w0, got_w, h) < 0.97 * obs.reconstruction_error(w0, plain, h)   # (nearly independent channels: a few percent)
     assert obs.reconstruction_error(w0, got_w, h) <= 1.001 * obs.reconstruction_error(w0, want_w, h)
+
+
+def _popcount32(a):
+    a = a.astype(np.uint32)
+    a = a - ((a >> 1) & 0x55555555)
+    a = (a & 0x33333333) + ((a >> 2) & 0x33333333)
+    a = (a + (a >> 4)) & 0x0F0F0F0F
+    return (a * 0x01010101 >> 24) & 0xFF
+
+
+def test_obs_fullsize_q_projection(lib):
+    """The q projection of the LLaMA-7B-shaped layer (4096 x 4096, 262144 calibration tokens) through all three
+    stages, in the shapes the benchmark times.  Sampled entries of R R^T against the damped Hessian; for sampled
+    column blocks the selection against the oracle's on the kernel's fp32 saliencies and the new weights against a
+    float64 replay of the block; the per-block quota over every block; and the reconstruction error of the whole
+    projection against plain masking with the same mask."""
+    cfg = synth.CONFIGS["llama7b_layer"]
+    x = synth.make_activation(cfg, 0, "attn_in", DEV)
+    w = synth.make_weight(cfg, 0, "q", DEV)
+    rows, cols = w.shape
+    h = torch.zeros((cols, cols), dtype=torch.float32, device=DEV)
+    prune.hessian_accumulate(x, h)
+    del x
+    h_plain = to_np(h).astype(np.float64)
+    dead = torch.zeros(cols, dtype=torch.uint8, device=DEV)
+    info = torch.zeros(1, dtype=torch.int32, device=DEV)
+    prune.hessian_factor(h, 0.01, dead=dead, info=info)
+    _sync()
+    assert info.item() == 0 and not to_np(dead).any()
+    h_damped, _ = obs.damped_hessian(h_plain, 0.01)
+    r64 = np.triu(to_np(h).astype(np.float64))
+    rng = np.random.default_rng(5)
+    ii, jj = rng.integers(0, cols, 400), rng.integers(0, cols, 400)
+    rrt = np.einsum("nk,nk->n", r64[ii], r64[jj])
+    scale = np.sqrt(np.diag(h_damped)[ii] * np.diag(h_damped)[jj])
+    assert np.max(np.abs(rrt - h_damped[ii, jj]) / scale) < 1e-5
+    sparsity = 0.53
+    v = torch.zeros((rows, cols), dtype=torch.float32, device=DEV)
+    w_out = torch.empty_like(w)
+    bits = torch.zeros((rows, cols // 32), dtype=torch.int32, device=DEV)
+    w0 = to_np(w).astype(np.float64)
+    rdiag = np.diag(r64)
+    ws, watch, snaps = None, (0, 1, 17, 31), {}
+    for b in range(cols // 128):
+        if b in watch and b > 0:
+            snaps[b] = to_np(v[:, 128 * b:128 * b + 128]).copy()
+        ws = prune.obs_sweep(w, h, sparsity, w_out=w_out, first_block=b, n_blocks=1, v=v, mask_bits=bits, ws=ws)
+    _sync()
+    snaps[0] = w0[:, :128].astype(np.float32) * rdiag[:128].astype(np.float32)[None, :]
+    got = to_np(w_out).astype(np.float64)
+    keep = to_np(bits).view(np.uint32)
+    quota = obs.block_quota(sparsity, rows, 128)
+    per_block = _popcount32(keep).reshape(rows, cols // 128, 4).sum(axis=(0, 2))
+    assert (per_block == rows * 128 - quota).all()                          # every block prunes exactly its quota
+    pruned_all = ~np.unpackbits(keep.view(np.uint8), axis=1, bitorder="little").astype(bool)
+    assert (got[pruned_all] == 0).all()
+    for b in watch:
+        c0 = 128 * b
+        vb = snaps[b].astype(np.float32)
+        want_mask = obs.select_block(vb * vb, quota)                        # the oracle's selection on the kernel's saliencies
+        assert np.array_equal(pruned_all[:, c0:c0 + 128], want_mask), b
+        # float64 replay of the block from its working matrix: kept w' = V_j / R_jj, D_j = w_j - w'_j spreads with R
+        cur = vb.astype(np.float64)
+        rb = r64[c0:c0 + 128, c0:c0 + 128]
+        want = np.zeros((rows, 128))
+        for j in range(128):
+            want[:, j] = np.where(want_mask[:, j], 0.0, cur[:, j] / rb[j, j])
+            d = w0[:, c0 + j] - want[:, j]
+            cur[:, j + 1:] += np.outer(d, rb[j, j + 1:])
+        err = np.max(np.abs(got[:, c0:c0 + 128] - want)) / np.max(np.abs(w0))
+        assert err < 6e-3, (b, err)                                         # half a bf16 ulp of the largest weights
+    delta = w0 - got
+    plain = np.where(pruned_all, w0, 0.0)                                    # what plain masking with this mask removes
+    e_obs = float(np.einsum("ij,ij->", delta @ h_damped, delta))
+    e_plain = float(np.einsum("ij,ij->", plain @ h_damped, plain))
+    assert e_obs < e_plain
