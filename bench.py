@@ -195,16 +195,7 @@ def run_obs_stage(args):
         s, _, _ = pipeline.plan(st.count.tolist(), numels, cols, 1, len(shapes), cfg.p, cfg.lam)
         if record:
             m[1].record()
-        for i, (a, x) in enumerate(acts.items()):
-            ob.hessian[a].zero_()
-            if record and a == big:
-                e0, e1 = ev(), ev()
-                e0.record()
-            prune.hessian_accumulate(x, ob.hessian[a], ws=ob.ws)
-            if record and a == big:
-                e1.record()
-                gram_events.append((e0, e1))
-            prune.hessian_factor(ob.hessian[a], 0.01, dead=ob.dead[a], info=ob.info[i:i + 1], ws=ob.ws)
+        pipeline.hessian_layer(ob, acts, on_big=(lambda e: gram_events.append(e)) if record else None, big=big)
         if record:
             m[2].record()
         pipeline.obs_prune_layer(st, ob, s)

@@ -180,8 +180,11 @@ __device__ __forceinline__ float lane_value(float x, int lane) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), lane));
 }
 
-// One wave per row walks the columns of the block in order.  mode: 0 nothing is pruned, 1 by the searched
+// A wave walks the columns of the block in order for kRowsPerWave rows at once (the rows are independent chains
+// of dependent operations, so they hide each other's latency).  mode: 0 nothing is pruned, 1 by the searched
 // threshold, 2 everything.  Lane l owns columns l and l + 64 of the block.
+constexpr int kRowsPerWave = 4;
+
 template <typename T>
 __global__ __launch_bounds__(256) void sweep_block(const T *w, int64_t ld_w, T *w_out, int64_t ld_out,
                                                    const float *__restrict__ r, int64_t ld_r,
@@ -191,12 +194,15 @@ __global__ __launch_bounds__(256) void sweep_block(const T *w, int64_t ld_w, T *
                                                    const uint32_t *__restrict__ row_before, float *__restrict__ dblk,
                                                    uint32_t *__restrict__ mask_bits, int64_t words_per_row,
                                                    int64_t cols) {
+    constexpr int NR = kRowsPerWave;
     __shared__ float rb[kSB][kSBPitch];
+    __shared__ float rinv[kSB];
     const int tid = threadIdx.x, lane = tid & 63;
     for (int e = tid; e < kSB * kSB; e += 256) {
         const int i = e >> 7, k = e & (kSB - 1);
         rb[i][k] = (i <= k && k < width) ? r[(c0 + i) * ld_r + c0 + k] : 0.f;
     }
+    if (tid < kSB) rinv[tid] = tid < width ? 1.f / r[(c0 + tid) * ld_r + c0 + tid] : 0.f;
     __syncthreads();
     uint32_t skey = 0u, need_eq = 0u;
     bool all_eq = true;
@@ -208,63 +214,82 @@ __global__ __launch_bounds__(256) void sweep_block(const T *w, int64_t ld_w, T *
     const bool valid0 = lane < width, valid1 = lane + 64 < width;
     const bool dead0 = valid0 && dead && dead[c0 + lane], dead1 = valid1 && dead && dead[c0 + lane + 64];
     const int n0 = width < 64 ? width : 64;
-    for (int64_t row = static_cast<int64_t>(blockIdx.x) * 4 + (tid >> 6); row < rows;
-         row += static_cast<int64_t>(gridDim.x) * 4) {
-        float v0 = valid0 ? v[row * ldv + c0 + lane] : 0.f;
-        float v1 = valid1 ? v[row * ldv + c0 + lane + 64] : 0.f;
-        const float w0 = (valid0 && !dead0) ? widen(w[row * ld_w + c0 + lane]) : 0.f;
-        const float w1 = (valid1 && !dead1) ? widen(w[row * ld_w + c0 + lane + 64]) : 0.f;
-        bool p0 = mode == 2 && valid0, p1 = mode == 2 && valid1;
-        if (mode == 1) {
-            const uint32_t k0 = valid0 ? saliency_key(v0) : 0xffffffffu, k1 = valid1 ? saliency_key(v1) : 0xffffffffu;
-            const bool e0 = k0 == skey, e1 = k1 == skey;
-            if (all_eq) {
-                p0 = k0 <= skey;
-                p1 = k1 <= skey;
-            } else {  // of the entries with the threshold key, the first need_eq in row-major order go
-                const unsigned long long b0 = __ballot(e0), b1 = __ballot(e1);
-                const unsigned long long below = (1ull << lane) - 1ull;
-                const uint32_t before = row_before[row];
-                const uint32_t rank0 = before + __popcll(b0 & below);
-                const uint32_t rank1 = before + __popcll(b0) + __popcll(b1 & below);
-                p0 = k0 < skey || (e0 && rank0 < need_eq);
-                p1 = k1 < skey || (e1 && rank1 < need_eq);
+    const unsigned long long live0 = __ballot(valid0), live1 = __ballot(valid1);
+    for (int64_t base = (static_cast<int64_t>(blockIdx.x) * 4 + (tid >> 6)) * NR; base < rows;
+         base += static_cast<int64_t>(gridDim.x) * 4 * NR) {
+        float v0[NR], v1[NR], w0[NR], w1[NR], o0[NR], o1[NR], d0[NR], d1[NR];
+        unsigned long long pm0[NR], pm1[NR];  // which columns of the row are pruned (uniform over the wave)
+#pragma unroll
+        for (int q = 0; q < NR; ++q) {
+            const int64_t row = base + q;
+            const bool live = row < rows;
+            v0[q] = (live && valid0) ? v[row * ldv + c0 + lane] : 0.f;
+            v1[q] = (live && valid1) ? v[row * ldv + c0 + lane + 64] : 0.f;
+            w0[q] = (live && valid0 && !dead0) ? widen(w[row * ld_w + c0 + lane]) : 0.f;
+            w1[q] = (live && valid1 && !dead1) ? widen(w[row * ld_w + c0 + lane + 64]) : 0.f;
+            bool p0 = mode == 2 && valid0, p1 = mode == 2 && valid1;
+            if (mode == 1) {
+                const uint32_t k0 = valid0 ? saliency_key(v0[q]) : 0xffffffffu;
+                const uint32_t k1 = valid1 ? saliency_key(v1[q]) : 0xffffffffu;
+                const bool e0 = k0 == skey, e1 = k1 == skey;
+                if (all_eq) {
+                    p0 = k0 <= skey;
+                    p1 = k1 <= skey;
+                } else {  // of the entries with the threshold key, the first need_eq in row-major order go
+                    const unsigned long long b0 = __ballot(e0), b1 = __ballot(e1);
+                    const unsigned long long below = (1ull << lane) - 1ull;
+                    const uint32_t before = live ? row_before[row] : 0u;
+                    const uint32_t rank0 = before + __popcll(b0 & below);
+                    const uint32_t rank1 = before + __popcll(b0) + __popcll(b1 & below);
+                    p0 = k0 < skey || (e0 && rank0 < need_eq);
+                    p1 = k1 < skey || (e1 && rank1 < need_eq);
+                }
             }
+            pm0[q] = __ballot(p0);
+            pm1[q] = __ballot(p1);
+            o0[q] = o1[q] = d0[q] = d1[q] = 0.f;
         }
-        float o0 = 0.f, o1 = 0.f, d0 = 0.f, d1 = 0.f;
         for (int j = 0; j < n0; ++j) {  // columns 0..63 of the block
-            const float vj = lane_value(v0, j), wj = lane_value(w0, j);
-            const bool pj = __builtin_amdgcn_readlane(p0 ? 1 : 0, j) != 0;
-            const float wnew = pj ? 0.f : vj / rb[j][j];
-            const float dj = wj - wnew;
-            if (lane == j) {
-                o0 = wnew;
-                d0 = dj;
+            const float ri = rinv[j], rl0 = lane > j ? rb[j][lane] : 0.f, rl1 = rb[j][lane + 64];
+#pragma unroll
+            for (int q = 0; q < NR; ++q) {
+                const float vj = lane_value(v0[q], j), wj = lane_value(w0[q], j);
+                const float wnew = ((pm0[q] >> j) & 1ull) ? 0.f : __fmul_rn(vj, ri);
+                const float dj = wj - wnew;
+                if (lane == j) {
+                    o0[q] = wnew;
+                    d0[q] = dj;
+                }
+                v0[q] = fmaf(dj, rl0, v0[q]);
+                v1[q] = fmaf(dj, rl1, v1[q]);
             }
-            if (lane > j) v0 = fmaf(dj, rb[j][lane], v0);
-            v1 = fmaf(dj, rb[j][lane + 64], v1);
         }
         for (int j = 64; j < width; ++j) {  // columns 64..127
-            const float vj = lane_value(v1, j - 64), wj = lane_value(w1, j - 64);
-            const bool pj = __builtin_amdgcn_readlane(p1 ? 1 : 0, j - 64) != 0;
-            const float wnew = pj ? 0.f : vj / rb[j][j];
-            const float dj = wj - wnew;
-            if (lane + 64 == j) {
-                o1 = wnew;
-                d1 = dj;
+            const float ri = rinv[j], rl1 = lane + 64 > j ? rb[j][lane + 64] : 0.f;
+#pragma unroll
+            for (int q = 0; q < NR; ++q) {
+                const float vj = lane_value(v1[q], j - 64), wj = lane_value(w1[q], j - 64);
+                const float wnew = ((pm1[q] >> (j - 64)) & 1ull) ? 0.f : __fmul_rn(vj, ri);
+                const float dj = wj - wnew;
+                if (lane + 64 == j) {
+                    o1[q] = wnew;
+                    d1[q] = dj;
+                }
+                v1[q] = fmaf(dj, rl1, v1[q]);
             }
-            if (lane + 64 > j) v1 = fmaf(dj, rb[j][lane + 64], v1);
         }
-        if (valid0) store_as(w_out + row * ld_out + c0 + lane, o0);
-        if (valid1) store_as(w_out + row * ld_out + c0 + lane + 64, o1);
-        dblk[row * kSB + lane] = d0;
-        dblk[row * kSB + lane + 64] = d1;
-        if (mask_bits) {  // keep-bits of the block's four words (bit set = kept); bits past the last column stay 0
-            const unsigned long long keep0 = __ballot(valid0 && !p0), keep1 = __ballot(valid1 && !p1);
-            if (lane < 4) {
+#pragma unroll
+        for (int q = 0; q < NR; ++q) {
+            const int64_t row = base + q;
+            if (row >= rows) break;  // uniform
+            if (valid0) store_as(w_out + row * ld_out + c0 + lane, o0[q]);
+            if (valid1) store_as(w_out + row * ld_out + c0 + lane + 64, o1[q]);
+            dblk[row * kSB + lane] = d0[q];
+            dblk[row * kSB + lane + 64] = d1[q];
+            if (mask_bits && lane < 4) {  // keep-bits of the block's four words (bit set = kept); bits past cols stay 0
                 const int64_t word = c0 / 32 + lane;
                 if (word * 32 < cols) {
-                    const unsigned long long src = lane < 2 ? keep0 : keep1;
+                    const unsigned long long src = lane < 2 ? (live0 & ~pm0[q]) : (live1 & ~pm1[q]);
                     mask_bits[row * words_per_row + word] = static_cast<uint32_t>(src >> (32 * (lane & 1)));
                 }
             }
@@ -312,6 +337,7 @@ int sweep_run(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld_w, in
     }
     const unsigned row_tiles = static_cast<unsigned>(ceil_div(rows, 16));
     const unsigned row_quads = static_cast<unsigned>(ceil_div(rows, 4) < 512 ? ceil_div(rows, 4) : 512);
+    const unsigned row_groups = static_cast<unsigned>(ceil_div(rows, 4 * kRowsPerWave) < 1024 ? ceil_div(rows, 4 * kRowsPerWave) : 1024);
     for (int64_t b = first_block; b < first_block + n_blocks; ++b) {
         const int64_t c0 = b * kSB;
         const int width = static_cast<int>(cols - c0 < kSB ? cols - c0 : kSB);
@@ -331,7 +357,7 @@ int sweep_run(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld_w, in
             hipLaunchKernelGGL(tie_scan, dim3(1), dim3(1024), 0, stream, row_eq, row_before, rows, state);
             if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
         }
-        hipLaunchKernelGGL(sweep_block<T>, dim3(row_quads), dim3(256), 0, stream, w, ld_w, w_out, ld_out, r, ld_r, dead,
+        hipLaunchKernelGGL(sweep_block<T>, dim3(row_groups), dim3(256), 0, stream, w, ld_w, w_out, ld_out, r, ld_r, dead,
                            v, cols, rows, c0, width, mode, state, row_before, dblk, mask_bits, words, cols);
         if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
         const int64_t c1 = c0 + width;

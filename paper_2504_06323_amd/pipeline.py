@@ -157,15 +157,21 @@ def struct_layer(st: LayerState, r: int, out: StructResult, masked: bool = True)
 
 @dataclass
 class ObsState:
-    """Device buffers of the Hessian-based path of one layer (on top of a LayerState)."""
+    """Device buffers of the Hessian-based path of one layer (on top of a LayerState).
 
-    hessian: Dict[str, torch.Tensor]        # per activation: [C, C] float32; after factor_layer its upper triangle is R
+    The factorisations of the different projection inputs, and the sweeps of the different projections, are
+    independent and each has phases that occupy a single compute unit or are bound by launch latency, so they are
+    spread over a few HIP streams (default priority), each with its own workspace."""
+
+    hessian: Dict[str, torch.Tensor]        # per activation: [C, C] float32; after hessian_layer its upper triangle is R
     dead: Dict[str, torch.Tensor]           # per activation: [C] uint8
     info: torch.Tensor                      # [n_activations] int32, 0 = factorisation went through
-    ws: torch.Tensor
+    ws: List[torch.Tensor]                  # one workspace per stream
+    streams: List["torch.cuda.Stream"]
+    factored: Dict[str, "torch.cuda.Event"] = field(default_factory=dict)
 
     @classmethod
-    def create(cls, st: LayerState, act_channels: Dict[str, int], act_tokens: int) -> "ObsState":
+    def create(cls, st: LayerState, act_channels: Dict[str, int], act_tokens: int, n_streams: int = 4) -> "ObsState":
         dev = st.device
         need = 256
         for a, ch in act_channels.items():
@@ -176,20 +182,60 @@ class ObsState:
         return cls(hessian={a: torch.zeros((ch, ch), dtype=torch.float32, device=dev) for a, ch in act_channels.items()},
                    dead={a: torch.zeros(ch, dtype=torch.uint8, device=dev) for a, ch in act_channels.items()},
                    info=torch.zeros(len(act_channels), dtype=torch.int32, device=dev),
-                   ws=torch.empty(need, dtype=torch.uint8, device=dev))
+                   ws=[torch.empty(need, dtype=torch.uint8, device=dev) for _ in range(n_streams)],
+                   streams=[torch.cuda.Stream(device=dev) for _ in range(n_streams)])
 
 
-def hessian_layer(ob: ObsState, acts: Dict[str, torch.Tensor], damp: float = 0.01) -> None:
-    """H = X^T X for every distinct projection input, then damping and factorisation in place."""
+def hessian_layer(ob: ObsState, acts: Dict[str, torch.Tensor], damp: float = 0.01, on_big=None, big: str = "") -> None:
+    """H = X^T X for every distinct projection input (one after the other: each fills the chip), each followed by
+    damping and factorisation in place on a stream of its own."""
+    main = torch.cuda.current_stream()
     for i, (a, x) in enumerate(acts.items()):
+        side = ob.streams[i % len(ob.streams)]
         ob.hessian[a].zero_()
-        prune.hessian_accumulate(x, ob.hessian[a], ws=ob.ws)
-        prune.hessian_factor(ob.hessian[a], damp, dead=ob.dead[a], info=ob.info[i:i + 1], ws=ob.ws)
+        timed = on_big is not None and a == big        # a benchmark's event pair around one accumulation
+        if timed:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(main)
+        prune.hessian_accumulate(x, ob.hessian[a], ws=ob.ws[0])
+        if timed:
+            e1.record(main)
+            on_big((e0, e1))
+        ready = torch.cuda.Event()
+        ready.record(main)
+        side.wait_event(ready)
+        prune.hessian_factor(ob.hessian[a], damp, dead=ob.dead[a], info=ob.info[i:i + 1],
+                             ws=ob.ws[i % len(ob.streams)] if i % len(ob.streams) else _factor_ws(ob), stream=side)
+        done = torch.cuda.Event()
+        done.record(side)
+        ob.factored[a] = done
+
+
+def _factor_ws(ob: ObsState) -> torch.Tensor:
+    """Stream 0's factorisations must not share scratch with the Hessian kernel that runs next on the main stream."""
+    if not hasattr(ob, "_factor_scratch"):
+        ob._factor_scratch = torch.empty(int(prune.load().prune_hessian_factor_workspace_bytes(128)) + 256,
+                                         dtype=torch.uint8, device=ob.info.device)
+    return ob._factor_scratch
 
 
 def obs_prune_layer(st: LayerState, ob: ObsState, sparsities: Sequence[float], in_place: bool = False) -> None:
-    """Compensated sweep of every projection with its own sparsity target (the planner's p_{n,m})."""
-    for name, s in zip(st.names, sparsities):
-        a = st.proj_inputs[name]
-        prune.obs_sweep(st.weights[name], ob.hessian[a], float(s), w_out=None if in_place else st.pruned[name],
-                        dead=ob.dead[a], mask_bits=st.mask_bits.get(name), ws=ob.ws)
+    """Compensated sweep of every projection with its own sparsity target (the planner's p_{n,m}), the
+    projections dealt round robin to the streams; the calling stream waits for all of them at the end."""
+    main = torch.cuda.current_stream()
+    start = torch.cuda.Event()
+    start.record(main)
+    order = sorted(range(len(st.names)), key=lambda i: -st.weights[st.names[i]].numel())   # longest sweeps first
+    for slot, i in enumerate(order):
+        name, a = st.names[i], st.proj_inputs[st.names[i]]
+        side = ob.streams[slot % len(ob.streams)]
+        side.wait_event(start)
+        if a in ob.factored:
+            side.wait_event(ob.factored[a])
+        prune.obs_sweep(st.weights[name], ob.hessian[a], float(sparsities[i]),
+                        w_out=None if in_place else st.pruned[name], dead=ob.dead[a], mask_bits=st.mask_bits.get(name),
+                        ws=ob.ws[slot % len(ob.streams)], stream=side)
+    for side in ob.streams:
+        done = torch.cuda.Event()
+        done.record(side)
+        main.wait_event(done)

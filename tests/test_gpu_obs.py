@@ -319,3 +319,34 @@ def test_obs_fullsize_q_projection(lib):
     e_obs = float(np.einsum("ij,ij->", delta @ h_damped, delta))
     e_plain = float(np.einsum("ij,ij->", plain @ h_damped, plain))
     assert e_obs < e_plain
+
+
+def test_pipeline_streams_give_the_same_bits(lib):
+    """The layer-level helpers spread factorisations and sweeps over several streams: the results must be those of
+    plain one-after-the-other calls on the current stream, bit for bit, also when a step is repeated."""
+    from paper_2504_06323_amd import pipeline
+    cfg = synth.CONFIGS["toy"]
+    shapes = synth.projection_shapes(cfg)
+    act_shapes = synth.activation_shapes(cfg)
+    weights = {n: synth.make_weight(cfg, 0, n, DEV) for n, _, _, _ in shapes}
+    acts = {a: synth.make_activation(cfg, 0, a, DEV) for a in act_shapes}
+    st = pipeline.LayerState.create(weights, {n: a for n, _, _, a in shapes}, act_shapes, cfg.n_tokens)
+    ob = pipeline.ObsState.create(st, act_shapes, cfg.n_tokens)
+    targets = [0.3 + 0.05 * i for i in range(len(shapes))]
+    for _ in range(2):
+        pipeline.hessian_layer(ob, acts)
+        pipeline.obs_prune_layer(st, ob, targets)
+    _sync()
+    assert ob.info.tolist() == [0] * len(acts)
+    for i, (n, rows, cols, a) in enumerate(shapes):
+        h = torch.zeros((cols, cols), dtype=torch.float32, device=DEV)
+        prune.hessian_accumulate(acts[a], h)
+        dead = torch.zeros(cols, dtype=torch.uint8, device=DEV)
+        prune.hessian_factor(h, 0.01, dead=dead)
+        out = torch.empty_like(weights[n])
+        bits = torch.zeros_like(st.mask_bits[n])
+        prune.obs_sweep(weights[n], h, targets[i], w_out=out, dead=dead, mask_bits=bits)
+        _sync()
+        assert torch.equal(out, st.pruned[n]) and torch.equal(bits, st.mask_bits[n]), n
+        quota = sum(obs.block_quota(targets[i], rows, min(128, cols - c)) for c in range(0, cols, 128))
+        assert int((~np.unpackbits(to_np(bits).view(np.uint8), axis=1, bitorder="little").astype(bool))[:, :cols].sum()) == quota
