@@ -167,6 +167,7 @@ class ObsState:
     dead: Dict[str, torch.Tensor]           # per activation: [C] uint8
     info: torch.Tensor                      # [n_activations] int32, 0 = factorisation went through
     ws: List[torch.Tensor]                  # one workspace per stream
+    factor_ws: torch.Tensor                 # scratch of the factorisations on stream 0 (ws[0] belongs to the Hessian kernel)
     streams: List["torch.cuda.Stream"]
     factored: Dict[str, "torch.cuda.Event"] = field(default_factory=dict)
 
@@ -183,6 +184,8 @@ class ObsState:
                    dead={a: torch.zeros(ch, dtype=torch.uint8, device=dev) for a, ch in act_channels.items()},
                    info=torch.zeros(len(act_channels), dtype=torch.int32, device=dev),
                    ws=[torch.empty(need, dtype=torch.uint8, device=dev) for _ in range(n_streams)],
+                   factor_ws=torch.empty(int(prune.load().prune_hessian_factor_workspace_bytes(128)),
+                                         dtype=torch.uint8, device=dev),
                    streams=[torch.cuda.Stream(device=dev) for _ in range(n_streams)])
 
 
@@ -205,18 +208,10 @@ def hessian_layer(ob: ObsState, acts: Dict[str, torch.Tensor], damp: float = 0.0
         ready.record(main)
         side.wait_event(ready)
         prune.hessian_factor(ob.hessian[a], damp, dead=ob.dead[a], info=ob.info[i:i + 1],
-                             ws=ob.ws[i % len(ob.streams)] if i % len(ob.streams) else _factor_ws(ob), stream=side)
+                             ws=ob.ws[i % len(ob.streams)] if i % len(ob.streams) else ob.factor_ws, stream=side)
         done = torch.cuda.Event()
         done.record(side)
         ob.factored[a] = done
-
-
-def _factor_ws(ob: ObsState) -> torch.Tensor:
-    """Stream 0's factorisations must not share scratch with the Hessian kernel that runs next on the main stream."""
-    if not hasattr(ob, "_factor_scratch"):
-        ob._factor_scratch = torch.empty(int(prune.load().prune_hessian_factor_workspace_bytes(128)) + 256,
-                                         dtype=torch.uint8, device=ob.info.device)
-    return ob._factor_scratch
 
 
 def obs_prune_layer(st: LayerState, ob: ObsState, sparsities: Sequence[float], in_place: bool = False) -> None:

@@ -87,6 +87,15 @@ def test_identity_hessian_is_magnitude_pruning_without_update():
     assert np.array_equal(got, np.where(pruned, 0.0, w))                        # kept weights are untouched
 
 
+def test_saliency_weighs_a_weight_by_its_channel_energy():
+    # Diagonal Hessian diag(100, 1): the saliency w^2 / [H^-1]_jj is w^2 * H_jj, so w = [0.5, 1.0] costs 25 and 1:
+    # the larger weight on the quiet channel goes, not the smaller weight on the loud one; nothing to compensate.
+    u = obs.inverse_factor(np.diag([100.0, 1.0]))
+    assert np.allclose(obs.block_saliency(np.array([[0.5, 1.0]]), np.diag(u)), [[25.0, 1.0]], rtol=1e-12)
+    got, pruned = obs.obs_sweep(np.array([[0.5, 1.0]]), u, 0.5, block=2)
+    assert pruned.tolist() == [[False, True]] and got.tolist() == [[0.5, 0.0]]
+
+
 def test_single_pruned_weight_is_the_closed_form_obs_update():
     _, h = _spd(7, 4)
     rng = np.random.default_rng(4)
@@ -135,6 +144,29 @@ def test_sweep_equals_explicit_trailing_inverse_elimination(block):
     for i in range(6):
         want = _eliminate_with_trailing_inverses(w[i], h, pruned[i])
         assert np.allclose(got[i], want, rtol=1e-8, atol=1e-10), i
+
+
+def test_later_blocks_select_on_compensated_weights():
+    """Selection of a block re-derived without the factor: current weights from the explicit elimination above,
+    saliency w^2 / [inverse of the trailing Hessian]_00.  With correlated channels the compensation of earlier
+    blocks changes which entries of later blocks go."""
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((60, 12)) @ (np.eye(12) + 0.6 * rng.standard_normal((12, 12)))
+    h = x.T @ x
+    w = rng.standard_normal((5, 12))
+    block, sparsity = 4, 0.5
+    got, pruned = obs.obs_sweep(w, obs.inverse_factor(h), sparsity, block=block)
+    mask = np.zeros_like(pruned)
+    differs_from_static = False
+    for c0 in range(0, 12, block):
+        cur = np.stack([_eliminate_with_trailing_inverses(w[i], h, mask[i]) for i in range(5)])
+        denom = np.array([np.linalg.inv(h[j:, j:])[0, 0] for j in range(c0, c0 + block)])
+        sal = cur[:, c0:c0 + block] ** 2 / denom[None, :]
+        mask[:, c0:c0 + block] = obs.select_block(sal, obs.block_quota(sparsity, 5, block))
+        static = obs.select_block(w[:, c0:c0 + block] ** 2 / denom[None, :], obs.block_quota(sparsity, 5, block))
+        differs_from_static |= not np.array_equal(static, mask[:, c0:c0 + block])
+    assert np.array_equal(pruned, mask)
+    assert differs_from_static                              # the example does exercise the difference
 
 
 def test_pruned_prefix_gives_the_least_squares_optimum():
