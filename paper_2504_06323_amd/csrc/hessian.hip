@@ -9,12 +9,13 @@
 // blocks per tile so that the grid fills the chip.  A block of four waves holds a
 // 256 x 256 fp32 accumulator tile in registers (128 x 128 per wave, sixteen
 // 32 x 32 x 16 MFMA accumulators) and walks its tokens 32 at a time: the two
-// [32 tokens x 256 channels] slabs of X go through LDS exactly as they lie in
-// memory (token-major), double buffered, and the MFMA operands -- which want eight
-// consecutive tokens of one channel per lane -- are formed by the LDS transpose
-// read.  Per-split partial tiles go to the workspace and are added up in a fixed
-// order (so the result is reproducible bit for bit), mirrored below the diagonal.
-// Any other element type, width or alignment takes a plain tiled FMA kernel.
+// [32 tokens x 256 channels] slabs of X are loaded from global memory directly
+// into a four-stage LDS ring, token-major as they lie in memory, and the MFMA
+// operands -- which want eight consecutive tokens of one channel per lane -- are
+// formed by the LDS transpose read.  Per-split partial tiles go to the workspace
+// and are added up in a fixed order (so the result is reproducible bit for bit),
+// mirrored below the diagonal.  Any other element type, width or alignment takes
+// a plain tiled FMA kernel.
 #include "common.hpp"
 
 namespace mp {
@@ -28,9 +29,6 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kTile = 256;        // output tile edge (channels)
 constexpr int kStep = 32;         // tokens per LDS stage
-constexpr int kSets = 3;          // register sets for loads in flight
-constexpr int kPitch = 288;       // bf16 elements per LDS row: 576 bytes, so that four consecutive rows start 64 bytes
-                                  // apart modulo 256 and the transpose reads of a half wave fall into distinct banks
 constexpr int kGramBlock = 256;
 constexpr int kMaxSplits = 64;
 
@@ -70,25 +68,45 @@ __device__ __forceinline__ bool item_of_block(int block, int n_items, int &item)
     return item < n_items;
 }
 
-// Eight consecutive tokens (k16 + 8 * (lane / 32) ...) of channel ch_base + lane % 32, as the MFMA wants them,
-// out of a token-major LDS slab.  The transpose read hands lane i of a 16-lane group, as element j, the
-// element i % 4 of the 64-bit row that lane 4 j + i / 4 of the group points at; so lane s' points at token
-// row s' / 4, channel quad s' % 4, and lane s receives channel s of four consecutive tokens.
-__device__ __forceinline__ bf16x8 operand_from_slab(const bf16_t *slab, int k16, int ch_base, int lane) {
+// The slabs of X go from global memory straight into LDS (no staging registers, no LDS stores): a wave's load
+// instruction drops 64 x 16 bytes at consecutive LDS addresses, so a slab row is 512
+// bytes without padding and bank conflicts of the transpose reads are avoided by a swizzle instead: in token row r
+// the 16-byte packet c sits at position c ^ (4 (r % 4)) -- which each lane implements simply by fetching the packet
+// that belongs at its fixed position.  Four 32 KB stages form a ring; the loads of stage s + 4 are issued in the
+// middle of stage s, right after the barrier behind which every wave has the operands of stage s in registers:
+// they reuse that stage's own buffer.  Loads that land in LDS are counted by vmcnt; the waits are explicit.
+constexpr int kRing = 4;
+constexpr int kSlabBytes = kStep * kTile * 2;
+
+__device__ __forceinline__ bf16x8 operand_from_ring(const unsigned char *slab, int k16, int group, int i, int lane) {
     const int s = lane & 15, g = lane >> 4;
-    const bf16_t *p = slab + (k16 + 8 * (g >> 1) + (s >> 2)) * kPitch + ch_base + 16 * (g & 1) + 4 * (s & 3);
+    const int row = k16 + 8 * (g >> 1) + (s >> 2);
+    const int packet = 16 * group + 4 * (i ^ (s >> 2)) + 2 * (g & 1) + ((s & 3) >> 1);
+    const unsigned char *p = slab + row * (kTile * 2) + packet * 16 + (s & 1) * 8;
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p);
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * kPitch));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(p + 4 * kTile * 2));
     const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     return __builtin_bit_cast(bf16x8, both);
 }
 
+// One global -> LDS load of 16 bytes per lane: lane l's packet lands at lds_addr + 16 l (lds_addr uniform, in M0).
+// Written as an instruction rather than through the builtin on purpose: the compiler would otherwise guard every
+// later LDS read with a wait for all such loads in flight (it cannot tell the ring's stages apart), which undoes
+// the prefetch; the waits are placed by hand below.
+__device__ __forceinline__ void load_to_lds(const void *src, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(src) : "memory");
+}
+
+// s_waitcnt with only the vector-memory counter set (6 bits: [3:0] and [15:14]); the others left at "no wait"
+#define MP_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt((((n) & 15) | (((n) >> 4) << 14)) | 0x0F70)
+
 __global__ __launch_bounds__(kGramBlock, 1) void gram_tiles_bf16(const bf16_t *__restrict__ x, int64_t n_tokens,
-                                                                 int channels, int64_t ld, int n_tiles, int n_pairs,
-                                                                 int n_splits, int64_t tokens_per_split,
-                                                                 float *__restrict__ partials) {
-    __shared__ __attribute__((aligned(16))) bf16_t slab[2][2][kStep * kPitch];  // [stage][operand]
+                                                                     int channels, int64_t ld, int n_tiles, int n_pairs,
+                                                                     int n_splits, int64_t tokens_per_split,
+                                                                     float *__restrict__ partials) {
+    __shared__ __attribute__((aligned(1024))) unsigned char ring[kRing][2][kSlabBytes];
+    typedef __attribute__((address_space(3))) unsigned char lds_byte;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
     int item;
     if (!item_of_block(blockIdx.x, n_pairs * n_splits, item)) return;  // the whole block, before any barrier
@@ -99,52 +117,55 @@ __global__ __launch_bounds__(kGramBlock, 1) void gram_tiles_bf16(const bf16_t *_
     const int64_t t_begin = split * tokens_per_split;
     int64_t t_end = t_begin + tokens_per_split;
     if (t_end > n_tokens) t_end = n_tokens;
+    const int64_t n_stages = (t_end - t_begin + kStep - 1) / kStep;
+    const int64_t n_whole = (t_end - t_begin) / kStep;
 
-    // staging: pass p moves token rows 8 p + tid / 32, channel packet tid % 32 of both slabs.  Three register
-    // sets: the loads of a stage are issued three stages ahead of its use (memory latency under this load is
-    // more than one stage of matrix-core work), and a set is free again once it has been parked in LDS.
-    // Loads are unconditional (a load behind a branch would make every later wait a wait for all loads in
-    // flight): a packet outside the matrix is fetched from a clamped, valid address instead.  Channels past
-    // the edge only feed outputs that are never stored; token rows past the end of the range are replaced by
-    // zeros when the stage is parked.
-    const int srow = tid >> 5, spkt = tid & 31;
-    const int cha = m0 + spkt * 8 < channels ? m0 + spkt * 8 : 0;
-    const int chb = n0 + spkt * 8 < channels ? n0 + spkt * 8 : 0;
-    constexpr int kPasses = kStep / 8;
-    u32x4 ra[kSets][kPasses], rb[kSets][kPasses];
-    // byte offsets of this thread's packets from the first token row of a stage; the stage base is uniform
-    const uint32_t offa = static_cast<uint32_t>((srow * ld + cha) * 2), offb = static_cast<uint32_t>((srow * ld + chb) * 2);
-    const uint32_t pass_bytes = static_cast<uint32_t>(8 * ld * 2);
+    // load instruction p of this wave fills LDS window 4 p + wave of a slab: token rows 2 (4 p + wave) + lane / 32,
+    // position lane % 32, i.e. packet (lane % 32) ^ (4 (row % 4)); channels past the edge are clamped to packet 0
+    // of the slab (they only feed outputs that are never stored)
+    int drow[4];
+    uint32_t offa[4], offb[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        drow[p] = 2 * (4 * p + wave) + (lane >> 5);
+        const int c = (lane & 31) ^ (4 * (drow[p] & 3));
+        const int cha = m0 + 8 * c < channels ? m0 + 8 * c : 0, chb = n0 + 8 * c < channels ? n0 + 8 * c : 0;
+        offa[p] = static_cast<uint32_t>((drow[p] * ld + cha) * 2);
+        offb[p] = static_cast<uint32_t>((drow[p] * ld + chb) * 2);
+    }
     const char *xb = reinterpret_cast<const char *>(x);
-    auto fetch_inside = [&](int set, int64_t stage_index) {  // every token row of the stage exists
-        const char *base = xb + (t_begin + stage_index * kStep) * ld * 2;
-#pragma unroll
-        for (int p = 0; p < kPasses; ++p) {
-            ra[set][p] = *reinterpret_cast<const u32x4 *>(base + (offa + p * pass_bytes));
-            rb[set][p] = *reinterpret_cast<const u32x4 *>(base + (offb + p * pass_bytes));
-        }
-    };
-    auto fetch_clamped = [&](int set, int64_t stage_index) {  // rows past the last token re-read the last one
-        const int64_t t0 = t_begin + stage_index * kStep + srow;
-#pragma unroll
-        for (int p = 0; p < kPasses; ++p) {
-            int64_t t = t0 + 8 * p;
+    auto issue_part = [&](int64_t stage_index, int p) {  // load instruction p (one for each slab) of a stage
+        // LDS byte address of this wave's first window in the stage's A slab (uniform over the wave)
+        const uint32_t dst = __builtin_amdgcn_readfirstlane(
+            static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_byte *)&ring[stage_index & (kRing - 1)][0][0])) +
+            static_cast<uint32_t>(wave) * 1024u);
+        const char *from;
+        if (stage_index < n_whole) {  // uniform: every token row of the stage exists
+            from = xb + (t_begin + stage_index * kStep) * ld * 2;
+        } else {  // rows past the last token re-read the last one (zeroed after landing, or never used)
+            int64_t t = t_begin + stage_index * kStep + drow[p];
             t = t < n_tokens ? t : n_tokens - 1;
-            ra[set][p] = *reinterpret_cast<const u32x4 *>(x + t * ld + cha);
-            rb[set][p] = *reinterpret_cast<const u32x4 *>(x + t * ld + chb);
+            from = xb + t * ld * 2 - static_cast<int64_t>(drow[p]) * ld * 2;
         }
+        load_to_lds(from + offa[p], dst + 4096u * p);
+        load_to_lds(from + offb[p], dst + kSlabBytes + 4096u * p);
     };
-    auto park = [&](int set, int buffer, int64_t stage_index, bool ragged) {
-        const int64_t t0 = t_begin + stage_index * kStep + srow;
+    auto issue = [&](int64_t stage_index) {
 #pragma unroll
-        for (int p = 0; p < kPasses; ++p) {
-            const int off = (srow + 8 * p) * kPitch + spkt * 8;
-            const u32x4 zero = {0u, 0u, 0u, 0u};
-            const bool in = !ragged || t0 + 8 * p < t_end;
-            *reinterpret_cast<u32x4 *>(&slab[buffer][0][off]) = in ? ra[set][p] : zero;
-            *reinterpret_cast<u32x4 *>(&slab[buffer][1][off]) = in ? rb[set][p] : zero;
-        }
+        for (int p = 0; p < 4; ++p) issue_part(stage_index, p);
     };
+    // token rows past the end of a ragged last stage must count as zeros
+    auto blank_tail = [&](int64_t stage_index) {
+        const int valid = static_cast<int>(t_end - t_begin - stage_index * kStep);  // < kStep
+        unsigned char *dst = &ring[stage_index & (kRing - 1)][0][0];
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        for (int e = tid; e < 2 * kStep * 32; e += kGramBlock) {
+            const int op = e / (kStep * 32), row = (e / 32) % kStep, pos = e % 32;
+            if (row >= valid) *reinterpret_cast<u32x4 *>(dst + op * kSlabBytes + row * 512 + pos * 16) = zero;
+        }
+        __syncthreads();
+    };
+
     f32x16 acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -152,77 +173,77 @@ __global__ __launch_bounds__(kGramBlock, 1) void gram_tiles_bf16(const bf16_t *_
         for (int j = 0; j < 4; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-    // MFMA operands: set 0 holds tokens 0..15 of the current stage, set 1 tokens 16..31.  Every LDS read is
-    // issued at least eight MFMAs (256 cycles) before its first use, and the issue order is pinned: a wave
-    // has its SIMD to itself, so whatever latency the schedule exposes is lost.
     bf16x8 a[2][4], b[2][4];
-    auto read_a = [&](int set, int buffer, int k16) {
+    auto read_a = [&](int set, int64_t stage_index, int k16) {
+        const unsigned char *slab = &ring[stage_index & (kRing - 1)][0][0];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) a[set][i] = operand_from_slab(slab[buffer][0], k16, wm * 128 + 32 * i, lane);
+        for (int i = 0; i < 4; ++i) a[set][i] = operand_from_ring(slab, k16, wm, i, lane);
     };
-    auto read_b = [&](int set, int buffer, int k16) {
+    auto read_b = [&](int set, int64_t stage_index, int k16) {
+        const unsigned char *slab = &ring[stage_index & (kRing - 1)][1][0];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) b[set][i] = operand_from_slab(slab[buffer][1], k16, wn * 128 + 32 * i, lane);
-    };
-    auto mfma_rows = [&](int set, int i0) {
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = i0; i < i0 + 2; ++i)
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[set][i], b[set][j], acc[i][j], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
+        for (int i = 0; i < 4; ++i) b[set][i] = operand_from_ring(slab, k16, wn, i, lane);
     };
 
-    // Stage s travels in register set s % 3 and is used from LDS buffer s % 2.  One trip of the body:
-    //   reads of the second half of stage s | 8 MFMAs | park stage s + 1, fetch stage s + 4, more reads | 8 MFMAs |
-    //   barrier | reads of the first half of stage s + 1 | 8 MFMAs | more reads | 8 MFMAs
-    const int64_t n_stages = (t_end - t_begin + kStep - 1) / kStep;
-    const int64_t n_whole = (t_end - t_begin) / kStep;  // stages without a ragged end
-    auto body = [&](int u, int64_t s, bool steady) {
-        const int cur = u % 2, nxt = (u + 1) % 2, set = (u + 1) % 3;
-        const bool has_next = steady || s + 1 < n_stages;
-        read_a(1, cur, 16);
-        mfma_rows(0, 0);
-        if (has_next) park(set, nxt, s + 1, !steady);
-        if (steady)
-            fetch_inside(set, s + 4);
-        else
-            fetch_clamped(set, s + 4);
-        read_b(1, cur, 16);
-        mfma_rows(0, 2);
-        __syncthreads();
-        if (has_next) read_a(0, nxt, 0);
-        mfma_rows(1, 0);
-        if (has_next) read_b(0, nxt, 0);
-        mfma_rows(1, 2);
-    };
-    fetch_clamped(0, 0);
-    fetch_clamped(1, 1);
-    fetch_clamped(2, 2);
-    park(0, 0, 0, true);
-    fetch_clamped(0, 3);
+    issue(0);
+    issue(1);
+    issue(2);
+    issue(3);
+    MP_WAIT_VMCNT(24);
     __syncthreads();
-    if (n_stages > 0) {
-        read_a(0, 0, 0);
-        read_b(0, 0, 0);
-    }
-    // Six stages per trip so that set and buffer indices are constants.  The steady state has no branches:
-    // with loads behind control flow the compiler can no longer tell how many newer loads may stay in flight
-    // at a park and waits for all of them.  It runs while stage s + 4 is still a whole one.
-    int64_t s0 = 0;
-    for (; s0 + 6 + 4 <= n_whole; s0 += 6) {
+    if (n_stages == 1 && n_whole == 0) blank_tail(0);
+    read_a(0, 0, 0);
+    read_b(0, 0, 0);
+    // A wave has its SIMD to itself, so every instruction that is not an MFMA should issue in the shadow of one
+    // (an MFMA keeps the pipe busy for 32 cycles, time for about eight other instructions).  The scheduler is told
+    // to alternate: one MFMA, then a couple of LDS reads of the operands needed later.
+    auto mfma_one = [&](int set, int i, int j) {
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[set][i], b[set][j], acc[i][j], 0, 0, 0);
+    };
+    for (int64_t s = 0; s < n_stages; ++s) {
+        // first 12 MFMAs of the stage's first 16 tokens, interleaved with the 16 reads of its last 16 tokens
+        __builtin_amdgcn_sched_barrier(0);
+        read_a(1, s, 16);
+        read_b(1, s, 16);
 #pragma unroll
-        for (int u = 0; u < 6; ++u) body(u, s0 + u, true);
-    }
-    for (; s0 < n_stages; s0 += 6) {  // the last trips
+        for (int i = 0; i < 3; ++i)
 #pragma unroll
-        for (int u = 0; u < 6; ++u)
-            if (s0 + u < n_stages) body(u, s0 + u, false);
+            for (int j = 0; j < 4; ++j) mfma_one(0, i, j);
+#pragma unroll
+        for (int g = 0; g < 12; ++g) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // one MFMA
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);  // two LDS reads (there are 16: the last groups stay empty)
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        MP_WAIT_VMCNT(16);  // this thread's loads of stage s + 1 have landed (stages s + 2, s + 3 may be in flight)
+        __syncthreads();    // ... and everyone's; and every wave has read all it needs of stage s from LDS:
+        // its buffer takes the stage four ahead; the eight load instructions go between the next four MFMAs
+        mfma_one(0, 3, 0);
+        issue_part(s + 4, 0);
+        mfma_one(0, 3, 1);
+        issue_part(s + 4, 1);
+        mfma_one(0, 3, 2);
+        issue_part(s + 4, 2);
+        mfma_one(0, 3, 3);
+        issue_part(s + 4, 3);
+        if (s + 1 == n_stages - 1 && n_whole < n_stages) blank_tail(s + 1);  // uniform
+        // the 16 MFMAs of the last 16 tokens, interleaved with the 16 reads of the next stage's first 16 tokens
+        __builtin_amdgcn_sched_barrier(0);
+        read_a(0, s + 1, 0);
+        read_b(0, s + 1, 0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) mfma_one(1, i, j);
+#pragma unroll
+        for (int g = 0; g < 16; ++g) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
     }
+    MP_WAIT_VMCNT(0);  // nothing may still be landing in this block's LDS when it ends
 
-    // accumulator element v of lane l sits at row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32 of its 32 x 32 tile
     float *out = partials + (static_cast<int64_t>(split) * n_pairs + pair) * (kTile * kTile);
 #pragma unroll
     for (int i = 0; i < 4; ++i)
