@@ -336,8 +336,11 @@ int prune_hessian_factor(float *h, int64_t n, int64_t ld_h, double damp, uint8_t
  *   first_block, n_blocks: the range of 128-column blocks to process in this call (n_blocks < 0: all the rest).
  *     A projection may be swept in several calls, in order, starting at block 0, as long as v (or, when v is
  *     NULL, the workspace) is left untouched in between.
- *   v: DEVICE fp32 [rows, cols] contiguous, nullable: the working matrix.  For every column j not yet processed it
- *     holds (current w[:, j]) * R[j, j] (so its square is the saliency); given by callers that want to look at it.
+ *   v: DEVICE fp32 [rows, cols] contiguous, nullable: the working matrix G.  For every column j not yet processed
+ *     it holds sum over the finished columns i of (w[:, i] - w_out[:, i]) * R[i, j]; zeroed by the call that
+ *     processes block 0.  Given by callers that sweep in several calls and want the state in a buffer of their own.
+ *   saliency: DEVICE fp32 [rows, cols] contiguous, nullable: receives, for the columns of every block processed,
+ *     the saliencies the selection of that block was taken on (fp32, as computed when the block started).
  *   mask_bits: nullable, uint32 [rows, ceil(cols / 32)] keep-bits as written by prune_select_mask (only the words
  *     of the processed blocks are written).
  * cols and ld_r must be multiples of 4; r 16-byte, ws 256-byte aligned.  fp32 arithmetic throughout.
@@ -346,7 +349,8 @@ int prune_hessian_factor(float *h, int64_t n, int64_t ld_h, double damp, uint8_t
 size_t prune_obs_sweep_workspace_bytes(int64_t rows, int64_t cols, int own_v);
 int prune_obs_sweep(const void *w, void *w_out, int dtype, int64_t rows, int64_t cols, int64_t ld_w, int64_t ld_out,
                     const float *r, int64_t ld_r, const uint8_t *dead, double sparsity, int64_t first_block,
-                    int64_t n_blocks, float *v, uint32_t *mask_bits, void *ws, size_t ws_bytes, void *stream);
+                    int64_t n_blocks, float *v, float *saliency, uint32_t *mask_bits, void *ws, size_t ws_bytes,
+                    void *stream);
 
 #ifdef __cplusplus
 }

@@ -5,14 +5,20 @@
 // The published algorithm is written with U, the upper Cholesky factor of H^-1: in column j the error
 // e = (w_j - w'_j) / U_jj is spread to the right with row j of U.  Here it runs on R = U^-1 (H = R R^T, from
 // prune_hessian_factor), which needs no n x n inverse.  Summing the updates, W - W' = E U, hence E = (W - W') R:
-// with D = W - W' (the change of every finished column) and g_j = sum_{i<j} D_i R_ij, the current value of
-// column j is w_j + g_j / R_jj and U_jj = 1 / R_jj.  So the working matrix is
-//     V_j = w_j R_jj + g_j      (= current weight / U_jj: its square is the saliency),
-// a kept entry becomes w' = V_j / R_jj, a pruned one 0, and finishing column j adds D_j R_j,j' to every later V_j'.
-// Per block of 128 columns: (1) the floor(s * rows * width) smallest V^2 of the block are found exactly by a
-// radix search over all rows together (ties by row-major position); (2) one wave per row walks the 128
-// columns in order, the block of R in LDS; (3) one fp32 matrix-core product adds D_block R[block, later] to V.
+// with D = W - W' (the change of every finished column) and G_j = sum_{i<j} D_i R_ij,
+//     V_j = w_j R_jj + G_j
+// is, once every column before j is finished, the current weight of column j divided by U_jj = 1 / R_jj: a kept
+// entry becomes w' = V_j / R_jj, a pruned one 0, and finishing column j adds D_j R_j,j' to every later G_j'.
+// The selection, however, looks at a whole block when only the columns before the block are finished.  The
+// published sweep's weights at that moment are W_block + G_block inv(R_bb) (R_bb the diagonal block of R; this is
+// the block form of U = R^-1), so the saliencies (w / U_jj)^2 of a block need one 128 x 128 triangular inverse and
+// one small product per block.
+// Per block of 128 columns: (1) T = G_block inv(R_bb) on the matrix cores, saliency ((w + T) R_jj)^2; (2) the
+// floor(s * rows * width) smallest saliencies of the block are found exactly by a radix search over all rows
+// together (ties by row-major position); (3) one wave walks the 128 columns in order for four rows at a time, the
+// block of R in LDS; (4) one fp32 matrix-core product adds D_block R[block, later] to G.
 #include "gemm_f32.hpp"
+#include "tri_inverse.hpp"
 
 namespace mp {
 
@@ -26,7 +32,7 @@ struct SweepState {
     uint32_t prefix, need, key, need_eq, count_eq, pad0, pad1, pad2;
 };
 
-__device__ __forceinline__ uint32_t saliency_key(float v) { return __float_as_uint(__fmul_rn(v, v)) & 0x7fffffffu; }
+__device__ __forceinline__ uint32_t saliency_key(float saliency) { return __float_as_uint(saliency) & 0x7fffffffu; }
 
 __device__ __forceinline__ bf16_t narrow_bf16(float f) {  // round to nearest, ties to even
     const uint32_t b = __float_as_uint(f);
@@ -36,17 +42,47 @@ __device__ __forceinline__ bf16_t narrow_bf16(float f) {  // round to nearest, t
 __device__ __forceinline__ void store_as(bf16_t *p, float f) { *p = narrow_bf16(f); }
 __device__ __forceinline__ void store_as(float *p, float f) { *p = f; }
 
-// V = W * diag(R), zero in dead columns
+__global__ __launch_bounds__(256) void sweep_zero(float *__restrict__ g, int64_t n) {
+    for (int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; e < n;
+         e += static_cast<int64_t>(gridDim.x) * 256)
+        g[e] = 0.f;
+}
+
+// inv(R_bb) of the diagonal blocks first_block + blockIdx.x of R, each to a dense [128 x 128] slot (zero padded)
+__global__ __launch_bounds__(256) void invert_diagonal_blocks(const float *__restrict__ r, int64_t ld_r, int64_t cols,
+                                                              int64_t first_block, float *__restrict__ dinv_all) {
+    __shared__ float d[kTriN][kTriPitch];
+    __shared__ float u[kTriN][kTriPitch];
+    const int tid = threadIdx.x;
+    const int64_t c0 = (first_block + blockIdx.x) * kSB;
+    const int sz = static_cast<int>(cols - c0 < kSB ? cols - c0 : kSB);
+    for (int e = tid; e < kTriN * kTriN; e += 256) {
+        const int i = e >> 7, k = e & (kTriN - 1);
+        d[i][k] = (i < sz && k < sz && i <= k) ? r[(c0 + i) * ld_r + c0 + k] : 0.f;
+        u[i][k] = 0.f;
+    }
+    __syncthreads();
+    invert_upper_triangle(d, u, sz, tid);
+    float *out = dinv_all + static_cast<int64_t>(blockIdx.x) * (kSB * kSB);
+    for (int e = tid; e < kSB * kSB; e += 256) out[e] = u[e >> 7][e & (kSB - 1)];
+}
+
+// saliency of the block's entries at the moment the block starts: ((w + t) * R_jj)^2, t = (G_block inv(R_bb))
 template <typename T>
-__global__ __launch_bounds__(256) void sweep_init(const T *__restrict__ w, int64_t ld_w, const float *__restrict__ r,
-                                                  int64_t ld_r, const uint8_t *__restrict__ dead, int64_t rows,
-                                                  int64_t cols, float *__restrict__ v) {
-    const int64_t n = rows * cols;
+__global__ __launch_bounds__(256) void block_saliency(const T *__restrict__ w, int64_t ld_w, const float *__restrict__ r,
+                                                      int64_t ld_r, const uint8_t *__restrict__ dead,
+                                                      const float *__restrict__ t, int64_t rows, int64_t c0, int width,
+                                                      float *__restrict__ sal, int64_t ld_sal) {
+    const int64_t n = rows * kSB;
     for (int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; e < n;
          e += static_cast<int64_t>(gridDim.x) * 256) {
-        const int64_t i = e / cols, j = e - i * cols;
-        const bool off = dead && dead[j];
-        v[e] = off ? 0.f : __fmul_rn(widen(w[i * ld_w + j]), r[j * ld_r + j]);
+        const int64_t i = e >> 7;
+        const int j = static_cast<int>(e & (kSB - 1));
+        if (j >= width) continue;
+        const bool off = dead && dead[c0 + j];
+        const float current = (off ? 0.f : widen(w[i * ld_w + c0 + j])) + t[e];
+        const float scaled = __fmul_rn(current, r[(c0 + j) * ld_r + c0 + j]);
+        sal[i * ld_sal + j] = __fmul_rn(scaled, scaled);
     }
 }
 
@@ -188,8 +224,9 @@ constexpr int kRowsPerWave = 4;
 template <typename T>
 __global__ __launch_bounds__(256) void sweep_block(const T *w, int64_t ld_w, T *w_out, int64_t ld_out,
                                                    const float *__restrict__ r, int64_t ld_r,
-                                                   const uint8_t *__restrict__ dead, float *__restrict__ v, int64_t ldv,
-                                                   int64_t rows, int64_t c0, int width, int mode,
+                                                   const uint8_t *__restrict__ dead, const float *__restrict__ g, int64_t ldg,
+                                                   const float *__restrict__ sal, int64_t ld_sal, int64_t rows,
+                                                   int64_t c0, int width, int mode,
                                                    const SweepState *__restrict__ state,
                                                    const uint32_t *__restrict__ row_before, float *__restrict__ dblk,
                                                    uint32_t *__restrict__ mask_bits, int64_t words_per_row,
@@ -214,6 +251,7 @@ __global__ __launch_bounds__(256) void sweep_block(const T *w, int64_t ld_w, T *
     const bool valid0 = lane < width, valid1 = lane + 64 < width;
     const bool dead0 = valid0 && dead && dead[c0 + lane], dead1 = valid1 && dead && dead[c0 + lane + 64];
     const int n0 = width < 64 ? width : 64;
+    const float rd0 = valid0 ? rb[lane][lane] : 0.f, rd1 = valid1 ? rb[lane + 64][lane + 64] : 0.f;
     const unsigned long long live0 = __ballot(valid0), live1 = __ballot(valid1);
     for (int64_t base = (static_cast<int64_t>(blockIdx.x) * 4 + (tid >> 6)) * NR; base < rows;
          base += static_cast<int64_t>(gridDim.x) * 4 * NR) {
@@ -223,14 +261,14 @@ __global__ __launch_bounds__(256) void sweep_block(const T *w, int64_t ld_w, T *
         for (int q = 0; q < NR; ++q) {
             const int64_t row = base + q;
             const bool live = row < rows;
-            v0[q] = (live && valid0) ? v[row * ldv + c0 + lane] : 0.f;
-            v1[q] = (live && valid1) ? v[row * ldv + c0 + lane + 64] : 0.f;
             w0[q] = (live && valid0 && !dead0) ? widen(w[row * ld_w + c0 + lane]) : 0.f;
             w1[q] = (live && valid1 && !dead1) ? widen(w[row * ld_w + c0 + lane + 64]) : 0.f;
+            v0[q] = (live && valid0) ? fmaf(w0[q], rd0, g[row * ldg + c0 + lane]) : 0.f;
+            v1[q] = (live && valid1) ? fmaf(w1[q], rd1, g[row * ldg + c0 + lane + 64]) : 0.f;
             bool p0 = mode == 2 && valid0, p1 = mode == 2 && valid1;
             if (mode == 1) {
-                const uint32_t k0 = valid0 ? saliency_key(v0[q]) : 0xffffffffu;
-                const uint32_t k1 = valid1 ? saliency_key(v1[q]) : 0xffffffffu;
+                const uint32_t k0 = (live && valid0) ? saliency_key(sal[row * ld_sal + lane]) : 0xffffffffu;
+                const uint32_t k1 = (live && valid1) ? saliency_key(sal[row * ld_sal + lane + 64]) : 0xffffffffu;
                 const bool e0 = k0 == skey, e1 = k1 == skey;
                 if (all_eq) {
                     p0 = k0 <= skey;
@@ -298,7 +336,7 @@ __global__ __launch_bounds__(256) void sweep_block(const T *w, int64_t ld_w, T *
 }
 
 struct SweepLayout {
-    size_t v, d, hist, state, row_eq, row_before, total;
+    size_t v, d, t, sal, dinv, hist, state, row_eq, row_before, total;
 };
 
 SweepLayout sweep_layout(int64_t rows, int64_t cols, bool own_v) {
@@ -309,6 +347,12 @@ SweepLayout sweep_layout(int64_t rows, int64_t cols, bool own_v) {
     at += own_v ? up(static_cast<size_t>(rows) * cols * 4) : 0;
     l.d = at;
     at += up(static_cast<size_t>(rows) * kSB * 4);
+    l.t = at;
+    at += up(static_cast<size_t>(rows) * kSB * 4);
+    l.sal = at;
+    at += up(static_cast<size_t>(rows) * kSB * 4);
+    l.dinv = at;
+    at += up(static_cast<size_t>(ceil_div(cols, kSB)) * kSB * kSB * 4);
     l.hist = at;
     at += up(kHistBins * 4);
     l.state = at;
@@ -323,18 +367,24 @@ SweepLayout sweep_layout(int64_t rows, int64_t cols, bool own_v) {
 
 template <typename T>
 int sweep_run(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld_w, int64_t ld_out, const float *r,
-              int64_t ld_r, const uint8_t *dead, double sparsity, int64_t first_block, int64_t n_blocks, float *v,
-              uint32_t *mask_bits, char *ws, const SweepLayout &l, hipStream_t stream) {
+              int64_t ld_r, const uint8_t *dead, double sparsity, int64_t first_block, int64_t n_blocks, float *g,
+              float *saliency, uint32_t *mask_bits, char *ws, const SweepLayout &l, hipStream_t stream) {
     float *dblk = reinterpret_cast<float *>(ws + l.d);
+    float *tbuf = reinterpret_cast<float *>(ws + l.t);
+    float *dinv_all = reinterpret_cast<float *>(ws + l.dinv);
     uint32_t *hist = reinterpret_cast<uint32_t *>(ws + l.hist);
     SweepState *state = reinterpret_cast<SweepState *>(ws + l.state);
     uint32_t *row_eq = reinterpret_cast<uint32_t *>(ws + l.row_eq);
     uint32_t *row_before = reinterpret_cast<uint32_t *>(ws + l.row_before);
     const int64_t words = ceil_div(cols, 32);
+    if (n_blocks == 0) return PRUNE_OK;
     if (first_block == 0) {
-        hipLaunchKernelGGL(sweep_init<T>, dim3(2048), dim3(256), 0, stream, w, ld_w, r, ld_r, dead, rows, cols, v);
+        hipLaunchKernelGGL(sweep_zero, dim3(2048), dim3(256), 0, stream, g, rows * cols);
         if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
     }
+    hipLaunchKernelGGL(invert_diagonal_blocks, dim3(static_cast<unsigned>(n_blocks)), dim3(256), 0, stream, r, ld_r, cols,
+                       first_block, dinv_all);
+    if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
     const unsigned row_tiles = static_cast<unsigned>(ceil_div(rows, 16));
     const unsigned row_quads = static_cast<unsigned>(ceil_div(rows, 4) < 512 ? ceil_div(rows, 4) : 512);
     const unsigned row_groups = static_cast<unsigned>(ceil_div(rows, 4 * kRowsPerWave) < 1024 ? ceil_div(rows, 4 * kRowsPerWave) : 1024);
@@ -345,25 +395,35 @@ int sweep_run(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld_w, in
         const int64_t n_el = rows * width;
         const int64_t k = quota < 0 ? 0 : static_cast<int64_t>(quota);
         const int mode = k <= 0 ? 0 : k >= n_el ? 2 : 1;
+        float *sal = saliency ? saliency + c0 : reinterpret_cast<float *>(ws + l.sal);
+        const int64_t ld_sal = saliency ? cols : kSB;
+        if (mode == 1 || saliency) {
+            // the weights of the block as the published sweep holds them when the block starts: W + G inv(R_bb)
+            int st = launch_gemm_f32<kBKN>(static_cast<int>(rows), width, width, 1.f, g + c0, cols,
+                                           dinv_all + (b - first_block) * (kSB * kSB), kSB, 0.f, tbuf, kSB, false, stream);
+            if (st != PRUNE_OK) return st;
+            hipLaunchKernelGGL(block_saliency<T>, dim3(1024), dim3(256), 0, stream, w, ld_w, r, ld_r, dead, tbuf, rows, c0,
+                               width, sal, ld_sal);
+        }
         if (mode == 1) {
             hipLaunchKernelGGL(select_begin, dim3(1), dim3(1024), 0, stream, state, hist, static_cast<uint32_t>(k));
-            hipLaunchKernelGGL(select_hist<0>, dim3(row_tiles), dim3(256), 0, stream, v, cols, c0, width, rows, state, hist);
+            hipLaunchKernelGGL(select_hist<0>, dim3(row_tiles), dim3(256), 0, stream, sal, ld_sal, int64_t(0), width, rows, state, hist);
             hipLaunchKernelGGL(select_locate<0>, dim3(1), dim3(1024), 0, stream, state, hist);
-            hipLaunchKernelGGL(select_hist<1>, dim3(row_tiles), dim3(256), 0, stream, v, cols, c0, width, rows, state, hist);
+            hipLaunchKernelGGL(select_hist<1>, dim3(row_tiles), dim3(256), 0, stream, sal, ld_sal, int64_t(0), width, rows, state, hist);
             hipLaunchKernelGGL(select_locate<1>, dim3(1), dim3(1024), 0, stream, state, hist);
-            hipLaunchKernelGGL(select_hist<2>, dim3(row_tiles), dim3(256), 0, stream, v, cols, c0, width, rows, state, hist);
+            hipLaunchKernelGGL(select_hist<2>, dim3(row_tiles), dim3(256), 0, stream, sal, ld_sal, int64_t(0), width, rows, state, hist);
             hipLaunchKernelGGL(select_locate<2>, dim3(1), dim3(1024), 0, stream, state, hist);
-            hipLaunchKernelGGL(tie_count, dim3(row_quads), dim3(256), 0, stream, v, cols, c0, width, rows, state, row_eq);
+            hipLaunchKernelGGL(tie_count, dim3(row_quads), dim3(256), 0, stream, sal, ld_sal, int64_t(0), width, rows, state, row_eq);
             hipLaunchKernelGGL(tie_scan, dim3(1), dim3(1024), 0, stream, row_eq, row_before, rows, state);
             if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
         }
         hipLaunchKernelGGL(sweep_block<T>, dim3(row_groups), dim3(256), 0, stream, w, ld_w, w_out, ld_out, r, ld_r, dead,
-                           v, cols, rows, c0, width, mode, state, row_before, dblk, mask_bits, words, cols);
+                           g, cols, sal, ld_sal, rows, c0, width, mode, state, row_before, dblk, mask_bits, words, cols);
         if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
         const int64_t c1 = c0 + width;
         if (c1 < cols) {
             const int st = launch_gemm_f32<kBKN>(static_cast<int>(rows), static_cast<int>(cols - c1), width, 1.f, dblk,
-                                                 kSB, r + c0 * ld_r + c1, ld_r, 1.f, v + c1, cols, false, stream);
+                                                 kSB, r + c0 * ld_r + c1, ld_r, 1.f, g + c1, cols, false, stream);
             if (st != PRUNE_OK) return st;
         }
     }
@@ -381,8 +441,8 @@ extern "C" size_t prune_obs_sweep_workspace_bytes(int64_t rows, int64_t cols, in
 
 extern "C" int prune_obs_sweep(const void *w, void *w_out, int dtype, int64_t rows, int64_t cols, int64_t ld_w,
                                int64_t ld_out, const float *r, int64_t ld_r, const uint8_t *dead, double sparsity,
-                               int64_t first_block, int64_t n_blocks, float *v, uint32_t *mask_bits, void *ws,
-                               size_t ws_bytes, void *stream_) {
+                               int64_t first_block, int64_t n_blocks, float *v, float *saliency, uint32_t *mask_bits,
+                               void *ws, size_t ws_bytes, void *stream_) {
     using namespace mp;
     if (!valid_dtype(dtype)) return PRUNE_ERR_DTYPE;
     if (rows <= 0 || cols <= 0 || ld_w < cols || ld_out < cols || ld_r < cols || rows > (int64_t(1) << 22) ||
@@ -397,7 +457,7 @@ extern "C" int prune_obs_sweep(const void *w, void *w_out, int dtype, int64_t ro
     if (first_block < 0 || n_blocks < 0 || first_block + n_blocks > total_blocks) return PRUNE_ERR_RANGE;
     const size_t es = elem_size(dtype);
     if (!aligned_to(w, es) || !aligned_to(w_out, es) || !aligned_to(r, 16) || !aligned_to(ws, 256) ||
-        (v && !aligned_to(v, 16)) || (mask_bits && !aligned_to(mask_bits, 4)))
+        (v && !aligned_to(v, 16)) || (saliency && !aligned_to(saliency, 4)) || (mask_bits && !aligned_to(mask_bits, 4)))
         return PRUNE_ERR_ALIGNMENT;
     const SweepLayout l = sweep_layout(rows, cols, v == nullptr);
     if (ws_bytes < l.total) return PRUNE_ERR_WORKSPACE;
@@ -406,7 +466,7 @@ extern "C" int prune_obs_sweep(const void *w, void *w_out, int dtype, int64_t ro
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     if (dtype == PRUNE_BF16)
         return sweep_run(static_cast<const bf16_t *>(w), static_cast<bf16_t *>(w_out), rows, cols, ld_w, ld_out, r, ld_r,
-                         dead, sparsity, first_block, n_blocks, vv, mask_bits, base, l, stream);
+                         dead, sparsity, first_block, n_blocks, vv, saliency, mask_bits, base, l, stream);
     return sweep_run(static_cast<const float *>(w), static_cast<float *>(w_out), rows, cols, ld_w, ld_out, r, ld_r, dead,
-                     sparsity, first_block, n_blocks, vv, mask_bits, base, l, stream);
+                     sparsity, first_block, n_blocks, vv, saliency, mask_bits, base, l, stream);
 }

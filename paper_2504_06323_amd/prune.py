@@ -47,7 +47,7 @@ _SIGNATURES = {
     "prune_hessian_factor": (_int, [_vp, _i64, _i64, _f64, _vp, _vp, _vp, _sz, _vp]),
     "prune_obs_sweep_workspace_bytes": (_sz, [_i64, _i64, _int]),
     "prune_obs_sweep": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _i64, _vp, _i64, _vp, _f64, _i64, _i64, _vp, _vp, _vp,
-                               _sz, _vp]),
+                               _vp, _sz, _vp]),
     "prune_plan_sparsity_device": (_int, [_vp, _vp, _vp, _int, _int, _f64, _f64, _int, _vp, _vp, _vp, _vp]),
     "prune_struct_groups_workspace_bytes": (_sz, [_vp, _vp, _int, _vp, _vp, _int, _i64]),
     "prune_struct_groups": (_int, [_vp, _vp, _vp, _int, _vp, _vp, _vp, _int, _int, _i64, _u32, _vp, _vp, _vp, _vp,
@@ -391,7 +391,7 @@ def hessian_factor(h: torch.Tensor, damp: float = 0.01, dead: Optional[torch.Ten
 def obs_sweep(w: torch.Tensor, r: torch.Tensor, sparsity: float, w_out: Optional[torch.Tensor] = None,
               dead: Optional[torch.Tensor] = None, first_block: int = 0, n_blocks: int = -1,
               v: Optional[torch.Tensor] = None, mask_bits: Optional[torch.Tensor] = None,
-              ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+              ws: Optional[torch.Tensor] = None, stream=None, saliency: Optional[torch.Tensor] = None) -> torch.Tensor:
     """Compensated pruning sweep of one projection (prune_obs_sweep).  In place when w_out is None.
     Returns the workspace, which a caller sweeping in several calls hands back in."""
     ptr, rows, cols, ld = _matrix(w, "w")
@@ -412,6 +412,7 @@ def obs_sweep(w: torch.Tensor, r: torch.Tensor, sparsity: float, w_out: Optional
            load().prune_obs_sweep(ptr, out_ptr, _dtype_code(w), rows, cols, ld, ld_out, r.data_ptr(), r.stride(0),
                                   _vector(dead, "dead", torch.uint8, cols), float(sparsity), int(first_block),
                                   int(n_blocks), _vector(v, "v", torch.float32, rows * cols),
+                                  _vector(saliency, "saliency", torch.float32, rows * cols),
                                   None if mask_bits is None else _vector(mask_bits, "mask_bits", mask_bits.dtype,
                                                                          rows * ((cols + 31) // 32)),
                                   ws.data_ptr(), ws.numel(), _stream(stream)))

@@ -167,13 +167,18 @@ def test_factor_reports_a_bad_pivot(lib):
 
 # ----------------------------------------------------------------- compensated sweep
 
-def _sweep_case(rows, cols, tokens, dtype, sparsity, seed, zero_frac=0.0, dead_cols=()):
-    """Run the sweep one 128-column block at a time, looking at the working matrix before every block.
+def _sweep_case(rows, cols, tokens, dtype, sparsity, seed, zero_frac=0.0, dead_cols=(), mix=0.1):
+    """Run the sweep one 128-column block at a time and record the saliencies every block's selection was taken on.
 
     The selection is an integer decision taken on fp32 saliencies, so the oracle takes it on the very saliencies
-    the kernel saw (the square, in fp32, of the working matrix at the start of the block); everything else of the
-    oracle runs in float64 on the factor the kernel was given."""
-    x = _acts(tokens, cols, torch.bfloat16, seed=seed)
+    the kernel computed -- after checking that they are the oracle's own float64 saliencies at that moment, to
+    rounding; everything else of the oracle runs in float64 on the factor the kernel was given.  The activation
+    channels are correlated (mix), so that compensation between columns and blocks matters."""
+    rng = np.random.default_rng(seed)
+    x = _acts(tokens, cols, torch.float32, seed=seed)
+    mixer = torch.tensor(np.eye(cols) + mix * rng.standard_normal((cols, cols)) / np.sqrt(cols) * 8, dtype=torch.float32,
+                         device=DEV)
+    x = (x @ mixer).to(torch.bfloat16)
     for c in dead_cols:
         x[:, c] = 0
     w = synth.random_matrix(rows, cols, dtype, seed=seed + 1, device=DEV, scale=0.05, zero_frac=zero_frac)
@@ -185,27 +190,32 @@ def _sweep_case(rows, cols, tokens, dtype, sparsity, seed, zero_frac=0.0, dead_c
     _sync()
     assert info.item() == 0 and sorted(np.nonzero(to_np(dead))[0].tolist()) == sorted(dead_cols)
     r64 = np.triu(to_np(h).astype(np.float64))
-    v = torch.full((rows, cols), float("nan"), dtype=torch.float32, device=DEV)
+    g = torch.full((rows, cols), float("nan"), dtype=torch.float32, device=DEV)
+    sal = torch.full((rows, cols), float("nan"), dtype=torch.float32, device=DEV)
     w_out = torch.full_like(w, 7.0)
     bits = torch.full((rows, (cols + 31) // 32), -1, dtype=torch.int32, device=DEV)
     n_blocks = (cols + 127) // 128
     w0 = to_np(w).astype(np.float64)
     w0[:, to_np(dead).astype(bool)] = 0.0
-    seen = []                                           # fp32 saliencies the kernel's selection saw, per block
     ws = None
     for b in range(n_blocks):
-        c0, c1 = 128 * b, min(128 * b + 128, cols)
-        if b == 0:                                      # the working matrix starts as w * diag(R), one fp32 product
-            vb = w0[:, c0:c1].astype(np.float32) * np.diag(r64)[c0:c1].astype(np.float32)[None, :]
-        else:
-            vb = to_np(v[:, c0:c1])
-        seen.append(vb.astype(np.float32) * vb.astype(np.float32))
-        ws = prune.obs_sweep(w, h, sparsity, w_out=w_out, dead=dead, first_block=b, n_blocks=1, v=v, mask_bits=bits,
-                             ws=ws)
-        _sync()
-    calls = iter(seen)
-    want_w, want_pruned = obs.obs_sweep(w0, np.linalg.inv(r64), sparsity, block=128,
-                                        saliency_fn=lambda wb, ud: next(calls))
+        ws = prune.obs_sweep(w, h, sparsity, w_out=w_out, dead=dead, first_block=b, n_blocks=1, v=g, mask_bits=bits,
+                             ws=ws, saliency=sal)
+    _sync()
+    seen = to_np(sal)
+    assert np.isfinite(seen).all()
+    calls = iter(range(n_blocks))
+    worst = [0.0]
+
+    def kernel_saliency(w_block, u_diag):
+        b = next(calls)
+        mine = obs.block_saliency(w_block, u_diag)                       # the oracle's own, float64, at this moment
+        theirs = seen[:, 128 * b:128 * b + w_block.shape[1]].astype(np.float64)
+        worst[0] = max(worst[0], float(np.max(np.abs(theirs - mine)) / np.max(mine)))
+        return theirs
+
+    want_w, want_pruned = obs.obs_sweep(w0, np.linalg.inv(r64), sparsity, block=128, saliency_fn=kernel_saliency)
+    assert worst[0] < 2e-5, worst[0]                                     # fp32 saliencies against float64 ones
     got_w = to_np(w_out).astype(np.float64)
     assert np.array_equal(to_np(bits).view(np.uint32), orc.pack_keep_bits(want_pruned))      # the same entries go
     assert (got_w[want_pruned] == 0).all()
@@ -280,18 +290,18 @@ def test_obs_fullsize_q_projection(lib):
     scale = np.sqrt(np.diag(h_damped)[ii] * np.diag(h_damped)[jj])
     assert np.max(np.abs(rrt - h_damped[ii, jj]) / scale) < 1e-5
     sparsity = 0.53
-    v = torch.zeros((rows, cols), dtype=torch.float32, device=DEV)
+    g = torch.zeros((rows, cols), dtype=torch.float32, device=DEV)
+    sal = torch.zeros((rows, cols), dtype=torch.float32, device=DEV)
     w_out = torch.empty_like(w)
     bits = torch.zeros((rows, cols // 32), dtype=torch.int32, device=DEV)
     w0 = to_np(w).astype(np.float64)
-    rdiag = np.diag(r64)
     ws, watch, snaps = None, (0, 1, 17, 31), {}
     for b in range(cols // 128):
-        if b in watch and b > 0:
-            snaps[b] = to_np(v[:, 128 * b:128 * b + 128]).copy()
-        ws = prune.obs_sweep(w, h, sparsity, w_out=w_out, first_block=b, n_blocks=1, v=v, mask_bits=bits, ws=ws)
+        if b in watch:
+            snaps[b] = np.zeros((rows, 128), dtype=np.float32) if b == 0 else to_np(g[:, 128 * b:128 * b + 128]).copy()
+        ws = prune.obs_sweep(w, h, sparsity, w_out=w_out, first_block=b, n_blocks=1, v=g, mask_bits=bits, ws=ws,
+                             saliency=sal)
     _sync()
-    snaps[0] = w0[:, :128].astype(np.float32) * rdiag[:128].astype(np.float32)[None, :]
     got = to_np(w_out).astype(np.float64)
     keep = to_np(bits).view(np.uint32)
     quota = obs.block_quota(sparsity, rows, 128)
@@ -301,12 +311,17 @@ def test_obs_fullsize_q_projection(lib):
     assert (got[pruned_all] == 0).all()
     for b in watch:
         c0 = 128 * b
-        vb = snaps[b].astype(np.float32)
-        want_mask = obs.select_block(vb * vb, quota)                        # the oracle's selection on the kernel's saliencies
-        assert np.array_equal(pruned_all[:, c0:c0 + 128], want_mask), b
-        # float64 replay of the block from its working matrix: kept w' = V_j / R_jj, D_j = w_j - w'_j spreads with R
-        cur = vb.astype(np.float64)
+        gb = snaps[b].astype(np.float64)                                    # the kernel's state when the block started
         rb = r64[c0:c0 + 128, c0:c0 + 128]
+        # the published sweep's weights at that moment, W + G inv(R_bb), and their saliencies (w / U_jj)^2 = (w R_jj)^2
+        current = w0[:, c0:c0 + 128] + gb @ np.linalg.inv(rb)
+        sal64 = (current * np.diag(rb)[None, :]) ** 2
+        sal32 = to_np(sal[:, c0:c0 + 128])
+        assert np.max(np.abs(sal32 - sal64)) / np.max(sal64) < 5e-5, b
+        want_mask = obs.select_block(sal32, quota)                          # the oracle's selection on the kernel's saliencies
+        assert np.array_equal(pruned_all[:, c0:c0 + 128], want_mask), b
+        # float64 replay of the block: V_j = w_j R_jj + G_j; kept w' = V_j / R_jj, D_j = w_j - w'_j spreads with R
+        cur = w0[:, c0:c0 + 128] * np.diag(rb)[None, :] + gb
         want = np.zeros((rows, 128))
         for j in range(128):
             want[:, j] = np.where(want_mask[:, j], 0.0, cur[:, j] / rb[j, j])
@@ -350,3 +365,35 @@ def test_pipeline_streams_give_the_same_bits(lib):
         assert torch.equal(out, st.pruned[n]) and torch.equal(bits, st.mask_bits[n]), n
         quota = sum(obs.block_quota(targets[i], rows, min(128, cols - c)) for c in range(0, cols, 128))
         assert int((~np.unpackbits(to_np(bits).view(np.uint8), axis=1, bitorder="little").astype(bool))[:, :cols].sum()) == quota
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_whole_pruner_against_the_float64_oracle(lib, dtype):
+    """All three stages on the GPU against obs_prune in float64 with its own decisions.  Near-equal saliencies may
+    be taken in a different order, so a few individual weights may differ; what must agree is what the method is
+    for: the same number of weights goes in every block and the layer output on the calibration data is reproduced
+    equally well."""
+    rows, cols, tokens, sparsity = 96, 512, 3000, 0.6
+    rng = np.random.default_rng(3)
+    mix = torch.tensor(np.eye(cols) + 0.15 * rng.standard_normal((cols, cols)), dtype=torch.float32, device=DEV)
+    x = (synth.random_matrix(tokens, cols, torch.float32, seed=5, device=DEV) @ mix).to(torch.bfloat16)   # correlated channels
+    w = synth.random_matrix(rows, cols, dtype, seed=6, device=DEV, scale=0.05)
+    h = torch.zeros((cols, cols), dtype=torch.float32, device=DEV)
+    prune.hessian_accumulate(x, h)
+    dead = torch.zeros(cols, dtype=torch.uint8, device=DEV)
+    prune.hessian_factor(h, 0.01, dead=dead)
+    out = torch.empty_like(w)
+    bits = torch.zeros((rows, cols // 32), dtype=torch.int32, device=DEV)
+    prune.obs_sweep(w, h, sparsity, w_out=out, dead=dead, mask_bits=bits)
+    _sync()
+    x64, w64 = to_np(x).astype(np.float64), to_np(w).astype(np.float64)
+    want_w, want_pruned = obs.obs_prune(x64, w64, sparsity)
+    got_w = to_np(out).astype(np.float64)
+    got_pruned = ~np.unpackbits(to_np(bits).view(np.uint8), axis=1, bitorder="little").astype(bool)
+    assert np.array_equal(got_pruned.reshape(rows, -1, 128).sum(axis=(0, 2)), want_pruned.reshape(rows, -1, 128).sum(axis=(0, 2)))
+    assert np.mean(got_pruned != want_pruned) < 2e-3                         # only near-ties may be decided differently
+    hd, _ = obs.damped_hessian(obs.gram_matrix(x64))
+    e_gpu, e_ref = obs.reconstruction_error(w64, got_w, hd), obs.reconstruction_error(w64, want_w, hd)
+    e_plain = obs.reconstruction_error(w64, np.where(want_pruned, 0.0, w64), hd)
+    assert e_ref < 0.8 * e_plain                                             # correlated channels: compensation matters here
+    assert abs(e_gpu / e_ref - 1.0) < (2e-2 if dtype == torch.bfloat16 else 2e-3)

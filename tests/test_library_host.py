@@ -146,9 +146,9 @@ def test_error_paths_return_before_any_launch(lib):
     sw = lib.prune_obs_sweep
     big = ctypes.c_void_p(0x10000)
     ok = lambda **kw: sw(*[{**dict(w=big, o=big, dt=1, rows=8, cols=8, ldw=8, ldo=8, r=big, ldr=8, dead=None, s=0.5, fb=0,
-                                  nb=-1, v=None, mb=None, ws=big, wsb=1 << 30, st=None), **kw}[k]
+                                  nb=-1, v=None, sal=None, mb=None, ws=big, wsb=1 << 30, st=None), **kw}[k]
                            for k in ("w", "o", "dt", "rows", "cols", "ldw", "ldo", "r", "ldr", "dead", "s", "fb", "nb", "v",
-                                     "mb", "ws", "wsb", "st")])
+                                     "sal", "mb", "ws", "wsb", "st")])
     assert ok(dt=5) == E["dtype"]
     assert ok(rows=0) == E["shape"]
     assert ok(cols=6, ldw=6, ldo=6) == E["shape"]                                  # cols must be a multiple of 4
