@@ -3,7 +3,7 @@
 // A [M, K] row-major; op(B) = B for B [K, N] row-major (kBKN) or B^T for B [N, K] row-major (kBNK);
 // C [M, N] row-major.  K and every leading dimension are multiples of 4 and all bases 16-byte aligned
 // (checked by the callers), M and N are arbitrary.  A block of four waves owns a 128 x 128 tile of C
-// (64 x 64 per wave, four 32 x 32 x 2 MFMA accumulators), K is walked 16 at a time through LDS with both
+// (64 x 64 per wave, four 32 x 32 x 2 MFMA accumulators), K is walked 32 at a time through LDS with both
 // operands stored k-major so that a wave reads 32 consecutive floats per MFMA operand.  One owner per
 // output element and a fixed order over K: results are reproducible.  C may be the same memory as A when N <= 128
 // (a block then reads all of its rows of A before it writes them).
@@ -18,14 +18,16 @@ enum GemmB { kBKN = 0, kBNK = 1 };
 namespace gemm_detail {
 
 typedef __attribute__((ext_vector_type(16))) float f32x16;
-constexpr int kTileMN = 128, kTileK = 16, kPitch = kTileMN + 4;
+constexpr int kTileMN = 128, kTileK = 32, kPitch = kTileMN + 4;
 
 template <int BL>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, float alpha, const float *A, int64_t lda,
                                                        const float *B, int64_t ldb, float beta, float *C,
                                                        int64_t ldc,
                                                        int upper_tiles_only) {
-    __shared__ float sa[kTileK][kPitch], sb[kTileK][kPitch];
+    __shared__ __attribute__((aligned(16))) float smem[2][kTileK][kPitch];
+    float (&sa)[kTileK][kPitch] = smem[0];
+    float (&sb)[kTileK][kPitch] = smem[1];
     const int m0 = blockIdx.y * kTileMN, n0 = blockIdx.x * kTileMN;
     if (upper_tiles_only && n0 + kTileMN <= m0) return;  // tile strictly below the diagonal: not needed
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
@@ -40,8 +42,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, floa
     for (int k0 = 0; k0 < K; k0 += kTileK) {
         // A tile: rows m0 .. m0 + 127, four consecutive k per thread and pass
 #pragma unroll
-        for (int p = 0; p < 2; ++p) {
-            const int r = (tid >> 2) + 64 * p, kk = (tid & 3) * 4;
+        for (int p = 0; p < 4; ++p) {
+            const int r = (tid >> 3) + 32 * p, kk = (tid & 7) * 4;
             f32x4 v = {0.f, 0.f, 0.f, 0.f};
             if (m0 + r < M && k0 + kk < K) v = *reinterpret_cast<const f32x4 *>(A + (m0 + r) * lda + k0 + kk);
 #pragma unroll
@@ -49,8 +51,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, floa
         }
         if (BL == kBNK) {
 #pragma unroll
-            for (int p = 0; p < 2; ++p) {
-                const int r = (tid >> 2) + 64 * p, kk = (tid & 3) * 4;
+            for (int p = 0; p < 4; ++p) {
+                const int r = (tid >> 3) + 32 * p, kk = (tid & 7) * 4;
                 f32x4 v = {0.f, 0.f, 0.f, 0.f};
                 if (n0 + r < N && k0 + kk < K) v = *reinterpret_cast<const f32x4 *>(B + (n0 + r) * ldb + k0 + kk);
 #pragma unroll
@@ -58,7 +60,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, floa
             }
         } else {
 #pragma unroll
-            for (int p = 0; p < 2; ++p) {
+            for (int p = 0; p < 4; ++p) {
                 const int kk = (tid >> 5) + 8 * p, c = (tid & 31) * 4;
                 f32x4 v = {0.f, 0.f, 0.f, 0.f};
                 if (k0 + kk < K) {
@@ -91,7 +93,53 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, floa
         }
         __syncthreads();
     }
-    // accumulator element v of lane l: row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32 of its 32 x 32 tile
+    // Accumulator element v of lane l: row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32 of its 32 x 32 tile.
+    // When C allows 16-byte accesses, a wave passes its tile through LDS eight rows at a time (the operand
+    // slices are dead by now), so that the update of C runs in 256-byte runs of 16 bytes per lane instead of
+    // 4-byte accesses: with K as short as it is here, reading and writing C is most of the memory traffic.
+    const bool wide = (ldc % 4 == 0) && (reinterpret_cast<uintptr_t>(C) % 16 == 0);
+    if (wide) {
+        constexpr int kEpPitch = 64 + 4;
+        float *ep = &smem[0][0][0] + wave * (8 * kEpPitch);
+        static_assert(4 * 8 * kEpPitch <= 2 * kTileK * kPitch, "the epilogue buffer fits in the operand slices");
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int vq = 0; vq < 4; ++vq) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        ep[(4 * (lane >> 5) + e) * kEpPitch + 32 * j + (lane & 31)] = acc[i][j][4 * vq + e];
+                // (only this wave touches its part of the buffer: LDS operations of a wave complete in order)
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const int rr = (lane + 64 * q) >> 4, c4 = ((lane + 64 * q) & 15) * 4;
+                    const f32x4 mine = *reinterpret_cast<const f32x4 *>(&ep[rr * kEpPitch + c4]);
+                    const int row = m0 + wm + 32 * i + 8 * vq + rr, col = n0 + wn + c4;
+                    if (row < M && col < N) {
+                        float *dst = C + row * ldc + col;
+                        if (col + 4 <= N) {
+                            f32x4 out;
+                            if (beta == 0.f) {
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) out[e] = alpha * mine[e];
+                            } else {
+                                const f32x4 old = *reinterpret_cast<const f32x4 *>(dst);
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) out[e] = beta * old[e] + alpha * mine[e];
+                            }
+                            *reinterpret_cast<f32x4 *>(dst) = out;
+                        } else {
+#pragma unroll
+                            for (int e = 0; e < 4; ++e)
+                                if (col + e < N) dst[e] = beta == 0.f ? alpha * mine[e] : beta * dst[e] + alpha * mine[e];
+                        }
+                    }
+                }
+            }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
