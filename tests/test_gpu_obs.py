@@ -397,3 +397,47 @@ def test_whole_pruner_against_the_float64_oracle(lib, dtype):
     e_plain = obs.reconstruction_error(w64, np.where(want_pruned, 0.0, w64), hd)
     assert e_ref < 0.8 * e_plain                                             # correlated channels: compensation matters here
     assert abs(e_gpu / e_ref - 1.0) < (2e-2 if dtype == torch.bfloat16 else 2e-3)
+
+
+@pytest.mark.parametrize("channels", [5120, 13824, 14336])
+def test_obs_other_model_widths(lib, channels):
+    """Input widths of the other configurations (LLaMA-2-13B: 5120 / 13824, LLaMA-3-8B: 14336) through all three
+    stages with fewer tokens and rows: tile counts and splits that the 7B layer does not reach.  Sampled entries
+    of H and of R R^T against the oracle, exact quotas, and a better reconstruction than plain masking."""
+    tokens, rows, sparsity = 16384, 256, 0.5
+    x = _acts(tokens, channels, torch.bfloat16, seed=channels)
+    w = synth.random_matrix(rows, channels, torch.bfloat16, seed=channels + 1, device=DEV, scale=0.02)
+    h = torch.zeros((channels, channels), dtype=torch.float32, device=DEV)
+    prune.hessian_accumulate(x, h)
+    _sync()
+    rng = np.random.default_rng(channels)
+    idx = np.unique(np.concatenate([rng.choice(channels, size=48, replace=False), [0, 3, 255, 256, channels - 1]]))
+    xs = to_np(x[:, torch.as_tensor(idx, device=DEV)]).astype(np.float64)
+    want = xs.T @ xs
+    got = to_np(h)[np.ix_(idx, idx)].astype(np.float64)
+    d = np.sqrt(np.diag(want))
+    assert np.max(np.abs(got - want) / np.outer(d, d)) < 5e-6
+    assert bool(torch.equal(h, h.t()))
+    diag = to_np(torch.diagonal(h)).astype(np.float64)
+    damped = got + np.diag(np.full(len(idx), 0.01 * diag.mean()))
+    info = torch.zeros(1, dtype=torch.int32, device=DEV)
+    prune.hessian_factor(h, 0.01, info=info)
+    _sync()
+    assert info.item() == 0
+    r_rows = to_np(torch.triu(h)[torch.as_tensor(idx, device=DEV)]).astype(np.float64)
+    assert np.max(np.abs(r_rows @ r_rows.T - damped) / np.outer(d, d)) < 2e-5
+    out = torch.empty_like(w)
+    bits = torch.zeros((rows, channels // 32), dtype=torch.int32, device=DEV)
+    prune.obs_sweep(w, h, sparsity, w_out=out, mask_bits=bits)
+    _sync()
+    keep = to_np(bits).view(np.uint32)
+    per_block = _popcount32(keep).reshape(rows, channels // 128, 4).sum(axis=(0, 2))
+    assert (per_block == rows * 128 - obs.block_quota(sparsity, rows, 128)).all()
+    pruned = ~np.unpackbits(keep.view(np.uint8), axis=1, bitorder="little").astype(bool)
+    got_w, w0 = to_np(out).astype(np.float64), to_np(w).astype(np.float64)
+    assert (got_w[pruned] == 0).all()
+    # reconstruction error through R: ||(W - W') X^T||^2 + damping = ||(W - W') R||_F^2
+    r64 = to_np(torch.triu(h)).astype(np.float64)
+    e_obs = np.sum(((w0 - got_w) @ r64) ** 2)
+    e_plain = np.sum((np.where(pruned, w0, 0.0) @ r64) ** 2)
+    assert e_obs < e_plain
