@@ -67,34 +67,39 @@ __global__ __launch_bounds__(256) void invert_diagonal_blocks(const float *__res
     for (int e = tid; e < kSB * kSB; e += 256) out[e] = u[e >> 7][e & (kSB - 1)];
 }
 
-// saliency of the block's entries at the moment the block starts: ((w + t) * R_jj)^2, t = (G_block inv(R_bb))
-template <typename T>
-__global__ __launch_bounds__(256) void block_saliency(const T *__restrict__ w, int64_t ld_w, const float *__restrict__ r,
-                                                      int64_t ld_r, const uint8_t *__restrict__ dead,
-                                                      const float *__restrict__ t, int64_t rows, int64_t c0, int width,
-                                                      float *__restrict__ sal, int64_t ld_sal) {
-    const int64_t n = rows * kSB;
-    for (int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; e < n;
-         e += static_cast<int64_t>(gridDim.x) * 256) {
-        const int64_t i = e >> 7;
-        const int j = static_cast<int>(e & (kSB - 1));
-        if (j >= width) continue;
-        const bool off = dead && dead[c0 + j];
-        const float current = (off ? 0.f : widen(w[i * ld_w + c0 + j])) + t[e];
-        const float scaled = __fmul_rn(current, r[(c0 + j) * ld_r + c0 + j]);
-        sal[i * ld_sal + j] = __fmul_rn(scaled, scaled);
-    }
+// the search's global histogram is all zero between passes; this clears it once per call
+__global__ __launch_bounds__(1024) void select_reset(uint32_t *hist) {
+    for (int b = threadIdx.x; b < kHistBins; b += 1024) hist[b] = 0u;
 }
 
-__global__ __launch_bounds__(1024) void select_begin(SweepState *state, uint32_t *hist, uint32_t k) {
-    for (int b = threadIdx.x; b < kHistBins; b += 1024) hist[b] = 0u;
-    if (threadIdx.x == 0) {
-        state->prefix = 0u;
-        state->need = k;
-        state->key = 0u;
-        state->need_eq = 0u;
-        state->count_eq = 0u;
+// Saliency of the block's entries at the moment the block starts, ((w + t) * R_jj)^2 with t = G_block inv(R_bb),
+// stored for the later passes and for the sweep, and the first pass of the radix search over them (16 rows a block).
+template <typename T>
+__global__ __launch_bounds__(256) void saliency_first_pass(const T *__restrict__ w, int64_t ld_w,
+                                                           const float *__restrict__ r, int64_t ld_r,
+                                                           const uint8_t *__restrict__ dead, const float *__restrict__ t,
+                                                           int64_t rows, int64_t c0, int width, float *__restrict__ sal,
+                                                           int64_t ld_sal, uint32_t *__restrict__ hist) {
+    __shared__ uint32_t h[kHistBins];
+    const int tid = threadIdx.x;
+    for (int b = tid; b < kHistBins; b += 256) h[b] = 0u;
+    __syncthreads();
+    const int64_t r0 = static_cast<int64_t>(blockIdx.x) * 16;
+    for (int e = tid; e < 16 * kSB; e += 256) {
+        const int64_t row = r0 + (e >> 7);
+        const int col = e & (kSB - 1);
+        if (row < rows && col < width) {
+            const bool off = dead && dead[c0 + col];
+            const float current = (off ? 0.f : widen(w[row * ld_w + c0 + col])) + t[row * kSB + col];
+            const float scaled = __fmul_rn(current, r[(c0 + col) * ld_r + c0 + col]);
+            const float s2 = __fmul_rn(scaled, scaled);
+            sal[row * ld_sal + col] = s2;
+            atomicAdd(&h[saliency_key(s2) >> 20], 1u);
+        }
     }
+    __syncthreads();
+    for (int b = tid; b < kHistBins; b += 256)
+        if (h[b]) atomicAdd(&hist[b], h[b]);
 }
 
 // digits of the 31-bit key: bits 30..20, 19..10, 9..0
@@ -130,14 +135,14 @@ __global__ __launch_bounds__(256) void select_hist(const float *__restrict__ v, 
 
 // One block: find the bin of the `need`-th smallest key, extend the prefix, clear the histogram.
 template <int PASS>
-__global__ __launch_bounds__(1024) void select_locate(SweepState *state, uint32_t *hist) {
+__global__ __launch_bounds__(1024) void select_locate(SweepState *state, uint32_t *hist, uint32_t k) {
     constexpr int kBins = PASS == 0 ? 2048 : 1024;
     constexpr int kPer = kBins / 1024;
     constexpr int kBits = PASS == 0 ? 11 : 10;
     __shared__ uint32_t wave_tot[16];
     __shared__ uint32_t found[3];
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const uint32_t need = state->need, prefix = state->prefix;
+    const uint32_t need = PASS == 0 ? k : state->need, prefix = PASS == 0 ? 0u : state->prefix;  // pass 0 starts the search
     uint32_t mine[kPer], s = 0;
 #pragma unroll
     for (int i = 0; i < kPer; ++i) {
@@ -382,6 +387,7 @@ int sweep_run(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld_w, in
         hipLaunchKernelGGL(sweep_zero, dim3(2048), dim3(256), 0, stream, g, rows * cols);
         if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
     }
+    hipLaunchKernelGGL(select_reset, dim3(1), dim3(1024), 0, stream, hist);
     hipLaunchKernelGGL(invert_diagonal_blocks, dim3(static_cast<unsigned>(n_blocks)), dim3(256), 0, stream, r, ld_r, cols,
                        first_block, dinv_all);
     if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
@@ -402,17 +408,16 @@ int sweep_run(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld_w, in
             int st = launch_gemm_f32<kBKN>(static_cast<int>(rows), width, width, 1.f, g + c0, cols,
                                            dinv_all + (b - first_block) * (kSB * kSB), kSB, 0.f, tbuf, kSB, false, stream);
             if (st != PRUNE_OK) return st;
-            hipLaunchKernelGGL(block_saliency<T>, dim3(1024), dim3(256), 0, stream, w, ld_w, r, ld_r, dead, tbuf, rows, c0,
-                               width, sal, ld_sal);
+            const uint32_t k32 = static_cast<uint32_t>(mode == 1 ? k : 1);
+            hipLaunchKernelGGL(saliency_first_pass<T>, dim3(row_tiles), dim3(256), 0, stream, w, ld_w, r, ld_r, dead, tbuf,
+                               rows, c0, width, sal, ld_sal, hist);
+            hipLaunchKernelGGL(select_locate<0>, dim3(1), dim3(1024), 0, stream, state, hist, k32);
         }
         if (mode == 1) {
-            hipLaunchKernelGGL(select_begin, dim3(1), dim3(1024), 0, stream, state, hist, static_cast<uint32_t>(k));
-            hipLaunchKernelGGL(select_hist<0>, dim3(row_tiles), dim3(256), 0, stream, sal, ld_sal, int64_t(0), width, rows, state, hist);
-            hipLaunchKernelGGL(select_locate<0>, dim3(1), dim3(1024), 0, stream, state, hist);
             hipLaunchKernelGGL(select_hist<1>, dim3(row_tiles), dim3(256), 0, stream, sal, ld_sal, int64_t(0), width, rows, state, hist);
-            hipLaunchKernelGGL(select_locate<1>, dim3(1), dim3(1024), 0, stream, state, hist);
+            hipLaunchKernelGGL(select_locate<1>, dim3(1), dim3(1024), 0, stream, state, hist, 0u);
             hipLaunchKernelGGL(select_hist<2>, dim3(row_tiles), dim3(256), 0, stream, sal, ld_sal, int64_t(0), width, rows, state, hist);
-            hipLaunchKernelGGL(select_locate<2>, dim3(1), dim3(1024), 0, stream, state, hist);
+            hipLaunchKernelGGL(select_locate<2>, dim3(1), dim3(1024), 0, stream, state, hist, 0u);
             hipLaunchKernelGGL(tie_count, dim3(row_quads), dim3(256), 0, stream, sal, ld_sal, int64_t(0), width, rows, state, row_eq);
             hipLaunchKernelGGL(tie_scan, dim3(1), dim3(1024), 0, stream, row_eq, row_before, rows, state);
             if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
