@@ -232,6 +232,19 @@ def run_obs_stage(args):
                         "achieved": round(achieved, 1), "peak": 2500.0, "unit": "TFLOP/s",
                         "frac": round(achieved / 2500.0, 4), "traffic": None, "avg_launch_ms": round(launch_ms, 4),
                         "launches": len(gram_events)}}
+    if not args.no_cpu_baseline:
+        from oracle import obs_oracle as obs
+        name, a = st.names[0], st.proj_inputs[st.names[0]]
+        xs = acts[a][:8192].detach().cpu().to(torch.float32).numpy()
+        wsamp = weights[name][:256].detach().cpu().to(torch.float32).numpy()
+        t0 = time.perf_counter()
+        obs.obs_prune(xs, wsamp, float(s[0]))
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": wsamp.size / dt, "unit": "weights/s", "cores": len(os.sched_getaffinity(0)),
+                               "kind": "oracle",
+                               "sample": f"projection {name}: 256 of {weights[name].shape[0]} rows, 8192 of {cfg.n_tokens} "
+                                         f"calibration tokens (the Hessian and its factor cost the same for any number "
+                                         f"of rows); NumPy float64, {dt:.1f} s"}
     log(f"obs stage: {ms:.2f} ms per layer | rank+plan {seg[0]:.2f} | hessians+factors {seg[1]:.2f} | sweeps {seg[2]:.2f}")
     print(json.dumps(out), flush=True)
 
