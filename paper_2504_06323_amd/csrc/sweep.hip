@@ -16,7 +16,8 @@
 // Per block of 128 columns: (1) T = G_block inv(R_bb) on the matrix cores, saliency ((w + T) R_jj)^2; (2) the
 // floor(s * rows * width) smallest saliencies of the block are found exactly by a radix search over all rows
 // together (ties by row-major position); (3) one wave walks the 128 columns in order for four rows at a time, the
-// block of R in LDS; (4) one fp32 matrix-core product adds D_block R[block, later] to G.
+// block of R in LDS; (4) fp32 matrix-core products add D R[finished, later] to G: after every block for the rest
+// of its group of four blocks, after every group for everything beyond it.
 #include "gemm_f32.hpp"
 #include "tri_inverse.hpp"
 
@@ -25,6 +26,7 @@ namespace mp {
 namespace {
 
 constexpr int kSB = 128;  // columns per block
+constexpr int kGroup = 4; // blocks per group: columns beyond the group receive a group's changes in one product
 constexpr int kSBPitch = kSB + 1;
 constexpr int kHistBins = 2048;
 
@@ -234,6 +236,7 @@ __global__ __launch_bounds__(256) void sweep_block(const T *w, int64_t ld_w, T *
                                                    int64_t c0, int width, int mode,
                                                    const SweepState *__restrict__ state,
                                                    const uint32_t *__restrict__ row_before, float *__restrict__ dblk,
+                                                   int64_t ld_d,
                                                    uint32_t *__restrict__ mask_bits, int64_t words_per_row,
                                                    int64_t cols) {
     constexpr int NR = kRowsPerWave;
@@ -327,8 +330,8 @@ __global__ __launch_bounds__(256) void sweep_block(const T *w, int64_t ld_w, T *
             if (row >= rows) break;  // uniform
             if (valid0) store_as(w_out + row * ld_out + c0 + lane, o0[q]);
             if (valid1) store_as(w_out + row * ld_out + c0 + lane + 64, o1[q]);
-            dblk[row * kSB + lane] = d0[q];
-            dblk[row * kSB + lane + 64] = d1[q];
+            dblk[row * ld_d + lane] = d0[q];
+            dblk[row * ld_d + lane + 64] = d1[q];
             if (mask_bits && lane < 4) {  // keep-bits of the block's four words (bit set = kept); bits past cols stay 0
                 const int64_t word = c0 / 32 + lane;
                 if (word * 32 < cols) {
@@ -351,7 +354,7 @@ SweepLayout sweep_layout(int64_t rows, int64_t cols, bool own_v) {
     l.v = at;
     at += own_v ? up(static_cast<size_t>(rows) * cols * 4) : 0;
     l.d = at;
-    at += up(static_cast<size_t>(rows) * kSB * 4);
+    at += up(static_cast<size_t>(rows) * kGroup * kSB * 4);
     l.t = at;
     at += up(static_cast<size_t>(rows) * kSB * 4);
     l.sal = at;
@@ -374,7 +377,8 @@ template <typename T>
 int sweep_run(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld_w, int64_t ld_out, const float *r,
               int64_t ld_r, const uint8_t *dead, double sparsity, int64_t first_block, int64_t n_blocks, float *g,
               float *saliency, uint32_t *mask_bits, char *ws, const SweepLayout &l, hipStream_t stream) {
-    float *dblk = reinterpret_cast<float *>(ws + l.d);
+    float *dgroup = reinterpret_cast<float *>(ws + l.d);  // D of the current group of blocks, [rows, kGroup * kSB]
+    constexpr int64_t ld_d = kGroup * kSB;
     float *tbuf = reinterpret_cast<float *>(ws + l.t);
     float *dinv_all = reinterpret_cast<float *>(ws + l.dinv);
     uint32_t *hist = reinterpret_cast<uint32_t *>(ws + l.hist);
@@ -422,13 +426,27 @@ int sweep_run(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld_w, in
             hipLaunchKernelGGL(tie_scan, dim3(1), dim3(1024), 0, stream, row_eq, row_before, rows, state);
             if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
         }
+        // Blocks are taken in groups of kGroup (aligned in the matrix, so that a sweep split over several calls does
+        // the same operations): a finished block updates the rest of its group at once, and the columns beyond the
+        // group receive the whole group's changes in one product with a four times longer inner dimension, which
+        // cuts the read-modify-write traffic on G -- the bulk of the sweep's memory traffic -- by four.
+        const int slot = static_cast<int>(b % kGroup);
+        const int64_t group0 = (b - slot) * kSB;
+        const int64_t group_end = group0 + ld_d < cols ? group0 + ld_d : cols;
+        float *dblk = dgroup + slot * kSB;
         hipLaunchKernelGGL(sweep_block<T>, dim3(row_groups), dim3(256), 0, stream, w, ld_w, w_out, ld_out, r, ld_r, dead,
-                           g, cols, sal, ld_sal, rows, c0, width, mode, state, row_before, dblk, mask_bits, words, cols);
+                           g, cols, sal, ld_sal, rows, c0, width, mode, state, row_before, dblk, ld_d, mask_bits, words,
+                           cols);
         if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
         const int64_t c1 = c0 + width;
-        if (c1 < cols) {
-            const int st = launch_gemm_f32<kBKN>(static_cast<int>(rows), static_cast<int>(cols - c1), width, 1.f, dblk,
-                                                 kSB, r + c0 * ld_r + c1, ld_r, 1.f, g + c1, cols, false, stream);
+        if (c1 < group_end) {
+            const int st = launch_gemm_f32<kBKN>(static_cast<int>(rows), static_cast<int>(group_end - c1), width, 1.f, dblk,
+                                                 ld_d, r + c0 * ld_r + c1, ld_r, 1.f, g + c1, cols, false, stream);
+            if (st != PRUNE_OK) return st;
+        } else if (group_end < cols) {
+            const int st = launch_gemm_f32<kBKN>(static_cast<int>(rows), static_cast<int>(cols - group_end),
+                                                 static_cast<int>(group_end - group0), 1.f, dgroup, ld_d,
+                                                 r + group0 * ld_r + group_end, ld_r, 1.f, g + group_end, cols, false, stream);
             if (st != PRUNE_OK) return st;
         }
     }
