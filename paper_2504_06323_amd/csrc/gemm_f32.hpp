@@ -39,32 +39,23 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, floa
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    for (int k0 = 0; k0 < K; k0 += kTileK) {
-        // A tile: rows m0 .. m0 + 127, four consecutive k per thread and pass
+    // The next 32-deep slice of both operands is fetched into registers while the matrix cores work on the
+    // current one, and parked in LDS afterwards.
+    f32x4 ra[4], rbv[4];
+    auto fetch = [&](int k0) {
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const int r = (tid >> 3) + 32 * p, kk = (tid & 7) * 4;
-            f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (m0 + r < M && k0 + kk < K) v = *reinterpret_cast<const f32x4 *>(A + (m0 + r) * lda + k0 + kk);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) sa[kk + e][r] = v[e];
-        }
-        if (BL == kBNK) {
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const int r = (tid >> 3) + 32 * p, kk = (tid & 7) * 4;
-                f32x4 v = {0.f, 0.f, 0.f, 0.f};
-                if (n0 + r < N && k0 + kk < K) v = *reinterpret_cast<const f32x4 *>(B + (n0 + r) * ldb + k0 + kk);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) sb[kk + e][r] = v[e];
-            }
-        } else {
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                const int kk = (tid >> 5) + 8 * p, c = (tid & 31) * 4;
-                f32x4 v = {0.f, 0.f, 0.f, 0.f};
-                if (k0 + kk < K) {
-                    const float *src = B + (k0 + kk) * ldb + n0 + c;
+            const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+            ra[p] = (m0 + r < M && k0 + kk < K) ? *reinterpret_cast<const f32x4 *>(A + (m0 + r) * lda + k0 + kk) : zero;
+            if (BL == kBNK) {
+                rbv[p] = (n0 + r < N && k0 + kk < K) ? *reinterpret_cast<const f32x4 *>(B + (n0 + r) * ldb + k0 + kk)
+                                                     : zero;
+            } else {
+                const int kb = (tid >> 5) + 8 * p, c = (tid & 31) * 4;
+                f32x4 v = zero;
+                if (k0 + kb < K) {
+                    const float *src = B + (k0 + kb) * ldb + n0 + c;
                     if (n0 + c + 4 <= N) {
                         v = *reinterpret_cast<const f32x4 *>(src);
                     } else {
@@ -73,10 +64,31 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, floa
                             if (n0 + c + e < N) v[e] = src[e];
                     }
                 }
-                *reinterpret_cast<f32x4 *>(&sb[kk][c]) = v;
+                rbv[p] = v;
             }
         }
-        __syncthreads();
+    };
+    auto park = [&]() {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            const int r = (tid >> 3) + 32 * p, kk = (tid & 7) * 4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) sa[kk + e][r] = ra[p][e];
+            if (BL == kBNK) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) sb[kk + e][r] = rbv[p][e];
+            } else {
+                const int kb = (tid >> 5) + 8 * p, c = (tid & 31) * 4;
+                *reinterpret_cast<f32x4 *>(&sb[kb][c]) = rbv[p];
+            }
+        }
+    };
+    fetch(0);
+    park();
+    __syncthreads();
+    for (int k0 = 0; k0 < K; k0 += kTileK) {
+        const bool more = k0 + kTileK < K;
+        if (more) fetch(k0 + kTileK);
 #pragma unroll
         for (int kk = 0; kk < kTileK; kk += 2) {
             const int k = kk + (lane >> 5), c = lane & 31;
@@ -92,6 +104,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, floa
                 for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
         }
         __syncthreads();
+        if (more) {
+            park();
+            __syncthreads();
+        }
     }
     // Accumulator element v of lane l: row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32 of its 32 x 32 tile.
     // When C allows 16-byte accesses, a wave passes its tile through LDS eight rows at a time (the operand
