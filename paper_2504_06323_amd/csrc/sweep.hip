@@ -223,12 +223,11 @@ __device__ __forceinline__ float lane_value(float x, int lane) {
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), lane));
 }
 
-// A wave walks the columns of the block in order for kRowsPerWave rows at once (the rows are independent chains
-// of dependent operations, so they hide each other's latency).  mode: 0 nothing is pruned, 1 by the searched
+// A wave walks the columns of the block in order for NR rows at once (the rows are independent chains of
+// dependent operations, so they hide each other's latency; fewer rows per wave when there are few rows, so that
+// every SIMD still gets two waves).  mode: 0 nothing is pruned, 1 by the searched
 // threshold, 2 everything.  Lane l owns columns l and l + 64 of the block.
-constexpr int kRowsPerWave = 4;
-
-template <typename T>
+template <typename T, int NR>
 __global__ __launch_bounds__(256) void sweep_block(const T *w, int64_t ld_w, T *w_out, int64_t ld_out,
                                                    const float *__restrict__ r, int64_t ld_r,
                                                    const uint8_t *__restrict__ dead, const float *__restrict__ g, int64_t ldg,
@@ -239,7 +238,6 @@ __global__ __launch_bounds__(256) void sweep_block(const T *w, int64_t ld_w, T *
                                                    int64_t ld_d,
                                                    uint32_t *__restrict__ mask_bits, int64_t words_per_row,
                                                    int64_t cols) {
-    constexpr int NR = kRowsPerWave;
     __shared__ float rb[kSB][kSBPitch];
     __shared__ float rinv[kSB];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -397,7 +395,8 @@ int sweep_run(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld_w, in
     if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
     const unsigned row_tiles = static_cast<unsigned>(ceil_div(rows, 16));
     const unsigned row_quads = static_cast<unsigned>(ceil_div(rows, 4) < 512 ? ceil_div(rows, 4) : 512);
-    const unsigned row_groups = static_cast<unsigned>(ceil_div(rows, 4 * kRowsPerWave) < 1024 ? ceil_div(rows, 4 * kRowsPerWave) : 1024);
+    const int rows_per_wave = rows <= 8192 ? 2 : 4;
+    const unsigned row_groups = static_cast<unsigned>(ceil_div(rows, 4 * rows_per_wave) < 1024 ? ceil_div(rows, 4 * rows_per_wave) : 1024);
     for (int64_t b = first_block; b < first_block + n_blocks; ++b) {
         const int64_t c0 = b * kSB;
         const int width = static_cast<int>(cols - c0 < kSB ? cols - c0 : kSB);
@@ -434,9 +433,14 @@ int sweep_run(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld_w, in
         const int64_t group0 = (b - slot) * kSB;
         const int64_t group_end = group0 + ld_d < cols ? group0 + ld_d : cols;
         float *dblk = dgroup + slot * kSB;
-        hipLaunchKernelGGL(sweep_block<T>, dim3(row_groups), dim3(256), 0, stream, w, ld_w, w_out, ld_out, r, ld_r, dead,
-                           g, cols, sal, ld_sal, rows, c0, width, mode, state, row_before, dblk, ld_d, mask_bits, words,
-                           cols);
+        if (rows_per_wave == 2)
+            hipLaunchKernelGGL((sweep_block<T, 2>), dim3(row_groups), dim3(256), 0, stream, w, ld_w, w_out, ld_out, r, ld_r,
+                               dead, g, cols, sal, ld_sal, rows, c0, width, mode, state, row_before, dblk, ld_d, mask_bits,
+                               words, cols);
+        else
+            hipLaunchKernelGGL((sweep_block<T, 4>), dim3(row_groups), dim3(256), 0, stream, w, ld_w, w_out, ld_out, r, ld_r,
+                               dead, g, cols, sal, ld_sal, rows, c0, width, mode, state, row_before, dblk, ld_d, mask_bits,
+                               words, cols);
         if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
         const int64_t c1 = c0 + width;
         if (c1 < group_end) {
