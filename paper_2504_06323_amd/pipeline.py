@@ -193,8 +193,11 @@ def hessian_layer(ob: ObsState, acts: Dict[str, torch.Tensor], damp: float = 0.0
     """H = X^T X for every distinct projection input (one after the other: each fills the chip), each followed by
     damping and factorisation in place on a stream of its own."""
     main = torch.cuda.current_stream()
-    for i, (a, x) in enumerate(acts.items()):
-        side = ob.streams[i % len(ob.streams)]
+    order = sorted(range(len(acts)), key=lambda i: -list(acts.values())[i].shape[1])   # widest first: its
+    names = list(acts)                                   # factorisation is the longest and overlaps the other Hessians
+    for slot, i in enumerate(order):
+        a, x = names[i], acts[names[i]]
+        side = ob.streams[slot % len(ob.streams)]
         ob.hessian[a].zero_()
         timed = on_big is not None and a == big        # a benchmark's event pair around one accumulation
         if timed:
@@ -208,7 +211,7 @@ def hessian_layer(ob: ObsState, acts: Dict[str, torch.Tensor], damp: float = 0.0
         ready.record(main)
         side.wait_event(ready)
         prune.hessian_factor(ob.hessian[a], damp, dead=ob.dead[a], info=ob.info[i:i + 1],
-                             ws=ob.ws[i % len(ob.streams)] if i % len(ob.streams) else ob.factor_ws, stream=side)
+                             ws=ob.ws[slot % len(ob.streams)] if slot % len(ob.streams) else ob.factor_ws, stream=side)
         done = torch.cuda.Event()
         done.record(side)
         ob.factored[a] = done
