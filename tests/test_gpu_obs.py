@@ -441,3 +441,24 @@ def test_obs_other_model_widths(lib, channels):
     e_obs = np.sum(((w0 - got_w) @ r64) ** 2)
     e_plain = np.sum((np.where(pruned, w0, 0.0) @ r64) ** 2)
     assert e_obs < e_plain
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_sweep_in_place_with_pitch(lib, dtype):
+    """Weights that are a view into a wider buffer, pruned in place: the same bits as the contiguous out-of-place
+    call, and nothing outside the view is touched."""
+    rows, cols, tokens, sparsity = 70, 264, 1200, 0.4
+    x = _acts(tokens, cols, torch.bfloat16, seed=21)
+    w = synth.random_matrix(rows, cols, dtype, seed=22, device=DEV, scale=0.05)
+    h = torch.zeros((cols, cols), dtype=torch.float32, device=DEV)
+    prune.hessian_accumulate(x, h)
+    prune.hessian_factor(h, 0.01)
+    want = torch.empty_like(w)
+    prune.obs_sweep(w, h, sparsity, w_out=want)
+    wide = torch.full((rows, cols + 24), 3.0, dtype=dtype, device=DEV)
+    view = wide[:, 8:8 + cols]
+    view.copy_(w)
+    prune.obs_sweep(view, h, sparsity)                       # in place, pitch cols + 24
+    _sync()
+    assert torch.equal(view, want)
+    assert bool((wide[:, :8] == 3.0).all()) and bool((wide[:, 8 + cols:] == 3.0).all())
