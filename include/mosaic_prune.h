@@ -352,6 +352,35 @@ int prune_obs_sweep(const void *w, void *w_out, int dtype, int64_t rows, int64_t
                     int64_t n_blocks, float *v, float *saliency, uint32_t *mask_bits, void *ws, size_t ws_bytes,
                     void *stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * Forward pass of the feed-forward block (LLaMA-style layers of Table 2, Section 4.1.1):
+ *   h = silu(x gate^T) * (x up^T),   y = h down^T.
+ * The down projection's input h, whose per-channel norms enter its weight metric (Eq. 5), thereby comes from
+ * a real forward pass, and the block can be run at full and at structurally pruned size (Section 4.1.3,
+ * categories 2 and 3).
+ * ------------------------------------------------------------------------------------------------ */
+
+/*
+ * y[t, j] = sum_k x[t, k] * w[j, k]: a bias-free projection with weights [n, k].
+ * x [tokens, k] pitch ld_x, w [n, k] pitch ld_w, y [tokens, n] pitch ld_y, all DEVICE and of dtype; fp32
+ * accumulation, the result rounded once to dtype.  bf16 data with k a multiple of 32, pitches multiples of 8 and
+ * 16-byte aligned x and w runs on the matrix cores; anything else on a plain kernel with the same semantics.
+ */
+int prune_linear(const void *x, const void *w, void *y, int dtype, int64_t tokens, int64_t n, int64_t k, int64_t ld_x,
+                 int64_t ld_w, int64_t ld_y, void *stream);
+
+/*
+ * h[t, c] = silu(sum_k x[t, k] gate[c, k]) * (sum_k x[t, k] up[c, k]),  silu(a) = a / (1 + exp(-a)),
+ * rounded once to dtype; gate, up [inter, hidden] with the same pitch ld_w.
+ * sumsq (DEVICE fp32 [inter], nullable, in/out): sumsq[c] += sum_t h[t, c]^2 over the stored (rounded) values --
+ * the statistic prune_stats_accumulate would give on h, produced where h is produced; fixed summation order.
+ * ws: needed only with sumsq on the matrix-core path, ws_bytes >= prune_mlp_workspace_bytes(tokens, inter).
+ */
+size_t prune_mlp_workspace_bytes(int64_t tokens, int64_t inter);
+int prune_mlp_gate_up(const void *x, const void *gate, const void *up, void *h, int dtype, int64_t tokens,
+                      int64_t hidden, int64_t inter, int64_t ld_x, int64_t ld_w, int64_t ld_h, float *sumsq, void *ws,
+                      size_t ws_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -16,16 +16,11 @@
 // and are added up in a fixed order (so the result is reproducible bit for bit),
 // mirrored below the diagonal.  Any other element type, width or alignment takes
 // a plain tiled FMA kernel.
-#include "common.hpp"
+#include "mfma_bf16.hpp"
 
 namespace mp {
 
 namespace {
-
-typedef __attribute__((ext_vector_type(4))) short s16x4;
-typedef __attribute__((ext_vector_type(8))) short s16x8;
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kTile = 256;        // output tile edge (channels)
 constexpr int kStep = 32;         // tokens per LDS stage
@@ -89,17 +84,6 @@ __device__ __forceinline__ bf16x8 operand_from_ring(const unsigned char *slab, i
     const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     return __builtin_bit_cast(bf16x8, both);
 }
-
-// One global -> LDS load of 16 bytes per lane: lane l's packet lands at lds_addr + 16 l (lds_addr uniform, in M0).
-// Written as an instruction rather than through the builtin on purpose: the compiler would otherwise guard every
-// later LDS read with a wait for all such loads in flight (it cannot tell the ring's stages apart), which undoes
-// the prefetch; the waits are placed by hand below.
-__device__ __forceinline__ void load_to_lds(const void *src, uint32_t lds_addr) {
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(src) : "memory");
-}
-
-// s_waitcnt with only the vector-memory counter set (6 bits: [3:0] and [15:14]); the others left at "no wait"
-#define MP_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt((((n) & 15) | (((n) >> 4) << 14)) | 0x0F70)
 
 __global__ __launch_bounds__(kGramBlock, 1) void gram_tiles_bf16(const bf16_t *__restrict__ x, int64_t n_tokens,
                                                                      int channels, int64_t ld, int n_tiles, int n_pairs,

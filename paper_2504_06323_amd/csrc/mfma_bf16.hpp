@@ -1,0 +1,31 @@
+// Pieces shared by the bf16 matrix-core kernels: operand vector types, the global -> LDS load and the explicit
+// wait that goes with it.
+#pragma once
+
+#include "common.hpp"
+
+namespace mp {
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+// One global -> LDS load of 16 bytes per lane: lane l's packet lands at lds_addr + 16 l (lds_addr uniform, in M0).
+// Written as an instruction rather than through the builtin on purpose: the compiler would otherwise guard every
+// later LDS read with a wait for all such loads in flight (it cannot tell the ring's stages apart), which undoes
+// the prefetch; the waits are placed by hand below.
+__device__ __forceinline__ void load_to_lds(const void *src, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(src) : "memory");
+}
+
+// s_waitcnt with only the vector-memory counter set (6 bits: [3:0] and [15:14]); the others left at "no wait"
+#define MP_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt((((n) & 15) | (((n) >> 4) << 14)) | 0x0F70)
+
+__device__ __forceinline__ bf16_t narrow_to_bf16(float f) {  // round to nearest, ties to even
+    const uint32_t b = __float_as_uint(f);
+    if ((b & 0x7fffffffu) > 0x7f800000u) return static_cast<bf16_t>(0x7fc0u);
+    return static_cast<bf16_t>((b + 0x7fffu + ((b >> 16) & 1u)) >> 16);
+}
+
+}  // namespace mp

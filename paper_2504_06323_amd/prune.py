@@ -48,6 +48,9 @@ _SIGNATURES = {
     "prune_obs_sweep_workspace_bytes": (_sz, [_i64, _i64, _int]),
     "prune_obs_sweep": (_int, [_vp, _vp, _int, _i64, _i64, _i64, _i64, _vp, _i64, _vp, _f64, _i64, _i64, _vp, _vp, _vp,
                                _vp, _sz, _vp]),
+    "prune_linear": (_int, [_vp, _vp, _vp, _int, _i64, _i64, _i64, _i64, _i64, _i64, _vp]),
+    "prune_mlp_workspace_bytes": (_sz, [_i64, _i64]),
+    "prune_mlp_gate_up": (_int, [_vp, _vp, _vp, _vp, _int, _i64, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "prune_plan_sparsity_device": (_int, [_vp, _vp, _vp, _int, _int, _f64, _f64, _int, _vp, _vp, _vp, _vp]),
     "prune_struct_groups_workspace_bytes": (_sz, [_vp, _vp, _int, _vp, _vp, _int, _i64]),
     "prune_struct_groups": (_int, [_vp, _vp, _vp, _int, _vp, _vp, _vp, _int, _int, _i64, _u32, _vp, _vp, _vp, _vp,
@@ -417,6 +420,42 @@ def obs_sweep(w: torch.Tensor, r: torch.Tensor, sparsity: float, w_out: Optional
                                                                          rows * ((cols + 31) // 32)),
                                   ws.data_ptr(), ws.numel(), _stream(stream)))
     return ws
+
+
+def linear(x: torch.Tensor, w: torch.Tensor, y: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """y = x w^T for weights [n, k] (prune_linear)."""
+    xp, tokens, k, ld_x = _matrix(x, "x")
+    wp, n, kw, ld_w = _matrix(w, "w")
+    if kw != k or w.dtype != x.dtype:
+        raise ValueError("w must be [n, k] of x's dtype")
+    if y is None:
+        y = torch.empty((tokens, n), dtype=x.dtype, device=x.device)
+    yp, yt, yn, ld_y = _matrix(y, "y")
+    if (yt, yn) != (tokens, n) or y.dtype != x.dtype:
+        raise ValueError("y must be [tokens, n] of x's dtype")
+    _check("prune_linear", load().prune_linear(xp, wp, yp, _dtype_code(x), tokens, n, k, ld_x, ld_w, ld_y, _stream(stream)))
+    return y
+
+
+def mlp_gate_up(x: torch.Tensor, gate: torch.Tensor, up: torch.Tensor, h: Optional[torch.Tensor] = None,
+                sumsq: Optional[torch.Tensor] = None, ws: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """h = silu(x gate^T) * (x up^T), optionally sumsq += column sums of squares of h (prune_mlp_gate_up)."""
+    xp, tokens, hidden, ld_x = _matrix(x, "x")
+    gp, inter, kg, ld_w = _matrix(gate, "gate")
+    up_p, iu, ku, ld_u = _matrix(up, "up")
+    if (kg, ku, iu) != (hidden, hidden, inter) or ld_u != ld_w or gate.dtype != x.dtype or up.dtype != x.dtype:
+        raise ValueError("gate and up must be [inter, hidden] of x's dtype with the same pitch")
+    if h is None:
+        h = torch.empty((tokens, inter), dtype=x.dtype, device=x.device)
+    hp, ht, hn, ld_h = _matrix(h, "h")
+    if (ht, hn) != (tokens, inter) or h.dtype != x.dtype:
+        raise ValueError("h must be [tokens, inter] of x's dtype")
+    need = int(load().prune_mlp_workspace_bytes(tokens, inter)) if sumsq is not None else 0
+    ws_ptr, ws_bytes, keep = _workspace(ws, need, x.device)
+    _check("prune_mlp_gate_up",
+           load().prune_mlp_gate_up(xp, gp, up_p, hp, _dtype_code(x), tokens, hidden, inter, ld_x, ld_w, ld_h,
+                                    _vector(sumsq, "sumsq", torch.float32, inter), ws_ptr, ws_bytes, _stream(stream)))
+    return h
 
 
 def struct_compact(gate: torch.Tensor, up: torch.Tensor, down: torch.Tensor, r: int, group_mag: torch.Tensor,

@@ -1,0 +1,124 @@
+"""GPU parity of the feed-forward forward pass (prune_linear, prune_mlp_gate_up) against oracle/mlp_oracle.py."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import mlp_oracle as mlp
+from oracle import mosaic_oracle as orc
+from paper_2504_06323_amd import prune, synth
+from util import to_np
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _sync():
+    torch.cuda.synchronize()
+
+
+def _mat(rows, cols, dtype, seed, scale):
+    return synth.random_matrix(rows, cols, dtype, seed=seed, device=DEV, scale=scale)
+
+
+def _close(got, want, dtype, terms_abs):
+    """Output rounded once to dtype (half an ulp: 2^-9 bf16, 2^-24 fp32) on top of fp32 accumulation of the exact
+    products (a few 1e-6 of the sum of |terms|)."""
+    ulp = 2.0 ** -8 if dtype == torch.bfloat16 else 2.0 ** -23
+    bound = ulp * np.abs(want) + 4e-6 * terms_abs + 1e-30
+    return float(np.max(np.abs(got - want) / bound))
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("shape", [(300, 520, 256), (1000, 256, 4096), (257, 129, 96), (64, 64, 100), (5, 7, 8)])
+def test_linear_vs_oracle(lib, dtype, shape):
+    tokens, n, k = shape
+    x, w = _mat(tokens, k, dtype, 1 + k, 1.0), _mat(n, k, dtype, 2 + n, 0.05)
+    y = prune.linear(x, w)
+    _sync()
+    x64, w64 = to_np(x).astype(np.float64), to_np(w).astype(np.float64)
+    want = mlp.linear(x64, w64)
+    assert _close(to_np(y).astype(np.float64), want, dtype, np.abs(x64) @ np.abs(w64).T) < 1.0
+    y2 = prune.linear(x, w)
+    _sync()
+    assert torch.equal(y, y2)
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("shape", [(512, 256, 688), (300, 256, 200), (1000, 4096, 384), (33, 40, 50)])
+def test_gate_up_vs_oracle_and_fused_statistic(lib, dtype, shape):
+    tokens, hidden, inter = shape
+    x = _mat(tokens, hidden, dtype, 3, 1.0)
+    gate, up = _mat(inter, hidden, dtype, 4, 0.05), _mat(inter, hidden, dtype, 5, 0.05)
+    sumsq = torch.full((inter,), 2.0, dtype=torch.float32, device=DEV)          # accumulates on top of what is there
+    h = prune.mlp_gate_up(x, gate, up, sumsq=sumsq)
+    _sync()
+    x64, g64, u64 = (to_np(t).astype(np.float64) for t in (x, gate, up))
+    a, b = mlp.linear(x64, g64), mlp.linear(x64, u64)
+    want = mlp.silu(a) * b
+    got = to_np(h).astype(np.float64)
+    # silu in fp32 with the hardware exponential (a few ulp), both products accumulated in fp32, one rounding to dtype
+    ulp = 2.0 ** -8 if dtype == torch.bfloat16 else 2.0 ** -22
+    terms = (np.abs(x64) @ np.abs(g64).T) * np.abs(b) + np.abs(mlp.silu(a)) * (np.abs(x64) @ np.abs(u64).T)
+    assert np.max(np.abs(got - want) / (ulp * np.abs(want) + 8e-6 * terms + 1e-30)) < 1.0
+    # the fused statistic is the column sum of squares of the stored h: against the oracle on the kernel's own h,
+    # and against the statistics kernel of the metric path
+    want_sq = 2.0 + orc.column_sumsq(got)
+    assert np.max(np.abs(to_np(sumsq) - want_sq) / want_sq) < 1e-5
+    other = torch.full((inter,), 2.0, dtype=torch.float32, device=DEV)
+    prune.stats_accumulate(h, other)
+    _sync()
+    assert np.max(np.abs(to_np(sumsq) / to_np(other) - 1.0)) < 1e-5
+    h2 = prune.mlp_gate_up(x, gate, up)                                         # without the statistic: same h
+    _sync()
+    assert torch.equal(h, h2)
+
+
+def test_compacted_block_is_the_full_block_without_the_removed_channels(lib):
+    """The structured pass removes coupled channels (gate / up rows, down columns); the smaller block must give the
+    output of the full block with those channels' hidden activations dropped (Fig. 4), here on the GPU end to end."""
+    tokens, hidden, inter, r = 384, 256, 704, 200
+    x = _mat(tokens, hidden, torch.bfloat16, 6, 1.0)
+    gate, up, down = (_mat(inter, hidden, torch.bfloat16, 7, 0.05), _mat(inter, hidden, torch.bfloat16, 8, 0.05),
+                      _mat(hidden, inter, torch.bfloat16, 9, 0.05))
+    g = torch.empty(inter, dtype=torch.float32, device=DEV)
+    kept = torch.empty(inter - r, dtype=torch.int32, device=DEV)
+    outs = [torch.empty((inter - r, hidden), dtype=torch.bfloat16, device=DEV) for _ in range(2)] + \
+           [torch.empty((hidden, inter - r), dtype=torch.bfloat16, device=DEV)]
+    prune.struct_compact(gate, up, down, r, g, kept, *outs)
+    small = prune.linear(prune.mlp_gate_up(x, outs[0], outs[1]), outs[2])        # K = 504 is not a multiple of 32: plain kernel
+    h = prune.mlp_gate_up(x, gate, up)
+    _sync()
+    hz = torch.zeros_like(h)
+    idx = kept.long()
+    hz[:, idx] = h[:, idx]
+    full = prune.linear(hz, down)
+    _sync()
+    want = mlp.linear(to_np(hz).astype(np.float64), to_np(down).astype(np.float64))
+    for got in (small, full):
+        assert np.max(np.abs(to_np(got).astype(np.float64) - want)) <= 2.0 ** -7 * np.max(np.abs(want))
+    assert torch.equal(prune.mlp_gate_up(x, outs[0], outs[1]), h[:, idx].contiguous())
+
+
+def test_mlp_fullsize_sampled(lib):
+    """The feed-forward block of the LLaMA-7B-shaped layer on 16384 tokens: sampled rows against the oracle, the
+    fused statistic against the statistics kernel."""
+    cfg = synth.CONFIGS["llama7b_layer"]
+    tokens = 16384
+    x = synth.make_activation(cfg, 0, "mlp_in", DEV, n_seqs=8)[:tokens]
+    gate, up, down = (synth.make_weight(cfg, 0, n, DEV) for n in ("gate", "up", "down"))
+    sumsq = torch.zeros(cfg.inter, dtype=torch.float32, device=DEV)
+    h = prune.mlp_gate_up(x, gate, up, sumsq=sumsq)
+    y = prune.linear(h, down)
+    other = torch.zeros(cfg.inter, dtype=torch.float32, device=DEV)
+    prune.stats_accumulate(h, other)
+    _sync()
+    assert np.max(np.abs(to_np(sumsq) / np.maximum(to_np(other), 1e-30) - 1.0)) < 1e-5
+    rows = np.unique(np.concatenate([np.random.default_rng(0).choice(tokens, 24, replace=False), [0, 255, 256, tokens - 1]]))
+    xs = to_np(x[torch.as_tensor(rows, device=DEV)]).astype(np.float64)
+    g64, u64, d64 = (to_np(t).astype(np.float64) for t in (gate, up, down))
+    want_h = mlp.mlp_hidden(xs, g64, u64)
+    got_h = to_np(h[torch.as_tensor(rows, device=DEV)]).astype(np.float64)
+    assert np.max(np.abs(got_h - want_h)) <= 2.0 ** -7 * np.max(np.abs(want_h))
+    want_y = mlp.linear(got_h, d64)                                              # the second product on the stored h
+    got_y = to_np(y[torch.as_tensor(rows, device=DEV)]).astype(np.float64)
+    assert np.max(np.abs(got_y - want_y)) <= 2.0 ** -7 * np.max(np.abs(want_y))

@@ -163,6 +163,19 @@ def test_error_paths_return_before_any_launch(lib):
     assert ok(wsb=64) == E["ws"]
     assert lib.prune_obs_sweep_workspace_bytes(4096, 4096, 1) >= 4096 * 4096 * 4 + 4096 * 128 * 4
     assert lib.prune_obs_sweep_workspace_bytes(4096, 4096, 0) < 4096 * 4096 * 4
+    ln = lib.prune_linear
+    assert ln(fake, fake, fake, 9, 8, 8, 8, 8, 8, 8, None) == E["dtype"]
+    assert ln(fake, fake, fake, 1, 0, 8, 8, 8, 8, 8, None) == E["shape"]
+    assert ln(fake, fake, fake, 1, 8, 8, 8, 4, 8, 8, None) == E["shape"]              # ld_x < k
+    assert ln(fake, fake, fake, 1, 8, 16, 8, 8, 8, 8, None) == E["shape"]             # ld_y < n
+    assert ln(None, fake, fake, 1, 8, 8, 8, 8, 8, 8, None) == E["null"]
+    assert ln(odd, fake, fake, 1, 8, 8, 8, 8, 8, 8, None) == E["align"]
+    gu = lib.prune_mlp_gate_up
+    assert gu(fake, fake, None, fake, 1, 8, 8, 8, 8, 8, 8, None, None, 0, None) == E["null"]
+    assert gu(fake, fake, fake, fake, 1, 8, 8, 8, 8, 8, 4, None, None, 0, None) == E["shape"]   # ld_h < inter
+    assert gu(fake, fake, fake, fake, 1, 256, 32, 128, 32, 32, 128, fake, None, 0, None) == E["null"]   # statistic wanted, no workspace
+    assert gu(fake, fake, fake, fake, 1, 256, 32, 128, 32, 32, 128, fake, fake, 16, None) == E["ws"]
+    assert lib.prune_mlp_workspace_bytes(16384, 11008) >= 2 * 64 * 11008 * 4
     st = lib.prune_struct_compact
     assert st(fake, fake, fake, 1, 8, 8, 8, fake, fake, None, None, None, fake, 1 << 20, None) == E["rng"]  # r >= inter
     assert st(fake, fake, fake, 1, 8, 8, 1, fake, fake, fake, None, None, fake, 1 << 20, None) == E["null"]  # 1 of 3 outs
