@@ -249,12 +249,117 @@ def run_obs_stage(args):
     print(json.dumps(out), flush=True)
 
 
+def run_mlp_stage(args):
+    """--stage mlp: forward pass of the layer's feed-forward block on calibration tokens, at full size and after
+    the composite pruning of the headline path has removed MLP channels; the first product also accumulates the
+    statistic of the down projection's input.  Prints its own JSON line."""
+    import numpy as np
+    import torch
+    from paper_2504_06323_amd import pipeline, prune, synth
+
+    prune.load()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.workload]
+    shapes = synth.projection_shapes(cfg)
+    act_shapes = synth.activation_shapes(cfg)
+    weights = {n: synth.make_weight(cfg, 0, n, dev) for n, _, _, _ in shapes}
+    n_seqs = min(cfg.n_seqs, 32)
+    acts = {a: synth.make_activation(cfg, 0, a, dev, n_seqs=n_seqs) for a in act_shapes}
+    tokens = n_seqs * cfg.seq_len
+    st = pipeline.LayerState.create(weights, {n: a for n, _, _, a in shapes}, act_shapes, tokens)
+    # the pruned block: rank, plan, mask, remove channels (the headline path), then pad the kept channels to a
+    # multiple of 32 with zero rows / columns (they contribute silu(0) * 0 = 0)
+    r = int(cfg.struct_frac * cfg.inter)
+    pipeline.rank_layer(st, acts, cfg.alpha)
+    _, ks, _ = pipeline.plan(st.count.tolist(), [rw * c for _, rw, c, _ in shapes], [c for _, _, c, _ in shapes], 1,
+                             len(shapes), cfg.p, cfg.lam)
+    pipeline.prune_layer(st, ks)
+    res = pipeline.alloc_struct(st, r)
+    pipeline.struct_layer(st, r, res)
+    kept = cfg.inter - r
+    padded = (kept + 31) // 32 * 32
+    small = {"gate": torch.zeros((padded, cfg.hidden), dtype=res.gate.dtype, device=dev),
+             "up": torch.zeros((padded, cfg.hidden), dtype=res.gate.dtype, device=dev),
+             "down": torch.zeros((cfg.hidden, padded), dtype=res.gate.dtype, device=dev)}
+    small["gate"][:kept] = res.gate
+    small["up"][:kept] = res.up
+    small["down"][:, :kept] = res.down
+    full = {n: st.pruned[n] for n in ("gate", "up", "down")}
+    x = acts["mlp_in"]
+    bufs = {}
+    for tag, ws_ in (("full", full), ("pruned", small)):
+        inter = ws_["gate"].shape[0]
+        bufs[tag] = (torch.empty((tokens, inter), dtype=x.dtype, device=dev),
+                     torch.empty((tokens, cfg.hidden), dtype=x.dtype, device=dev),
+                     torch.zeros(inter, dtype=torch.float32, device=dev),
+                     torch.empty(int(prune.load().prune_mlp_workspace_bytes(tokens, inter)), dtype=torch.uint8, device=dev))
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    events = {"full": [], "pruned": [], "gate_up": []}
+
+    def block(tag, ws_, record):
+        h, y, sq, wsb = bufs[tag]
+        e0, e1, e2 = ev(), ev(), ev()
+        e0.record()
+        prune.mlp_gate_up(x, ws_["gate"], ws_["up"], h=h, sumsq=sq, ws=wsb)
+        e1.record()
+        prune.linear(h, ws_["down"], y=y)
+        e2.record()
+        if record:
+            events[tag].append((e0, e2))
+            if tag == "full":
+                events["gate_up"].append((e0, e1))
+
+    for _ in range(args.warmup):
+        block("full", full, False)
+        block("pruned", small, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        block("full", full, True)
+        block("pruned", small, True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    mean = lambda k: sum(a.elapsed_time(b) for a, b in events[k]) / len(events[k])
+    ms_full, ms_small, ms_gu = mean("full"), mean("pruned"), mean("gate_up")
+    flops_gu = 4.0 * tokens * cfg.hidden * cfg.inter
+    achieved = flops_gu / (ms_gu * 1e-3) / 1e12
+    out = {"metric": "feed-forward block forward pass on calibration tokens, full and after composite pruning (tokens/s)",
+           "value": tokens / (ms_full * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": round(1e3 * elapsed / args.steps, 3), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"{cfg.name}: feed-forward block, hidden {cfg.hidden}, intermediate {cfg.inter} -> {kept} "
+                                  f"kept channels (padded to {padded}), {tokens} tokens, bf16, fp32 accumulation; a step "
+                                  f"runs the full and the pruned block once each"},
+           "ms_full_block": round(ms_full, 3), "ms_pruned_block": round(ms_small, 3),
+           "speedup_from_removed_channels": round(ms_full / ms_small, 3),
+           "tflops_full_block": round(6.0 * tokens * cfg.hidden * cfg.inter / (ms_full * 1e-3) / 1e12, 1),
+           "roofline": {"bound": "mfma", "kernel": f"linear_tiles_bf16<gate / up pair> on [{tokens}, {cfg.hidden}] x 2 x [{cfg.inter}, {cfg.hidden}]",
+                        "achieved": round(achieved, 1), "peak": 2500.0, "unit": "TFLOP/s",
+                        "frac": round(achieved / 2500.0, 4), "traffic": None, "avg_launch_ms": round(ms_gu, 4),
+                        "launches": len(events["gate_up"])}}
+    if not args.no_cpu_baseline:
+        from oracle import mlp_oracle as mlp
+        rows = 512
+        xs = x[:rows].detach().cpu().to(torch.float32).numpy()
+        ws64 = {n: full[n].detach().cpu().to(torch.float32).numpy() for n in full}
+        t0 = time.perf_counter()
+        mlp.mlp_forward(xs, ws64["gate"], ws64["up"], ws64["down"])
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": rows / dt, "unit": "tokens/s", "cores": len(os.sched_getaffinity(0)),
+                               "kind": "oracle", "sample": f"{rows} tokens through the full block, NumPy float64, {dt:.1f} s"}
+    log(f"mlp stage: full block {ms_full:.3f} ms, pruned block {ms_small:.3f} ms (x{ms_full / ms_small:.2f}); "
+        f"gate/up pair {ms_gu:.3f} ms = {achieved:.0f} TFLOP/s")
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--stage", default="prune", choices=["prune", "hessian", "obs"],
+    ap.add_argument("--stage", default="prune", choices=["prune", "hessian", "obs", "mlp"],
                     help="prune (default): the scoring / masking / structured path the headline metric is quoted on; "
                          "hessian: the matrix-core stage of the Hessian-based pruner, its own JSON line; "
-                         "obs: the whole Hessian-based path of one layer, its own JSON line")
+                         "obs: the whole Hessian-based path of one layer, its own JSON line; "
+                         "mlp: forward pass of the feed-forward block, full and pruned, its own JSON line")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
@@ -277,6 +382,9 @@ def main():
         return
     if args.stage == "obs":
         run_obs_stage(args)
+        return
+    if args.stage == "mlp":
+        run_mlp_stage(args)
         return
 
     import torch
