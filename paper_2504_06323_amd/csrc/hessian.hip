@@ -30,7 +30,7 @@ constexpr int kMaxSplits = 64;
 // Tile pairs (mt, nt), mt <= nt, are numbered patch by patch: a patch is 4 tile rows by 8 tile columns of the
 // upper triangle (32 pairs that need only 12 of the 256-channel slabs of X), patches are walked row band by
 // row band.  Pairs that are neighbours in this order share slabs.
-constexpr int kPatchRows = 4, kPatchCols = 8, kChunk = 32, kXcds = 8;
+constexpr int kPatchRows = 4, kPatchCols = 8;
 
 __device__ __forceinline__ void pair_of(int p, int n_tiles, int &mt, int &nt) {
     mt = nt = 0;
@@ -51,16 +51,6 @@ __device__ __forceinline__ void pair_of(int p, int n_tiles, int &mt, int &nt) {
             }
         }
     }
-}
-
-// Work item (token split, tile pair) of a block.  Workgroups go to the chip's eight dies round robin, each
-// die has its own L2, and a die runs 32 of these blocks at a time: so die x takes items in chunks of 32
-// consecutive ones (one patch of one split, more or less), and the blocks that share an L2 share slabs.
-// Returns false for the padding blocks at the end of the grid.
-__device__ __forceinline__ bool item_of_block(int block, int n_items, int &item) {
-    const int die = block % kXcds, j = block / kXcds;
-    item = ((j / kChunk) * kXcds + die) * kChunk + j % kChunk;
-    return item < n_items;
 }
 
 // The slabs of X go from global memory straight into LDS (no staging registers, no LDS stores): a wave's load

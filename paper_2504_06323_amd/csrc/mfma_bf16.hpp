@@ -22,6 +22,19 @@ __device__ __forceinline__ void load_to_lds(const void *src, uint32_t lds_addr) 
 // s_waitcnt with only the vector-memory counter set (6 bits: [3:0] and [15:14]); the others left at "no wait"
 #define MP_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt((((n) & 15) | (((n) >> 4) << 14)) | 0x0F70)
 
+constexpr int kChunk = 32, kXcds = 8;
+
+// Work item of a block of a tiled matrix-core kernel.  Workgroups go to the chip's eight dies round robin, each
+// die has its own L2, and a die runs 32 of these blocks at a time: so die x takes items in chunks of 32
+// consecutive ones (the kernels number their items so that neighbours share operand slabs), and the blocks that
+// share an L2 share slabs.
+// Returns false for the padding blocks at the end of the grid.
+__device__ __forceinline__ bool item_of_block(int block, int n_items, int &item) {
+    const int die = block % kXcds, j = block / kXcds;
+    item = ((j / kChunk) * kXcds + die) * kChunk + j % kChunk;
+    return item < n_items;
+}
+
 __device__ __forceinline__ bf16_t narrow_to_bf16(float f) {  // round to nearest, ties to even
     const uint32_t b = __float_as_uint(f);
     if ((b & 0x7fffffffu) > 0x7f800000u) return static_cast<bf16_t>(0x7fc0u);

@@ -32,8 +32,26 @@ __device__ __forceinline__ bf16x8 operand_rows(const unsigned char *slab, int ro
 
 __device__ __forceinline__ float silu(float a) { return a / (1.f + __expf(-a)); }
 
+// Output tiles are numbered patch by patch (4 row tiles x 8 column tiles: 32 tiles that need only 12 operand
+// slabs), patches row band by row band; tile `item` -> (mt, nt).
+__device__ __forceinline__ void tile_of(int item, int m_tiles, int n_tiles, int &mt, int &nt) {
+    mt = nt = 0;
+    for (int r0 = 0; r0 < m_tiles; r0 += 4) {
+        const int rows = m_tiles - r0 < 4 ? m_tiles - r0 : 4;
+        for (int c0 = 0; c0 < n_tiles; c0 += 8) {
+            const int cols = n_tiles - c0 < 8 ? n_tiles - c0 : 8;
+            if (item < rows * cols) {
+                mt = r0 + item / cols;
+                nt = c0 + item % cols;
+                return;
+            }
+            item -= rows * cols;
+        }
+    }
+}
+
 // DUAL = false: y[M, N] = x w0^T.   DUAL = true: y[M, N] = silu(x w0^T) * (x w1^T), N channels, and
-// sq_partial[2 * blockIdx.y + {0, 1}][n] = sum over 128 rows of y^2 (of the rounded values), when non-null.
+// sq_partial[2 * (row tile) + {0, 1}][n] = sum over 128 rows of y^2 (of the rounded values), when non-null.
 template <bool DUAL>
 __global__ __launch_bounds__(kLinBlock, 1) void linear_tiles_bf16(const bf16_t *__restrict__ x, int64_t ld_x,
                                                                   const bf16_t *__restrict__ w0,
@@ -43,8 +61,13 @@ __global__ __launch_bounds__(kLinBlock, 1) void linear_tiles_bf16(const bf16_t *
     __shared__ __attribute__((aligned(1024))) unsigned char ring[kLinRing][2][kLinSlabBytes];
     typedef __attribute__((address_space(3))) unsigned char lds_byte;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = wave >> 1, wn = wave & 1;
-    const int m0 = blockIdx.y * kLinTile;
-    const int n0 = blockIdx.x * (DUAL ? kLinTile / 2 : kLinTile);  // first output channel of the block
+    constexpr int kChannels = DUAL ? kLinTile / 2 : kLinTile;  // output channels of a block
+    const int m_tiles = (M + kLinTile - 1) / kLinTile, n_tiles = (N + kChannels - 1) / kChannels;
+    int item, mt, nt;
+    if (!item_of_block(blockIdx.x, m_tiles * n_tiles, item)) return;  // the whole block, before any barrier
+    tile_of(item, m_tiles, n_tiles, mt, nt);
+    const int m0 = mt * kLinTile;
+    const int n0 = nt * kChannels;  // first output channel of the block
     const int n_stages = K / kLinStep;
 
     // Load instruction p of this wave fills LDS window 4 p + wave (16 rows of 64 bytes) of a slab: row
@@ -188,7 +211,7 @@ __global__ __launch_bounds__(kLinBlock, 1) void linear_tiles_bf16(const bf16_t *
             // lanes l and l + 32 hold the other rows of the same column
             sq += __shfl_xor(sq, 32);
             if (sq_partial && lane < 32 && col < N)
-                sq_partial[(2 * static_cast<int64_t>(blockIdx.y) + wm) * N + col] = sq;
+                sq_partial[(2 * static_cast<int64_t>(mt) + wm) * N + col] = sq;
         }
     }
 }
@@ -273,11 +296,17 @@ __global__ __launch_bounds__(256) void linear_generic(const T *__restrict__ x, i
     }
 }
 
+// blocks for n_items tiles: whole chunks of 32 per die
+unsigned tiled_grid(int64_t n_items) {
+    return static_cast<unsigned>(ceil_div(ceil_div(n_items, kChunk), kXcds) * kXcds * kChunk);
+}
+
 bool linear_tiles_ok(int dtype, const void *x, int64_t ld_x, const void *w0, const void *w1, int64_t ld_w, int64_t M,
                      int64_t N, int64_t K) {
     return dtype == PRUNE_BF16 && K >= kLinStep && K % kLinStep == 0 && ld_x % 8 == 0 && ld_w % 8 == 0 &&
            aligned_to(x, 16) && aligned_to(w0, 16) && (!w1 || aligned_to(w1, 16)) && M > 0 && N > 0 &&
-           M < (int64_t(1) << 31) - kLinTile && N < (int64_t(1) << 31) - kLinTile && ceil_div(M, kLinTile) <= 65535;
+           M < (int64_t(1) << 31) - kLinTile && N < (int64_t(1) << 31) - kLinTile &&
+           ceil_div(M, kLinTile) * ceil_div(N, kLinTile / 2) < (int64_t(1) << 30);
 }
 
 template <typename T, bool DUAL>
@@ -319,7 +348,7 @@ extern "C" int prune_linear(const void *x, const void *w, void *y, int dtype, in
     if (st != PRUNE_OK) return st;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     if (linear_tiles_ok(dtype, x, ld_x, w, nullptr, ld_w, tokens, n, k)) {
-        const dim3 grid(static_cast<unsigned>(ceil_div(n, kLinTile)), static_cast<unsigned>(ceil_div(tokens, kLinTile)));
+        const dim3 grid(tiled_grid(ceil_div(tokens, kLinTile) * ceil_div(n, kLinTile)));
         hipLaunchKernelGGL(linear_tiles_bf16<false>, grid, dim3(kLinBlock), 0, stream, static_cast<const bf16_t *>(x),
                            ld_x, static_cast<const bf16_t *>(w), static_cast<const bf16_t *>(nullptr), ld_w,
                            static_cast<int>(tokens), static_cast<int>(n), static_cast<int>(k), static_cast<bf16_t *>(y),
@@ -348,8 +377,7 @@ extern "C" int prune_mlp_gate_up(const void *x, const void *gate, const void *up
             if (ws_bytes < static_cast<size_t>(n_groups) * inter * sizeof(float)) return PRUNE_ERR_WORKSPACE;
             partial = static_cast<float *>(ws);
         }
-        const dim3 grid(static_cast<unsigned>(ceil_div(inter, kLinTile / 2)),
-                        static_cast<unsigned>(ceil_div(tokens, kLinTile)));
+        const dim3 grid(tiled_grid(ceil_div(tokens, kLinTile) * ceil_div(inter, kLinTile / 2)));
         hipLaunchKernelGGL(linear_tiles_bf16<true>, grid, dim3(kLinBlock), 0, stream, static_cast<const bf16_t *>(x),
                            ld_x, static_cast<const bf16_t *>(gate), static_cast<const bf16_t *>(up), ld_w,
                            static_cast<int>(tokens), static_cast<int>(inter), static_cast<int>(hidden),
