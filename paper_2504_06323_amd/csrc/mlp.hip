@@ -216,14 +216,23 @@ __global__ __launch_bounds__(kLinBlock, 1) void linear_tiles_bf16(const bf16_t *
     }
 }
 
-// sumsq[n] += sum over the row groups, in order, of the partial sums (double accumulation)
+// sumsq[n] += sum over the row groups of the partial sums (double accumulation in a fixed order: a block takes 64
+// channels, four quarters of the groups side by side, then the quarters in order)
 __global__ __launch_bounds__(256) void fold_square_partials(const float *__restrict__ partial, int n_groups, int N,
                                                             float *__restrict__ sumsq) {
-    const int n = blockIdx.x * 256 + threadIdx.x;
-    if (n >= N) return;
+    __shared__ double quarter[4][64];
+    const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
+    const int n = blockIdx.x * 64 + c;
+    const int per = (n_groups + 3) / 4, g0 = q * per, g1 = g0 + per < n_groups ? g0 + per : n_groups;
     double s = 0.0;
-    for (int g = 0; g < n_groups; ++g) s += static_cast<double>(partial[static_cast<int64_t>(g) * N + n]);
-    sumsq[n] = static_cast<float>(static_cast<double>(sumsq[n]) + s);
+    if (n < N)
+        for (int g = g0; g < g1; ++g) s += static_cast<double>(partial[static_cast<int64_t>(g) * N + n]);
+    quarter[q][c] = s;
+    __syncthreads();
+    if (q == 0 && n < N) {
+        const double total = ((quarter[0][c] + quarter[1][c]) + quarter[2][c]) + quarter[3][c];
+        sumsq[n] = static_cast<float>(static_cast<double>(sumsq[n]) + total);
+    }
 }
 
 // Any element type and shape: a 64 x 64 output tile per block (16 x 16 threads, 4 x 4 outputs each), fp32 FMAs.
@@ -384,7 +393,7 @@ extern "C" int prune_mlp_gate_up(const void *x, const void *gate, const void *up
                            static_cast<bf16_t *>(h), ld_h, partial);
         if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
         if (sumsq) {
-            hipLaunchKernelGGL(fold_square_partials, dim3(static_cast<unsigned>(ceil_div(inter, 256))), dim3(256), 0,
+            hipLaunchKernelGGL(fold_square_partials, dim3(static_cast<unsigned>(ceil_div(inter, 64))), dim3(256), 0,
                                stream, partial, n_groups, static_cast<int>(inter), sumsq);
             return launch_status();
         }
