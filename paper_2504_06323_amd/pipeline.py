@@ -102,6 +102,17 @@ def rank_layer(st: LayerState, acts: Dict[str, torch.Tensor], alpha: float,
         prune.outlier_ratio(w, nrm, alpha, st.score_sum[i:i + 1], st.count[i:i + 1], tau=st.tau[i:i + 1], scores=sc)
 
 
+def down_input_from_forward(st: LayerState, x_mlp: torch.Tensor, h: Optional[torch.Tensor] = None,
+                            act: str = "down_in") -> torch.Tensor:
+    """The down projection's input from a real forward pass of the feed-forward block, h = silu(x gate^T) * (x up^T),
+    with its channel statistic accumulated where h is produced: fills st.sumsq[act] and st.norms[act] (instead of
+    a statistics pass over an injected tensor) and returns h."""
+    st.sumsq[act].zero_()
+    h = prune.mlp_gate_up(x_mlp, st.weights["gate"], st.weights["up"], h=h, sumsq=st.sumsq[act])
+    prune.stats_finalize(st.sumsq[act], st.norms[act])
+    return h
+
+
 def plan(counts: Sequence[int], numels: Sequence[int], cols: Sequence[int], n_layers: int, n_proj: int, p: float,
          lam: float, scope: int = prune.SCOPE_GLOBAL):
     """Host planner over all layers' counts: returns (sparsities, zeros per row, clamped)."""

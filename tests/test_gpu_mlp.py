@@ -122,3 +122,27 @@ def test_mlp_fullsize_sampled(lib):
     want_y = mlp.linear(got_h, d64)                                              # the second product on the stored h
     got_y = to_np(y[torch.as_tensor(rows, device=DEV)]).astype(np.float64)
     assert np.max(np.abs(got_y - want_y)) <= 2.0 ** -7 * np.max(np.abs(want_y))
+
+
+def test_down_input_statistic_from_the_forward_pass(lib):
+    """pipeline.down_input_from_forward: norms of the down projection's input taken from the block's own forward pass
+    equal the statistics pass over the same h, and feed the ranking like any other norms."""
+    from paper_2504_06323_amd import pipeline
+    cfg = synth.CONFIGS["toy"]
+    shapes = synth.projection_shapes(cfg)
+    act_shapes = synth.activation_shapes(cfg)
+    weights = {n: synth.make_weight(cfg, 0, n, DEV) for n, _, _, _ in shapes}
+    st = pipeline.LayerState.create(weights, {n: a for n, _, _, a in shapes}, act_shapes, cfg.n_tokens)
+    x = synth.make_activation(cfg, 0, "mlp_in", DEV)
+    h = pipeline.down_input_from_forward(st, x)
+    _sync()
+    want_h = mlp.mlp_hidden(to_np(x).astype(np.float64), to_np(weights["gate"]).astype(np.float64),
+                            to_np(weights["up"]).astype(np.float64))
+    assert np.max(np.abs(to_np(h).astype(np.float64) - want_h)) <= 1e-5 * np.max(np.abs(want_h))      # toy layer: fp32
+    want_norms = orc.column_norms(to_np(h))
+    assert np.max(np.abs(to_np(st.norms["down_in"]) / want_norms - 1.0)) < 1e-5
+    sums = torch.zeros(1, dtype=torch.float64, device=DEV)
+    prune.score(weights["down"], st.norms["down_in"], sums)
+    _sync()
+    omega = orc.weight_metric(to_np(weights["down"]), want_norms)
+    assert abs(sums.item() - omega.sum()) <= 1e-5 * omega.sum()
