@@ -381,6 +381,34 @@ int prune_mlp_gate_up(const void *x, const void *gate, const void *up, void *h, 
                       int64_t hidden, int64_t inter, int64_t ld_x, int64_t ld_w, int64_t ld_h, float *sumsq, void *ws,
                       size_t ws_bytes, void *stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * The attention half of a LLaMA-style layer (Table 2, Section 4.1.1), so that the inputs of the q / k / v, o and
+ * gate / up projections can come from a forward pass as well.  Token rows hold their heads side by side.
+ * ------------------------------------------------------------------------------------------------ */
+
+/* y[t, :] = x[t, :] / sqrt(mean_j x[t, j]^2 + eps) * weight[:]; x, y [tokens, channels] with pitches, weight [channels]. */
+int prune_rmsnorm(const void *x, const void *weight, void *y, int dtype, int64_t tokens, int64_t channels, int64_t ld_x,
+                  int64_t ld_y, float eps, void *stream);
+
+/*
+ * Rotary position embedding, in place on x [tokens, heads * head_dim] (pitch ld): in every head, dimension
+ * i < head_dim / 2 is paired with i + head_dim / 2 and the pair (a, b) becomes (a cos - b sin, b cos + a sin) with
+ * the angle (t mod seq_len) * base^(-2 i / head_dim).  head_dim even, base > 1 (the models use 10000).
+ */
+int prune_rotary(void *x, int dtype, int64_t tokens, int64_t heads, int64_t head_dim, int64_t ld, int64_t seq_len,
+                 float base, void *stream);
+
+/*
+ * Causal attention per sequence and head:
+ *   o[s, h, :] = sum_{t <= s} softmax_t(q[s, h, :] . k[t, g, :] / sqrt(head_dim)) v[t, g, :],  g = h / (heads / kv_heads)
+ * q, o [n_seqs * seq_len, heads * head_dim], k, v [n_seqs * seq_len, kv_heads * head_dim], with pitches; heads a
+ * multiple of kv_heads, head_dim <= 256.  bf16 with head_dim 128, pitches multiples of 8 and 16-byte aligned bases
+ * runs on the matrix cores; anything else on a plain kernel with the same semantics.
+ */
+int prune_causal_attention(const void *q, const void *k, const void *v, void *o, int dtype, int64_t n_seqs,
+                           int64_t seq_len, int64_t heads, int64_t kv_heads, int64_t head_dim, int64_t ld_q, int64_t ld_k,
+                           int64_t ld_v, int64_t ld_o, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB_PATH = os.path.join(CSRC, "libmosaic_prune.so")
-SOURCES = ["stats.hip", "score.hip", "rank_batch.hip", "select.hip", "structured.hip", "groups.hip", "plan_device.hip", "hessian.hip", "factor.hip", "sweep.hip", "mlp.hip", "host.cpp"]
+SOURCES = ["stats.hip", "score.hip", "rank_batch.hip", "select.hip", "structured.hip", "groups.hip", "plan_device.hip", "hessian.hip", "factor.hip", "sweep.hip", "mlp.hip", "layer.hip", "attention.hip", "host.cpp"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -1,0 +1,224 @@
+// Causal attention of one layer on the matrix cores (bf16, heads of width 128; grouped key / value heads):
+//   o[s, h] = sum_{t <= s} softmax_t(q[s, h] . k[t, g] / sqrt(d)) v[t, g],   g = h / (heads / kv_heads).
+// It produces the input of the o projection from the layer's own q, k, v (LLaMA-style layers of Table 2,
+// Section 4.1.1), so that this activation too can come from a forward pass.
+//
+// A block of four waves takes 128 consecutive queries of one (sequence, head), 32 per wave, and walks the keys
+// 64 at a time with the usual streaming softmax.  Both products are formed transposed, which keeps every step in
+// registers:  S^T = K Q^T puts a query in a lane (column) and its keys in that lane's accumulator elements, so
+// the running maximum and sum of a query are in-lane reductions plus one exchange with the lane 32 apart, and the
+// 8 probabilities an MFMA operand wants per lane are 8 consecutive accumulator elements -- P never leaves the
+// registers;  O^T = V^T P^T then needs V with the keys along the MFMA's inner dimension, which the LDS transpose
+// read provides from the row-major tile.  Any permutation of the inner (key) index is fine as long as both
+// operands use the same one; the one used is the accumulator's own element order.
+// K and V tiles go from global memory straight into LDS (two stages), swizzled per row against bank conflicts.
+#include "mfma_bf16.hpp"
+
+namespace mp {
+
+namespace {
+
+constexpr int kHeadDim = 128, kQueriesPerBlock = 128, kKeysPerTile = 64;
+constexpr int kTileBytes = kKeysPerTile * kHeadDim * 2;  // 16 KB
+constexpr int kOutPitch = 272;                           // bytes per query row in the output staging (256 + 16)
+
+// two floats -> two bf16 (round to nearest even) in one word, low half first
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    return static_cast<uint32_t>(narrow_to_bf16(lo)) | (static_cast<uint32_t>(narrow_to_bf16(hi)) << 16);
+}
+
+// A operand of S^T = K Q^T: keys row_base + lane % 32, the 8 head dimensions 16 kk + 8 (lane / 32) ...
+// K tile rows are 256 bytes (16 packets); packet c of row r sits at position c ^ (r % 16)
+__device__ __forceinline__ bf16x8 k_operand(const unsigned char *tile, int row_base, int kk, int lane) {
+    const int row = row_base + (lane & 31);
+    const int chunk = 2 * kk + (lane >> 5);
+    const u32x4 v = *reinterpret_cast<const u32x4 *>(tile + row * 256 + ((chunk ^ (row & 15)) << 4));
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// A operand of O^T = V^T P^T: head dimension col_base + lane % 32, and for the lane's half h = lane / 32 the keys
+// row_base + 4 h + {0, 1, 2, 3} and row_base + 8 + 4 h + {0, 1, 2, 3}: the keys whose probabilities sit in
+// accumulator elements v0 .. v0 + 7 of that half.  V tile rows are 256 bytes; packet c of row r at c ^ (4 (r % 4)).
+__device__ __forceinline__ bf16x8 v_operand(const unsigned char *tile, int row_base, int col_base, int lane) {
+    const int s = lane & 15, g = lane >> 4;
+    const int row = row_base + 4 * (g >> 1) + (s >> 2);
+    const int col = col_base + 16 * (g & 1) + 4 * (s & 3);
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const unsigned char *p0 = tile + row * 256 + ((((col >> 3) ^ (4 * (row & 3)))) << 4) + (col & 4) * 2;
+    const int row1 = row + 8;
+    const unsigned char *p1 = tile + row1 * 256 + ((((col >> 3) ^ (4 * (row1 & 3)))) << 4) + (col & 4) * 2;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p0);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p1);
+    const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+    return __builtin_bit_cast(bf16x8, both);
+}
+
+__global__ __launch_bounds__(256) void attention_tiles_bf16(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
+                                                            const bf16_t *__restrict__ v, bf16_t *__restrict__ o,
+                                                            int seq_len, int heads, int kv_heads, int64_t ld_q,
+                                                            int64_t ld_k, int64_t ld_v, int64_t ld_o, float scale_log2e) {
+    __shared__ __attribute__((aligned(1024))) unsigned char ring[2][2][kTileBytes];  // [stage][K, V]
+    typedef __attribute__((address_space(3))) unsigned char lds_byte;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int q_tiles = (seq_len + kQueriesPerBlock - 1) / kQueriesPerBlock;
+    // the blocks with the most keys go first
+    const int qt = q_tiles - 1 - static_cast<int>(blockIdx.x % q_tiles);
+    const int head = static_cast<int>((blockIdx.x / q_tiles) % heads);
+    const int64_t seq = blockIdx.x / (static_cast<int64_t>(q_tiles) * heads);
+    const int kv_head = head / (heads / kv_heads);
+    const int64_t t0 = seq * seq_len;
+    const int q0 = qt * kQueriesPerBlock + 32 * wave;  // first query of this wave
+    const int my_query = q0 + (lane & 31);
+    const int n_tiles = (qt * kQueriesPerBlock + kQueriesPerBlock + kKeysPerTile - 1) / kKeysPerTile;
+
+    // Q as the B operand, kept in registers: query lane % 32, head dimensions 16 kk + 8 (lane / 32) ...
+    bf16x8 qreg[8];
+    {
+        const int qr = my_query < seq_len ? my_query : seq_len - 1;
+        const bf16_t *src = q + (t0 + qr) * ld_q + head * kHeadDim + 8 * (lane >> 5);
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk)
+            qreg[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4 *>(src + 16 * kk));
+    }
+
+    // load instruction p of this wave fills rows 4 (4 p + wave) ... + 3 of a tile: row 4 (4 p + wave) + lane / 16,
+    // position lane % 16
+    const char *pk[4], *pv[4];
+    int lrow[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        lrow[p] = 4 * (4 * p + wave) + (lane >> 4);
+        const int pos = lane & 15;
+        pk[p] = reinterpret_cast<const char *>(k + t0 * ld_k + kv_head * kHeadDim + 8 * (pos ^ (lrow[p] & 15)));
+        pv[p] = reinterpret_cast<const char *>(v + t0 * ld_v + kv_head * kHeadDim + 8 * (pos ^ (4 * (lrow[p] & 3))));
+    }
+    auto issue = [&](int tile) {
+        const uint32_t dst = __builtin_amdgcn_readfirstlane(
+            static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_byte *)&ring[tile & 1][0][0])) +
+            static_cast<uint32_t>(wave) * 1024u);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            int key = tile * kKeysPerTile + lrow[p];
+            key = key < seq_len ? key : seq_len - 1;  // keys past the end are masked by causality anyway
+            load_to_lds(pk[p] + static_cast<int64_t>(key) * ld_k * 2, dst + 4096u * p);
+            load_to_lds(pv[p] + static_cast<int64_t>(key) * ld_v * 2, dst + kTileBytes + 4096u * p);
+        }
+    };
+
+    f32x16 acc_o[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc_o[dt][e] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;  // running maximum (in units of log2) and this lane's share of the sum
+
+    issue(0);
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        const bool more = tile + 1 < n_tiles;
+        if (more) issue(tile + 1);  // its buffer was released by the barrier that ended the previous trip
+        if (more)
+            MP_WAIT_VMCNT(8);
+        else
+            MP_WAIT_VMCNT(0);
+        __syncthreads();
+        const unsigned char *kt = &ring[tile & 1][0][0], *vt = &ring[tile & 1][1][0];
+
+        // S^T for 64 keys x 32 queries
+        f32x16 s[2];
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s[mt][e] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk)
+                s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_operand(kt, 32 * mt, kk, lane), qreg[kk], s[mt], 0, 0, 0);
+        }
+        // scale, causal mask (only the tiles that reach past this wave's first query need it), running maximum
+        const int key0 = tile * kKeysPerTile + 4 * (lane >> 5);
+        const bool on_diagonal = tile * kKeysPerTile + kKeysPerTile - 1 > q0;
+        float m_new = m_run;
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                float x = s[mt][e] * scale_log2e;
+                if (on_diagonal) {
+                    const int key = key0 + 32 * mt + 8 * (e >> 2) + (e & 3);
+                    x = key > my_query ? -INFINITY : x;
+                }
+                s[mt][e] = x;
+                m_new = fmaxf(m_new, x);
+            }
+        m_new = fmaxf(m_new, __shfl_xor(m_new, 32));  // the other half of the keys of this query
+        // (m_new is finite: key 0 is visible to every query, and tile 0 is processed first)
+        const float fix = exp2f(m_run - m_new);
+        m_run = m_new;
+        l_run *= fix;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc_o[dt][e] *= fix;
+        // probabilities, and O^T += V^T P^T sixteen keys at a time
+#pragma unroll
+        for (int step = 0; step < 4; ++step) {
+            const int mt = step >> 1, e0 = 8 * (step & 1);
+            float p[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                p[i] = exp2f(s[mt][e0 + i] - m_new);
+                l_run += p[i];
+            }
+            const u32x4 packed = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]),
+                                  pack_bf16(p[6], p[7])};
+            const bf16x8 pb = __builtin_bit_cast(bf16x8, packed);
+            const int row_base = 32 * mt + 16 * (step & 1);
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+                acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_operand(vt, row_base, 32 * dt, lane), pb, acc_o[dt], 0, 0, 0);
+        }
+        __syncthreads();  // every wave is done with this stage before the next trip loads into it
+    }
+
+    // o[query][d] = O^T[d][query] / sum; staged through LDS so that a query's 256 bytes leave in 16-byte pieces
+    const float inv = 1.f / (l_run + __shfl_xor(l_run, 32));
+    unsigned char *stage = &ring[0][0][0] + wave * (32 * kOutPitch);
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int e = 0; e < 16; e += 2) {
+            // elements e, e + 1 are head dimensions d, d + 1 of this lane's query
+            const int d = 32 * dt + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+            *reinterpret_cast<uint32_t *>(stage + (lane & 31) * kOutPitch + d * 2) =
+                pack_bf16(acc_o[dt][e] * inv, acc_o[dt][e + 1] * inv);
+        }
+    // (only this wave touches its part of the staging area: LDS operations of a wave complete in order)
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        const int piece = lane + 64 * r, row = piece >> 4, c = piece & 15;
+        const int query = q0 + row;
+        if (query < seq_len)
+            *reinterpret_cast<u32x4 *>(o + (t0 + query) * ld_o + head * kHeadDim + 8 * c) =
+                *reinterpret_cast<const u32x4 *>(stage + row * kOutPitch + c * 16);
+    }
+}
+
+}  // namespace
+
+bool launch_attention_tiles(const void *q, const void *k, const void *v, void *o, int dtype, int64_t n_seqs,
+                            int64_t seq_len, int64_t heads, int64_t kv_heads, int64_t head_dim, int64_t ld_q,
+                            int64_t ld_k, int64_t ld_v, int64_t ld_o, hipStream_t stream) {
+    const int64_t q_tiles = ceil_div(seq_len, kQueriesPerBlock);
+    const int64_t blocks = n_seqs * heads * q_tiles;
+    if (dtype != PRUNE_BF16 || head_dim != kHeadDim || seq_len > (1 << 24) || blocks >= (int64_t(1) << 31) ||
+        ld_q % 8 != 0 || ld_k % 8 != 0 || ld_v % 8 != 0 || ld_o % 8 != 0 || !aligned_to(q, 16) || !aligned_to(k, 16) ||
+        !aligned_to(v, 16) || !aligned_to(o, 16))
+        return false;
+    const float scale_log2e = 1.4426950408889634f / sqrtf(static_cast<float>(head_dim));
+    hipLaunchKernelGGL(attention_tiles_bf16, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream,
+                       static_cast<const bf16_t *>(q), static_cast<const bf16_t *>(k), static_cast<const bf16_t *>(v),
+                       static_cast<bf16_t *>(o), static_cast<int>(seq_len), static_cast<int>(heads),
+                       static_cast<int>(kv_heads), ld_q, ld_k, ld_v, ld_o, scale_log2e);
+    return true;
+}
+
+}  // namespace mp

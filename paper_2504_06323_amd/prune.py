@@ -51,6 +51,9 @@ _SIGNATURES = {
     "prune_linear": (_int, [_vp, _vp, _vp, _int, _i64, _i64, _i64, _i64, _i64, _i64, _vp]),
     "prune_mlp_workspace_bytes": (_sz, [_i64, _i64]),
     "prune_mlp_gate_up": (_int, [_vp, _vp, _vp, _vp, _int, _i64, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
+    "prune_rmsnorm": (_int, [_vp, _vp, _vp, _int, _i64, _i64, _i64, _i64, _f32, _vp]),
+    "prune_rotary": (_int, [_vp, _int, _i64, _i64, _i64, _i64, _i64, _f32, _vp]),
+    "prune_causal_attention": (_int, [_vp, _vp, _vp, _vp, _int, _i64, _i64, _i64, _i64, _i64, _i64, _i64, _i64, _i64, _vp]),
     "prune_plan_sparsity_device": (_int, [_vp, _vp, _vp, _int, _int, _f64, _f64, _int, _vp, _vp, _vp, _vp]),
     "prune_struct_groups_workspace_bytes": (_sz, [_vp, _vp, _int, _vp, _vp, _int, _i64]),
     "prune_struct_groups": (_int, [_vp, _vp, _vp, _int, _vp, _vp, _vp, _int, _int, _i64, _u32, _vp, _vp, _vp, _vp,
@@ -456,6 +459,48 @@ def mlp_gate_up(x: torch.Tensor, gate: torch.Tensor, up: torch.Tensor, h: Option
            load().prune_mlp_gate_up(xp, gp, up_p, hp, _dtype_code(x), tokens, hidden, inter, ld_x, ld_w, ld_h,
                                     _vector(sumsq, "sumsq", torch.float32, inter), ws_ptr, ws_bytes, _stream(stream)))
     return h
+
+
+def rmsnorm(x: torch.Tensor, weight: torch.Tensor, eps: float = 1e-5, y: Optional[torch.Tensor] = None,
+            stream=None) -> torch.Tensor:
+    """y = x / sqrt(mean(x^2) + eps) * weight, row by row (prune_rmsnorm)."""
+    xp, tokens, channels, ld_x = _matrix(x, "x")
+    if y is None:
+        y = torch.empty_like(x)
+    yp, yt, yc, ld_y = _matrix(y, "y")
+    if (yt, yc) != (tokens, channels) or y.dtype != x.dtype or weight.dtype != x.dtype:
+        raise ValueError("y must match x; weight must have x's dtype")
+    _check("prune_rmsnorm", load().prune_rmsnorm(xp, _vector(weight, "weight", x.dtype, channels), yp, _dtype_code(x),
+                                                 tokens, channels, ld_x, ld_y, float(eps), _stream(stream)))
+    return y
+
+
+def rotary(x: torch.Tensor, heads: int, head_dim: int, seq_len: int, base: float = 10000.0, stream=None) -> None:
+    """Rotary position embedding in place on [tokens, heads * head_dim] (prune_rotary)."""
+    xp, tokens, width, ld = _matrix(x, "x")
+    if width != heads * head_dim:
+        raise ValueError("x must be [tokens, heads * head_dim]")
+    _check("prune_rotary", load().prune_rotary(xp, _dtype_code(x), tokens, heads, head_dim, ld, seq_len, float(base),
+                                               _stream(stream)))
+
+
+def causal_attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, n_seqs: int, seq_len: int, heads: int,
+                     kv_heads: int, head_dim: int, o: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """Causal attention per sequence and head with grouped key / value heads (prune_causal_attention)."""
+    qp, tq, wq, ld_q = _matrix(q, "q")
+    kp, tk, wk, ld_k = _matrix(k, "k")
+    vp, tv, wv, ld_v = _matrix(v, "v")
+    if not (tq == tk == tv == n_seqs * seq_len and wq == heads * head_dim and wk == wv == kv_heads * head_dim):
+        raise ValueError("q [tokens, heads * d], k and v [tokens, kv_heads * d] expected")
+    if o is None:
+        o = torch.empty((tq, wq), dtype=q.dtype, device=q.device)
+    op, to_, wo, ld_o = _matrix(o, "o")
+    if (to_, wo) != (tq, wq) or len({q.dtype, k.dtype, v.dtype, o.dtype}) != 1:
+        raise ValueError("o must match q; all four share one dtype")
+    _check("prune_causal_attention",
+           load().prune_causal_attention(qp, kp, vp, op, _dtype_code(q), n_seqs, seq_len, heads, kv_heads, head_dim,
+                                         ld_q, ld_k, ld_v, ld_o, _stream(stream)))
+    return o
 
 
 def struct_compact(gate: torch.Tensor, up: torch.Tensor, down: torch.Tensor, r: int, group_mag: torch.Tensor,

@@ -1,0 +1,87 @@
+"""GPU parity of the attention-half kernels (rmsnorm, rotary embedding, causal attention) against oracle/layer_oracle.py."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import layer_oracle as lay
+from paper_2504_06323_amd import prune, synth
+from util import to_np
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+ULP = {torch.bfloat16: 2.0 ** -8, torch.float32: 2.0 ** -22}
+
+
+def _sync():
+    torch.cuda.synchronize()
+
+
+def _mat(rows, cols, dtype, seed, scale=1.0):
+    return synth.random_matrix(rows, cols, dtype, seed=seed, device=DEV, scale=scale)
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("shape", [(37, 256), (512, 4096), (5, 100)])
+def test_rmsnorm_vs_oracle(lib, dtype, shape):
+    tokens, channels = shape
+    x = _mat(tokens, channels, dtype, 1, 3.0)
+    w = _mat(1, channels, dtype, 2, 1.0).reshape(-1).contiguous()
+    y = prune.rmsnorm(x, w, eps=1e-5)
+    _sync()
+    want = lay.rmsnorm(to_np(x), to_np(w), 1e-5)
+    assert np.max(np.abs(to_np(y).astype(np.float64) - want) / (ULP[dtype] * np.abs(want) + 1e-6)) < 1.0
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_rotary_vs_oracle(lib, dtype):
+    n_seqs, seq_len, heads, d = 3, 200, 4, 64
+    x = _mat(n_seqs * seq_len, heads * d, dtype, 3)
+    x0 = to_np(x).astype(np.float64).reshape(n_seqs * seq_len, heads, d)
+    prune.rotary(x, heads, d, seq_len)
+    _sync()
+    pos = np.tile(np.arange(seq_len), n_seqs)
+    want = lay.rotary(x0, pos).reshape(n_seqs * seq_len, heads * d)
+    # fp32 angles up to 199 rad (relative error 2^-24 of the angle), then one rounding to dtype
+    assert np.max(np.abs(to_np(x).astype(np.float64) - want)) <= (ULP[dtype] + 5e-5) * np.max(np.abs(want))
+
+
+def _attention_case(dtype, n_seqs, seq_len, heads, kv_heads, d, seed):
+    tokens = n_seqs * seq_len
+    q, k, v = _mat(tokens, heads * d, dtype, seed), _mat(tokens, kv_heads * d, dtype, seed + 1), _mat(tokens, kv_heads * d, dtype, seed + 2)
+    o = prune.causal_attention(q, k, v, n_seqs, seq_len, heads, kv_heads, d)
+    _sync()
+    got = to_np(o).astype(np.float64).reshape(n_seqs, seq_len, heads, d)
+    q64, k64, v64 = (to_np(t).astype(np.float64) for t in (q, k, v))
+    worst = 0.0
+    for b in range(n_seqs):
+        sl = slice(b * seq_len, (b + 1) * seq_len)
+        want = lay.causal_attention(q64[sl].reshape(seq_len, heads, d), k64[sl].reshape(seq_len, kv_heads, d),
+                                    v64[sl].reshape(seq_len, kv_heads, d))
+        worst = max(worst, float(np.max(np.abs(got[b] - want))))
+    return worst, float(np.max(np.abs(v64)))
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("case", [(2, 100, 4, 2, 64), (1, 70, 3, 3, 40), (2, 64, 2, 1, 128)])
+def test_attention_plain_kernel_vs_oracle(lib, dtype, case):
+    """Shapes that take the any-shape kernel (fp32, or heads that are not 128 wide)."""
+    if dtype == torch.bfloat16 and case[4] == 128:
+        pytest.skip("bf16 heads of width 128 take the matrix-core kernel, tested below")
+    worst, vmax = _attention_case(dtype, *case, seed=10)
+    assert worst <= (ULP[dtype] + 2e-5) * vmax * 4
+
+
+@pytest.mark.parametrize("case", [(2, 256, 4, 2, 128), (1, 384, 2, 2, 128), (3, 200, 4, 1, 128), (1, 128, 1, 1, 128),
+                                  (2, 2048, 2, 1, 128)])
+def test_attention_matrix_core_kernel_vs_oracle(lib, case):
+    """bf16, 128-wide heads.  Probabilities enter the second product as bf16 (half an ulp each, averaging out over
+    the keys of a query) and the output is rounded to bf16."""
+    worst, vmax = _attention_case(torch.bfloat16, *case, seed=20)
+    assert worst <= 2.0 ** -7 * vmax
+    q = _mat(case[0] * case[1], case[2] * 128, torch.bfloat16, 30)
+    k = _mat(case[0] * case[1], case[3] * 128, torch.bfloat16, 31)
+    v = _mat(case[0] * case[1], case[3] * 128, torch.bfloat16, 32)
+    a = prune.causal_attention(q, k, v, *case)
+    b = prune.causal_attention(q, k, v, *case)
+    _sync()
+    assert torch.equal(a, b)
