@@ -24,7 +24,9 @@ constexpr int kOutPitch = 272;                           // bytes per query row 
 
 // two floats -> two bf16 (round to nearest even) in one word, low half first
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-    return static_cast<uint32_t>(narrow_to_bf16(lo)) | (static_cast<uint32_t>(narrow_to_bf16(hi)) << 16);
+    uint32_t r;
+    asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r) : "v"(lo), "v"(hi));
+    return r;
 }
 
 // A operand of S^T = K Q^T: keys row_base + lane % 32, the 8 head dimensions 16 kk + 8 (lane / 32) ...
@@ -122,6 +124,10 @@ __global__ __launch_bounds__(256) void attention_tiles_bf16(const bf16_t *__rest
             MP_WAIT_VMCNT(0);
         __syncthreads();
         const unsigned char *kt = &ring[tile & 1][0][0], *vt = &ring[tile & 1][1][0];
+        if (tile * kKeysPerTile > q0 + 31) {  // uniform over the wave: every key of the tile is masked for all its queries
+            __syncthreads();
+            continue;
+        }
 
         // S^T for 64 keys x 32 queries
         f32x16 s[2];
