@@ -390,6 +390,10 @@ int prune_mlp_gate_up(const void *x, const void *gate, const void *up, void *h, 
 int prune_rmsnorm(const void *x, const void *weight, void *y, int dtype, int64_t tokens, int64_t channels, int64_t ld_x,
                   int64_t ld_y, float eps, void *stream);
 
+/* out[t, j] = a[t, j] + b[t, j] (a residual connection); out may be a or b. */
+int prune_add(const void *a, const void *b, void *out, int dtype, int64_t rows, int64_t cols, int64_t ld_a, int64_t ld_b,
+              int64_t ld_out, void *stream);
+
 /*
  * Rotary position embedding, in place on x [tokens, heads * head_dim] (pitch ld): in every head, dimension
  * i < head_dim / 2 is paired with i + head_dim / 2 and the pair (a, b) becomes (a cos - b sin, b cos + a sin) with

@@ -22,6 +22,8 @@ Parity status:
   rotary             pinned (position 0 is the identity, norms preserved, relative-position property of the scores)
   causal_attention   pinned (brute-force loops, first token attends only to itself, uniform values give the mean,
                      grouped key / value heads equal repeated heads)
+  layer_forward      pinned (composition of the pinned pieces and of the feed-forward oracle; identity cases:
+                     zero o and down weights leave the residual stream unchanged)
 """
 from __future__ import annotations
 
@@ -66,3 +68,25 @@ def causal_attention(q, k, v) -> np.ndarray:
         p /= p.sum(axis=1, keepdims=True)
         out[:, h] = p @ v[:, g]
     return out
+
+
+def layer_forward(x, w, n_seqs: int, seq_len: int, heads: int, kv_heads: int, head_dim: int, eps: float = 1e-5,
+                  base: float = 10000.0):
+    """One layer on x [n_seqs * seq_len, hidden]; w maps names (attn_norm, q, k, v, o, mlp_norm, gate, up, down) to
+    weights.  Returns the four activation tensors the projections' statistics are taken from and the layer output."""
+    x = _f64(x)
+    tokens = n_seqs * seq_len
+    pos = np.tile(np.arange(seq_len), n_seqs)
+    attn_in = rmsnorm(x, w["attn_norm"], eps)
+    q = rotary((attn_in @ _f64(w["q"]).T).reshape(tokens, heads, head_dim), pos, base)
+    k = rotary((attn_in @ _f64(w["k"]).T).reshape(tokens, kv_heads, head_dim), pos, base)
+    v = (attn_in @ _f64(w["v"]).T).reshape(tokens, kv_heads, head_dim)
+    o_in = np.concatenate([causal_attention(q[b * seq_len:(b + 1) * seq_len], k[b * seq_len:(b + 1) * seq_len],
+                                            v[b * seq_len:(b + 1) * seq_len]) for b in range(n_seqs)])
+    o_in = o_in.reshape(tokens, heads * head_dim)
+    x1 = x + o_in @ _f64(w["o"]).T
+    mlp_in = rmsnorm(x1, w["mlp_norm"], eps)
+    a = mlp_in @ _f64(w["gate"]).T
+    down_in = a / (1.0 + np.exp(-a)) * (mlp_in @ _f64(w["up"]).T)
+    y = x1 + down_in @ _f64(w["down"]).T
+    return {"attn_in": attn_in, "o_in": o_in, "mlp_in": mlp_in, "down_in": down_in, "out": y}

@@ -39,6 +39,18 @@ __global__ __launch_bounds__(256) void rmsnorm_rows(const T *__restrict__ x, con
     }
 }
 
+// out[t, :] = a[t, :] + b[t, :] (the residual connections of the layer), fp32 sum rounded once
+template <typename T>
+__global__ __launch_bounds__(256) void add_rows(const T *__restrict__ a, const T *__restrict__ b, T *__restrict__ out,
+                                                int64_t rows, int64_t cols, int64_t ld_a, int64_t ld_b, int64_t ld_out) {
+    const int64_t n = rows * cols;
+    for (int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; e < n;
+         e += static_cast<int64_t>(gridDim.x) * 256) {
+        const int64_t r = e / cols, c = e - r * cols;
+        out[r * ld_out + c] = narrow_as<T>(widen(a[r * ld_a + c]) + widen(b[r * ld_b + c]));
+    }
+}
+
 // in place: dimension i < d/2 of every head is paired with i + d/2; the pair turns by position * base^(-2i/d)
 template <typename T>
 __global__ __launch_bounds__(256) void rotary_rows(T *__restrict__ x, int64_t tokens, int64_t heads, int64_t head_dim,
@@ -135,6 +147,24 @@ extern "C" int prune_rmsnorm(const void *x, const void *weight, void *y, int dty
     else
         hipLaunchKernelGGL(rmsnorm_rows<float>, dim3(blocks), dim3(256), 0, stream, static_cast<const float *>(x),
                            static_cast<const float *>(weight), static_cast<float *>(y), tokens, channels, ld_x, ld_y, eps);
+    return launch_status();
+}
+
+extern "C" int prune_add(const void *a, const void *b, void *out, int dtype, int64_t rows, int64_t cols, int64_t ld_a,
+                         int64_t ld_b, int64_t ld_out, void *stream_) {
+    using namespace mp;
+    if (!valid_dtype(dtype)) return PRUNE_ERR_DTYPE;
+    if (rows <= 0 || cols <= 0 || ld_a < cols || ld_b < cols || ld_out < cols) return PRUNE_ERR_SHAPE;
+    if (!a || !b || !out) return PRUNE_ERR_NULL;
+    const size_t es = elem_size(dtype);
+    if (!aligned_to(a, es) || !aligned_to(b, es) || !aligned_to(out, es)) return PRUNE_ERR_ALIGNMENT;
+    hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (dtype == PRUNE_BF16)
+        hipLaunchKernelGGL(add_rows<bf16_t>, dim3(8192), dim3(256), 0, stream, static_cast<const bf16_t *>(a),
+                           static_cast<const bf16_t *>(b), static_cast<bf16_t *>(out), rows, cols, ld_a, ld_b, ld_out);
+    else
+        hipLaunchKernelGGL(add_rows<float>, dim3(8192), dim3(256), 0, stream, static_cast<const float *>(a),
+                           static_cast<const float *>(b), static_cast<float *>(out), rows, cols, ld_a, ld_b, ld_out);
     return launch_status();
 }
 

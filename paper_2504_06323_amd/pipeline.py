@@ -248,3 +248,27 @@ def obs_prune_layer(st: LayerState, ob: ObsState, sparsities: Sequence[float], i
         done = torch.cuda.Event()
         done.record(side)
         main.wait_event(done)
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# Forward pass of one layer: the four activation tensors the projections' statistics are taken from come out of the
+# layer itself instead of being injected.
+
+def layer_forward(weights: Dict[str, torch.Tensor], norms: Dict[str, torch.Tensor], x: torch.Tensor, n_seqs: int,
+                  seq_len: int, heads: int, kv_heads: int, head_dim: int, eps: float = 1e-5, base: float = 10000.0,
+                  down_sumsq: Optional[torch.Tensor] = None) -> Dict[str, torch.Tensor]:
+    """x [n_seqs * seq_len, hidden] -> {"attn_in", "o_in", "mlp_in", "down_in", "out"}.
+
+    weights: the seven projections; norms: {"attn_norm", "mlp_norm"} weight vectors.  down_sumsq (fp32 [inter])
+    receives the channel sums of squares of down_in from the epilogue of the product that creates it."""
+    attn_in = prune.rmsnorm(x, norms["attn_norm"], eps)
+    q, k, v = (prune.linear(attn_in, weights[n]) for n in ("q", "k", "v"))
+    prune.rotary(q, heads, head_dim, seq_len, base)
+    prune.rotary(k, kv_heads, head_dim, seq_len, base)
+    o_in = prune.causal_attention(q, k, v, n_seqs, seq_len, heads, kv_heads, head_dim)
+    x1 = prune.add(x, prune.linear(o_in, weights["o"]))
+    mlp_in = prune.rmsnorm(x1, norms["mlp_norm"], eps)
+    down_in = prune.mlp_gate_up(mlp_in, weights["gate"], weights["up"], sumsq=down_sumsq)
+    out = prune.add(x1, prune.linear(down_in, weights["down"]))
+    return {"attn_in": attn_in, "o_in": o_in, "mlp_in": mlp_in, "down_in": down_in, "out": out,
+            "q": q, "k": k, "v": v, "x1": x1}

@@ -52,6 +52,7 @@ _SIGNATURES = {
     "prune_mlp_workspace_bytes": (_sz, [_i64, _i64]),
     "prune_mlp_gate_up": (_int, [_vp, _vp, _vp, _vp, _int, _i64, _i64, _i64, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "prune_rmsnorm": (_int, [_vp, _vp, _vp, _int, _i64, _i64, _i64, _i64, _f32, _vp]),
+    "prune_add": (_int, [_vp, _vp, _vp, _int, _i64, _i64, _i64, _i64, _i64, _vp]),
     "prune_rotary": (_int, [_vp, _int, _i64, _i64, _i64, _i64, _i64, _f32, _vp]),
     "prune_causal_attention": (_int, [_vp, _vp, _vp, _vp, _int, _i64, _i64, _i64, _i64, _i64, _i64, _i64, _i64, _i64, _vp]),
     "prune_plan_sparsity_device": (_int, [_vp, _vp, _vp, _int, _int, _f64, _f64, _int, _vp, _vp, _vp, _vp]),
@@ -473,6 +474,19 @@ def rmsnorm(x: torch.Tensor, weight: torch.Tensor, eps: float = 1e-5, y: Optiona
     _check("prune_rmsnorm", load().prune_rmsnorm(xp, _vector(weight, "weight", x.dtype, channels), yp, _dtype_code(x),
                                                  tokens, channels, ld_x, ld_y, float(eps), _stream(stream)))
     return y
+
+
+def add(a: torch.Tensor, b: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """out = a + b (prune_add)."""
+    ap, rows, cols, ld_a = _matrix(a, "a")
+    bp, rb, cb, ld_b = _matrix(b, "b")
+    if out is None:
+        out = torch.empty_like(a)
+    op, ro, co, ld_o = _matrix(out, "out")
+    if (rb, cb) != (rows, cols) or (ro, co) != (rows, cols) or len({a.dtype, b.dtype, out.dtype}) != 1:
+        raise ValueError("a, b and out must agree in shape and dtype")
+    _check("prune_add", load().prune_add(ap, bp, op, _dtype_code(a), rows, cols, ld_a, ld_b, ld_o, _stream(stream)))
+    return out
 
 
 def rotary(x: torch.Tensor, heads: int, head_dim: int, seq_len: int, base: float = 10000.0, stream=None) -> None:

@@ -85,3 +85,54 @@ def test_attention_matrix_core_kernel_vs_oracle(lib, case):
     b = prune.causal_attention(q, k, v, *case)
     _sync()
     assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("dtype,dims", [(torch.float32, (2, 96, 4, 2, 64, 256, 688)),       # the toy layer's widths: plain kernels
+                                        (torch.bfloat16, (2, 256, 4, 2, 128, 512, 1024))])  # matrix-core kernels throughout
+def test_layer_forward_stage_by_stage(lib, dtype, dims):
+    """pipeline.layer_forward against the oracle, stage by stage: every stage is checked on the previous stage's
+    stored output (so roundings to the storage type do not pile up in the comparison), and the fused statistic of
+    the down projection's input against the oracle's column sums of squares."""
+    from oracle import mlp_oracle as mlp
+    from oracle import mosaic_oracle as orc
+    from paper_2504_06323_amd import pipeline
+    n_seqs, seq_len, heads, kv_heads, d, hidden, inter = dims
+    tokens = n_seqs * seq_len
+    w = {"q": _mat(heads * d, hidden, dtype, 40, 0.05), "k": _mat(kv_heads * d, hidden, dtype, 41, 0.05),
+         "v": _mat(kv_heads * d, hidden, dtype, 42, 0.05), "o": _mat(hidden, heads * d, dtype, 43, 0.05),
+         "gate": _mat(inter, hidden, dtype, 44, 0.05), "up": _mat(inter, hidden, dtype, 45, 0.05),
+         "down": _mat(hidden, inter, dtype, 46, 0.05)}
+    norms = {"attn_norm": (1.0 + 0.1 * _mat(1, hidden, torch.float32, 47)).to(dtype).reshape(-1).contiguous(),
+             "mlp_norm": (1.0 + 0.1 * _mat(1, hidden, torch.float32, 48)).to(dtype).reshape(-1).contiguous()}
+    x = _mat(tokens, hidden, dtype, 49)
+    sumsq = torch.zeros(inter, dtype=torch.float32, device=DEV)
+    got = pipeline.layer_forward(w, norms, x, n_seqs, seq_len, heads, kv_heads, d, down_sumsq=sumsq)
+    _sync()
+    f = lambda t: to_np(t).astype(np.float64)
+    tol = 2.0 ** -7 if dtype == torch.bfloat16 else 2e-5
+
+    def check(name, want):
+        err = np.max(np.abs(f(got[name]) - want)) / np.max(np.abs(want))
+        assert err < tol, (name, err)
+
+    pos = np.tile(np.arange(seq_len), n_seqs)
+    check("attn_in", lay.rmsnorm(f(x), f(norms["attn_norm"])))
+    a = f(got["attn_in"])
+    check("q", lay.rotary((a @ f(w["q"]).T).reshape(tokens, heads, d), pos).reshape(tokens, -1))
+    check("k", lay.rotary((a @ f(w["k"]).T).reshape(tokens, kv_heads, d), pos).reshape(tokens, -1))
+    check("v", a @ f(w["v"]).T)
+    q3, k3, v3 = f(got["q"]).reshape(tokens, heads, d), f(got["k"]).reshape(tokens, kv_heads, d), f(got["v"]).reshape(tokens, kv_heads, d)
+    check("o_in", np.concatenate([lay.causal_attention(q3[b * seq_len:(b + 1) * seq_len], k3[b * seq_len:(b + 1) * seq_len],
+                                                       v3[b * seq_len:(b + 1) * seq_len]) for b in range(n_seqs)]).reshape(tokens, -1))
+    check("x1", f(x) + f(got["o_in"]) @ f(w["o"]).T)
+    check("mlp_in", lay.rmsnorm(f(got["x1"]), f(norms["mlp_norm"])))
+    check("down_in", mlp.mlp_hidden(f(got["mlp_in"]), f(w["gate"]), f(w["up"])))
+    check("out", f(got["x1"]) + f(got["down_in"]) @ f(w["down"]).T)
+    want_sq = orc.column_sumsq(f(got["down_in"]))
+    assert np.max(np.abs(to_np(sumsq) - want_sq) / np.maximum(want_sq, 1e-30)) < 1e-5
+    # and the whole layer at once against the oracle's own forward pass (roundings accumulate: looser)
+    whole = lay.layer_forward(f(x), {**{n: f(t) for n, t in w.items()}, **{n: f(t) for n, t in norms.items()}}, n_seqs,
+                              seq_len, heads, kv_heads, d)
+    for name in ("attn_in", "o_in", "mlp_in", "down_in", "out"):
+        err = np.max(np.abs(f(got[name]) - whole[name])) / np.max(np.abs(whole[name]))
+        assert err < 8 * tol, (name, err)

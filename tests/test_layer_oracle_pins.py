@@ -43,3 +43,28 @@ def test_causal_attention_brute_force_and_special_cases():
     flat = lay.causal_attention(np.zeros_like(q), k, v)                          # equal scores: the running mean of v
     assert np.allclose(flat[3, 0], v[:4, 0].mean(axis=0), rtol=1e-13)
     assert np.allclose(got, lay.causal_attention(q, np.repeat(k, 2, axis=1), np.repeat(v, 2, axis=1)), rtol=1e-14)
+
+
+def test_layer_forward_composition():
+    from oracle import mlp_oracle as mlp
+    rng = np.random.default_rng(3)
+    n_seqs, seq_len, heads, kv_heads, d, hidden, inter = 2, 5, 2, 1, 4, 8, 12
+    w = {"attn_norm": rng.standard_normal(hidden), "mlp_norm": rng.standard_normal(hidden),
+         "q": rng.standard_normal((heads * d, hidden)), "k": rng.standard_normal((kv_heads * d, hidden)),
+         "v": rng.standard_normal((kv_heads * d, hidden)), "o": rng.standard_normal((hidden, heads * d)),
+         "gate": rng.standard_normal((inter, hidden)), "up": rng.standard_normal((inter, hidden)),
+         "down": rng.standard_normal((hidden, inter))}
+    x = rng.standard_normal((n_seqs * seq_len, hidden))
+    out = lay.layer_forward(x, w, n_seqs, seq_len, heads, kv_heads, d)
+    assert np.allclose(out["attn_in"], lay.rmsnorm(x, w["attn_norm"]))
+    # the feed-forward part is the feed-forward oracle on the normalised residual stream
+    x1 = x + out["o_in"] @ w["o"].T
+    assert np.allclose(out["mlp_in"], lay.rmsnorm(x1, w["mlp_norm"]), rtol=1e-13)
+    assert np.allclose(out["down_in"], mlp.mlp_hidden(out["mlp_in"], w["gate"], w["up"]), rtol=1e-13)
+    assert np.allclose(out["out"], x1 + mlp.mlp_forward(out["mlp_in"], w["gate"], w["up"], w["down"]), rtol=1e-12)
+    # sequences do not see each other: the second sequence alone gives the same rows
+    alone = lay.layer_forward(x[seq_len:], w, 1, seq_len, heads, kv_heads, d)
+    assert np.allclose(alone["out"], out["out"][seq_len:], rtol=1e-12)
+    # with the o and down projections zeroed the residual stream passes through
+    w0 = dict(w, o=np.zeros_like(w["o"]), down=np.zeros_like(w["down"]))
+    assert np.allclose(lay.layer_forward(x, w0, n_seqs, seq_len, heads, kv_heads, d)["out"], x, rtol=1e-15)
