@@ -353,13 +353,88 @@ def run_mlp_stage(args):
     print(json.dumps(out), flush=True)
 
 
+def run_layer_stage(args):
+    """--stage layer: forward pass of one randomly initialised layer of the workload's shape on calibration
+    sequences (the activations of all seven projections come out of it), followed once, outside the timing, by
+    the headline ranking on those activations.  Prints its own JSON line."""
+    import torch
+    from paper_2504_06323_amd import pipeline, prune, synth
+
+    prune.load()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.workload]
+    shapes = synth.projection_shapes(cfg)
+    act_shapes = synth.activation_shapes(cfg)
+    weights = {n: synth.make_weight(cfg, 0, n, dev) for n, _, _, _ in shapes}
+    head_dim = 128
+    heads, kv_heads = cfg.q_out // head_dim, cfg.kv_out // head_dim
+    n_seqs = min(cfg.n_seqs, 32)
+    tokens = n_seqs * cfg.seq_len
+    x = synth.make_activation(cfg, 0, "attn_in", dev, n_seqs=n_seqs)          # the layer's input (residual stream)
+    norms = {n: torch.ones(cfg.hidden, dtype=x.dtype, device=dev) for n in ("attn_norm", "mlp_norm")}
+    sumsq = torch.zeros(cfg.inter, dtype=torch.float32, device=dev)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    spans = []
+
+    def step(record):
+        e0, e1 = ev(), ev()
+        e0.record()
+        out = pipeline.layer_forward(weights, norms, x, n_seqs, cfg.seq_len, heads, kv_heads, head_dim, down_sumsq=sumsq)
+        e1.record()
+        if record:
+            spans.append((e0, e1))
+        return out
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        acts_out = step(True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms = sum(a.elapsed_time(b) for a, b in spans) / len(spans)
+    proj_flops = 2.0 * tokens * sum(rw * c for _, rw, c, _ in shapes)
+    attn_flops = 4.0 * cfg.seq_len * cfg.seq_len * head_dim * heads * n_seqs / 2
+    # the headline ranking on the activations that came out of the forward pass
+    st = pipeline.LayerState.create(weights, {n: a for n, _, _, a in shapes}, act_shapes, tokens)
+    pipeline.rank_layer(st, {a: acts_out[a] for a in act_shapes}, cfg.alpha)
+    counts = st.count.tolist()
+    out = {"metric": "forward pass of one layer on calibration sequences (tokens/s); its activations feed the ranking",
+           "value": tokens / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(1e3 * elapsed / args.steps, 3), "higher_is_better": True, "scaling": "weak",
+           "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+           "config": {"workload": f"{cfg.name}: hidden {cfg.hidden}, {heads} query / {kv_heads} key-value heads of "
+                                  f"{head_dim}, intermediate {cfg.inter}, {n_seqs} sequences of {cfg.seq_len} tokens, "
+                                  f"random weights, unit norm weights; outlier counts on the real activations {counts}"},
+           "tflops": round((proj_flops + attn_flops) / (ms * 1e-3) / 1e12, 1),
+           "roofline": {"bound": "mfma", "kernel": "whole layer (seven projections and causal attention)",
+                        "achieved": round((proj_flops + attn_flops) / (ms * 1e-3) / 1e12, 1), "peak": 2500.0,
+                        "unit": "TFLOP/s", "frac": round((proj_flops + attn_flops) / (ms * 1e-3) / 1e12 / 2500.0, 4),
+                        "traffic": None, "avg_launch_ms": round(ms, 3), "launches": len(spans)}}
+    if not args.no_cpu_baseline:
+        from oracle import layer_oracle as lay
+        rows = 256
+        host = lambda t: t.detach().cpu().to(torch.float32).numpy()
+        w64 = {**{n: host(t) for n, t in weights.items()}, **{n: host(t) for n, t in norms.items()}}
+        t0 = time.perf_counter()
+        lay.layer_forward(host(x[:rows]), w64, 1, rows, heads, kv_heads, head_dim)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": rows / dt, "unit": "tokens/s", "cores": len(os.sched_getaffinity(0)),
+                               "kind": "oracle", "sample": f"one sequence of {rows} tokens, NumPy float64, {dt:.1f} s"}
+    log(f"layer stage: forward {ms:.2f} ms for {tokens} tokens ({(proj_flops + attn_flops) / (ms * 1e-3) / 1e12:.0f} TFLOP/s)")
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
-    ap.add_argument("--stage", default="prune", choices=["prune", "hessian", "obs", "mlp"],
+    ap.add_argument("--stage", default="prune", choices=["prune", "hessian", "obs", "mlp", "layer"],
                     help="prune (default): the scoring / masking / structured path the headline metric is quoted on; "
                          "hessian: the matrix-core stage of the Hessian-based pruner, its own JSON line; "
                          "obs: the whole Hessian-based path of one layer, its own JSON line; "
-                         "mlp: forward pass of the feed-forward block, full and pruned, its own JSON line")
+                         "mlp: forward pass of the feed-forward block, full and pruned, its own JSON line; "
+                         "layer: forward pass of a whole layer, its own JSON line")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
@@ -385,6 +460,9 @@ def main():
         return
     if args.stage == "mlp":
         run_mlp_stage(args)
+        return
+    if args.stage == "layer":
+        run_layer_stage(args)
         return
 
     import torch
