@@ -39,6 +39,43 @@ __global__ __launch_bounds__(256) void rmsnorm_rows(const T *__restrict__ x, con
     }
 }
 
+// the same with 16-byte accesses (8-element packets; channels and pitches multiples of 8, 16-byte aligned bases);
+// the row is read twice, the second time from cache
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_rows_vec(const T *__restrict__ x, const T *__restrict__ weight,
+                                                        T *__restrict__ y, int64_t tokens, int64_t channels,
+                                                        int64_t ld_x, int64_t ld_y, float eps) {
+    const int lane = threadIdx.x & 63;
+    for (int64_t t = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6); t < tokens;
+         t += static_cast<int64_t>(gridDim.x) * 4) {
+        const T *row = x + t * ld_x;
+        float s = 0.f;
+        for (int64_t j = lane * 8; j < channels; j += 512) {
+            Packet<T, 8> pk;
+            pk.load(row + j);
+            float v[8];
+            pk.to_float(v);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s = fmaf(v[e], v[e], s);
+        }
+        s = wave_sum(s);
+        s = __shfl(s, 0);
+        const float scale = 1.f / sqrtf(s / static_cast<float>(channels) + eps);
+        for (int64_t j = lane * 8; j < channels; j += 512) {
+            Packet<T, 8> pk, pw;
+            pk.load(row + j);
+            pw.load(weight + j);
+            float v[8], wv[8];
+            pk.to_float(v);
+            pw.to_float(wv);
+            T out[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) out[e] = narrow_as<T>(v[e] * scale * wv[e]);
+            *reinterpret_cast<Packet<T, 8> *>(y + t * ld_y + j) = *reinterpret_cast<const Packet<T, 8> *>(out);
+        }
+    }
+}
+
 // out[t, :] = a[t, :] + b[t, :] (the residual connections of the layer), fp32 sum rounded once
 template <typename T>
 __global__ __launch_bounds__(256) void add_rows(const T *__restrict__ a, const T *__restrict__ b, T *__restrict__ out,
@@ -48,6 +85,63 @@ __global__ __launch_bounds__(256) void add_rows(const T *__restrict__ a, const T
          e += static_cast<int64_t>(gridDim.x) * 256) {
         const int64_t r = e / cols, c = e - r * cols;
         out[r * ld_out + c] = narrow_as<T>(widen(a[r * ld_a + c]) + widen(b[r * ld_b + c]));
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void add_rows_vec(const T *__restrict__ a, const T *__restrict__ b, T *__restrict__ out,
+                                                    int64_t rows, int64_t cols, int64_t ld_a, int64_t ld_b,
+                                                    int64_t ld_out) {
+    const int64_t per_row = cols / 8, n = rows * per_row;
+    for (int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; e < n;
+         e += static_cast<int64_t>(gridDim.x) * 256) {
+        const int64_t r = e / per_row, c = (e - r * per_row) * 8;
+        Packet<T, 8> pa, pb;
+        pa.load(a + r * ld_a + c);
+        pb.load(b + r * ld_b + c);
+        float va[8], vb[8];
+        pa.to_float(va);
+        pb.to_float(vb);
+        T o[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] = narrow_as<T>(va[i] + vb[i]);
+        *reinterpret_cast<Packet<T, 8> *>(out + r * ld_out + c) = *reinterpret_cast<const Packet<T, 8> *>(o);
+    }
+}
+
+// Rotary embedding with 16-byte accesses: a thread takes 8 consecutive dimensions i of one token, computes their
+// angles once and turns those dimensions (and their partners i + d/2) in every head of the token.
+template <typename T>
+__global__ __launch_bounds__(256) void rotary_rows_vec(T *__restrict__ x, int64_t tokens, int64_t heads, int64_t head_dim,
+                                                       int64_t ld, int64_t seq_len, float log2_base) {
+    const int64_t half = head_dim / 2, per_token = half / 8, n = tokens * per_token;
+    for (int64_t e = static_cast<int64_t>(blockIdx.x) * 256 + threadIdx.x; e < n;
+         e += static_cast<int64_t>(gridDim.x) * 256) {
+        const int64_t t = e / per_token, i0 = (e - t * per_token) * 8;
+        const float pos = static_cast<float>(t % seq_len);
+        float sn[8], cs[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float inv = exp2f(-2.f * static_cast<float>(i0 + i) / static_cast<float>(head_dim) * log2_base);
+            sincosf(pos * inv, &sn[i], &cs[i]);
+        }
+        for (int64_t h = 0; h < heads; ++h) {
+            T *p = x + t * ld + h * head_dim + i0;
+            Packet<T, 8> pa, pb;
+            pa.load(p);
+            pb.load(p + half);
+            float a[8], b[8];
+            pa.to_float(a);
+            pb.to_float(b);
+            T oa[8], ob[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                oa[i] = narrow_as<T>(a[i] * cs[i] - b[i] * sn[i]);
+                ob[i] = narrow_as<T>(b[i] * cs[i] + a[i] * sn[i]);
+            }
+            *reinterpret_cast<Packet<T, 8> *>(p) = *reinterpret_cast<const Packet<T, 8> *>(oa);
+            *reinterpret_cast<Packet<T, 8> *>(p + half) = *reinterpret_cast<const Packet<T, 8> *>(ob);
+        }
     }
 }
 
@@ -141,6 +235,17 @@ extern "C" int prune_rmsnorm(const void *x, const void *weight, void *y, int dty
     if (!aligned_to(x, es) || !aligned_to(weight, es) || !aligned_to(y, es)) return PRUNE_ERR_ALIGNMENT;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const unsigned blocks = static_cast<unsigned>(ceil_div(tokens, 4) < 16384 ? ceil_div(tokens, 4) : 16384);
+    if (packet_ok(x, channels, ld_x) && packet_ok(y, channels, ld_y) && aligned_to(weight, 16)) {
+        if (dtype == PRUNE_BF16)
+            hipLaunchKernelGGL(rmsnorm_rows_vec<bf16_t>, dim3(blocks), dim3(256), 0, stream, static_cast<const bf16_t *>(x),
+                               static_cast<const bf16_t *>(weight), static_cast<bf16_t *>(y), tokens, channels, ld_x, ld_y,
+                               eps);
+        else
+            hipLaunchKernelGGL(rmsnorm_rows_vec<float>, dim3(blocks), dim3(256), 0, stream, static_cast<const float *>(x),
+                               static_cast<const float *>(weight), static_cast<float *>(y), tokens, channels, ld_x, ld_y,
+                               eps);
+        return launch_status();
+    }
     if (dtype == PRUNE_BF16)
         hipLaunchKernelGGL(rmsnorm_rows<bf16_t>, dim3(blocks), dim3(256), 0, stream, static_cast<const bf16_t *>(x),
                            static_cast<const bf16_t *>(weight), static_cast<bf16_t *>(y), tokens, channels, ld_x, ld_y, eps);
@@ -159,6 +264,15 @@ extern "C" int prune_add(const void *a, const void *b, void *out, int dtype, int
     const size_t es = elem_size(dtype);
     if (!aligned_to(a, es) || !aligned_to(b, es) || !aligned_to(out, es)) return PRUNE_ERR_ALIGNMENT;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
+    if (packet_ok(a, cols, ld_a) && packet_ok(b, cols, ld_b) && packet_ok(out, cols, ld_out)) {
+        if (dtype == PRUNE_BF16)
+            hipLaunchKernelGGL(add_rows_vec<bf16_t>, dim3(8192), dim3(256), 0, stream, static_cast<const bf16_t *>(a),
+                               static_cast<const bf16_t *>(b), static_cast<bf16_t *>(out), rows, cols, ld_a, ld_b, ld_out);
+        else
+            hipLaunchKernelGGL(add_rows_vec<float>, dim3(8192), dim3(256), 0, stream, static_cast<const float *>(a),
+                               static_cast<const float *>(b), static_cast<float *>(out), rows, cols, ld_a, ld_b, ld_out);
+        return launch_status();
+    }
     if (dtype == PRUNE_BF16)
         hipLaunchKernelGGL(add_rows<bf16_t>, dim3(8192), dim3(256), 0, stream, static_cast<const bf16_t *>(a),
                            static_cast<const bf16_t *>(b), static_cast<bf16_t *>(out), rows, cols, ld_a, ld_b, ld_out);
@@ -179,6 +293,15 @@ extern "C" int prune_rotary(void *x, int dtype, int64_t tokens, int64_t heads, i
     if (!aligned_to(x, elem_size(dtype))) return PRUNE_ERR_ALIGNMENT;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     const float log2_base = log2f(base);
+    if (head_dim % 16 == 0 && ld % 8 == 0 && aligned_to(x, 16)) {
+        if (dtype == PRUNE_BF16)
+            hipLaunchKernelGGL(rotary_rows_vec<bf16_t>, dim3(4096), dim3(256), 0, stream, static_cast<bf16_t *>(x), tokens,
+                               heads, head_dim, ld, seq_len, log2_base);
+        else
+            hipLaunchKernelGGL(rotary_rows_vec<float>, dim3(4096), dim3(256), 0, stream, static_cast<float *>(x), tokens,
+                               heads, head_dim, ld, seq_len, log2_base);
+        return launch_status();
+    }
     if (dtype == PRUNE_BF16)
         hipLaunchKernelGGL(rotary_rows<bf16_t>, dim3(4096), dim3(256), 0, stream, static_cast<bf16_t *>(x), tokens, heads,
                            head_dim, ld, seq_len, log2_base);
