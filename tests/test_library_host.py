@@ -176,6 +176,25 @@ def test_error_paths_return_before_any_launch(lib):
     assert gu(fake, fake, fake, fake, 1, 256, 32, 128, 32, 32, 128, fake, None, 0, None) == E["null"]   # statistic wanted, no workspace
     assert gu(fake, fake, fake, fake, 1, 256, 32, 128, 32, 32, 128, fake, fake, 16, None) == E["ws"]
     assert lib.prune_mlp_workspace_bytes(16384, 11008) >= 2 * 64 * 11008 * 4
+    F = ctypes.c_float
+    rn = lib.prune_rmsnorm
+    assert rn(fake, fake, fake, 5, 8, 8, 8, 8, F(1e-5), None) == E["dtype"]
+    assert rn(fake, fake, fake, 1, 8, 8, 4, 8, F(1e-5), None) == E["shape"]
+    assert rn(fake, None, fake, 1, 8, 8, 8, 8, F(1e-5), None) == E["null"]
+    assert rn(fake, fake, fake, 1, 8, 8, 8, 8, F(-1.0), None) == E["rng"]
+    ro = lib.prune_rotary
+    assert ro(fake, 1, 8, 2, 7, 14, 8, F(10000.0), None) == E["shape"]                 # odd head width
+    assert ro(fake, 1, 8, 2, 8, 8, 8, F(10000.0), None) == E["shape"]                  # pitch < heads * head_dim
+    assert ro(None, 1, 8, 2, 8, 16, 8, F(10000.0), None) == E["null"]
+    assert ro(fake, 1, 8, 2, 8, 16, 8, F(1.0), None) == E["rng"]
+    at = lib.prune_causal_attention
+    assert at(fake, fake, fake, fake, 1, 1, 8, 3, 2, 8, 24, 16, 16, 24, None) == E["shape"]   # heads not a multiple of kv heads
+    assert at(fake, fake, fake, fake, 1, 1, 8, 2, 1, 512, 1024, 512, 512, 1024, None) == E["shape"]   # head too wide
+    assert at(fake, fake, None, fake, 1, 1, 8, 2, 1, 8, 16, 8, 8, 16, None) == E["null"]
+    assert at(odd, fake, fake, fake, 1, 1, 8, 2, 1, 8, 16, 8, 8, 16, None) == E["align"]
+    ad = lib.prune_add
+    assert ad(fake, fake, fake, 1, 8, 8, 8, 4, 8, None) == E["shape"]
+    assert ad(fake, None, fake, 1, 8, 8, 8, 8, 8, None) == E["null"]
     st = lib.prune_struct_compact
     assert st(fake, fake, fake, 1, 8, 8, 8, fake, fake, None, None, None, fake, 1 << 20, None) == E["rng"]  # r >= inter
     assert st(fake, fake, fake, 1, 8, 8, 1, fake, fake, fake, None, None, fake, 1 << 20, None) == E["null"]  # 1 of 3 outs
