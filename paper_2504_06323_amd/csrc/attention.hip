@@ -116,18 +116,11 @@ __global__ __launch_bounds__(256) void attention_tiles_bf16(const bf16_t *__rest
 
     issue(0);
     for (int tile = 0; tile < n_tiles; ++tile) {
-        const bool more = tile + 1 < n_tiles;
-        if (more) issue(tile + 1);  // its buffer was released by the barrier that ended the previous trip
-        if (more)
-            MP_WAIT_VMCNT(8);
-        else
-            MP_WAIT_VMCNT(0);
-        __syncthreads();
+        MP_WAIT_VMCNT(0);  // this thread's loads of the tile have landed
+        __syncthreads();   // ... and everyone's; and every wave is done with the previous tile,
+        if (tile + 1 < n_tiles) issue(tile + 1);  // whose buffer takes the next one while this one is worked on
         const unsigned char *kt = &ring[tile & 1][0][0], *vt = &ring[tile & 1][1][0];
-        if (tile * kKeysPerTile > q0 + 31) {  // uniform over the wave: every key of the tile is masked for all its queries
-            __syncthreads();
-            continue;
-        }
+        if (tile * kKeysPerTile > q0 + 31) continue;  // uniform over the wave: every key is masked for all its queries
 
         // S^T for 64 keys x 32 queries
         f32x16 s[2];
@@ -182,8 +175,8 @@ __global__ __launch_bounds__(256) void attention_tiles_bf16(const bf16_t *__rest
             for (int dt = 0; dt < 4; ++dt)
                 acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_operand(vt, row_base, 32 * dt, lane), pb, acc_o[dt], 0, 0, 0);
         }
-        __syncthreads();  // every wave is done with this stage before the next trip loads into it
     }
+    __syncthreads();  // the tiles are dead: their memory stages the output
 
     // o[query][d] = O^T[d][query] / sum; staged through LDS so that a query's 256 bytes leave in 16-byte pieces
     const float inv = 1.f / (l_run + __shfl_xor(l_run, 32));
