@@ -61,12 +61,11 @@ def _attention_case(dtype, n_seqs, seq_len, heads, kv_heads, d, seed):
     return worst, float(np.max(np.abs(v64)))
 
 
-@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
-@pytest.mark.parametrize("case", [(2, 100, 4, 2, 64), (1, 70, 3, 3, 40), (2, 64, 2, 1, 128)])
+@pytest.mark.parametrize("dtype,case", [(torch.bfloat16, (2, 100, 4, 2, 64)), (torch.float32, (2, 100, 4, 2, 64)),
+                                        (torch.bfloat16, (1, 70, 3, 3, 40)), (torch.float32, (1, 70, 3, 3, 40)),
+                                        (torch.float32, (2, 64, 2, 1, 128))])
 def test_attention_plain_kernel_vs_oracle(lib, dtype, case):
     """Shapes that take the any-shape kernel (fp32, or heads that are not 128 wide)."""
-    if dtype == torch.bfloat16 and case[4] == 128:
-        pytest.skip("bf16 heads of width 128 take the matrix-core kernel, tested below")
     worst, vmax = _attention_case(dtype, *case, seed=10)
     assert worst <= (ULP[dtype] + 2e-5) * vmax * 4
 
