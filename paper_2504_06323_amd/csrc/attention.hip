@@ -132,31 +132,42 @@ __global__ __launch_bounds__(256) void attention_tiles_bf16(const bf16_t *__rest
             for (int kk = 0; kk < 8; ++kk)
                 s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_operand(kt, 32 * mt, kk, lane), qreg[kk], s[mt], 0, 0, 0);
         }
-        // scale, causal mask (only the tiles that reach past this wave's first query need it), running maximum
-        const int key0 = tile * kKeysPerTile + 4 * (lane >> 5);
-        const bool on_diagonal = tile * kKeysPerTile + kKeysPerTile - 1 > q0;
+        // scale, causal mask (only the tiles that reach past this wave's first query need it: a uniform branch),
+        // running maximum
         float m_new = m_run;
+        if (tile * kKeysPerTile + kKeysPerTile - 1 > q0) {
+            const int key0 = tile * kKeysPerTile + 4 * (lane >> 5);
 #pragma unroll
-        for (int mt = 0; mt < 2; ++mt)
+            for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                float x = s[mt][e] * scale_log2e;
-                if (on_diagonal) {
+                for (int e = 0; e < 16; ++e) {
                     const int key = key0 + 32 * mt + 8 * (e >> 2) + (e & 3);
-                    x = key > my_query ? -INFINITY : x;
+                    const float x = key > my_query ? -INFINITY : s[mt][e] * scale_log2e;
+                    s[mt][e] = x;
+                    m_new = fmaxf(m_new, x);
                 }
-                s[mt][e] = x;
-                m_new = fmaxf(m_new, x);
-            }
+        } else {
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    s[mt][e] *= scale_log2e;
+                    m_new = fmaxf(m_new, s[mt][e]);
+                }
+        }
         m_new = fmaxf(m_new, __shfl_xor(m_new, 32));  // the other half of the keys of this query
         // (m_new is finite: key 0 is visible to every query, and tile 0 is processed first)
-        const float fix = exp2f(m_run - m_new);
-        m_run = m_new;
-        l_run *= fix;
+        // The accumulated output is rescaled only when some query's maximum grew, which after the first few tiles
+        // is rare: the multiply would otherwise cost more vector instructions than the softmax itself.
+        if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0ull) {
+            const float fix = __builtin_amdgcn_exp2f(m_run - m_new);
+            m_run = m_new;
+            l_run *= fix;
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
+            for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc_o[dt][e] *= fix;
+                for (int e = 0; e < 16; ++e) acc_o[dt][e] *= fix;
+        }
         // probabilities, and O^T += V^T P^T sixteen keys at a time
 #pragma unroll
         for (int step = 0; step < 4; ++step) {
@@ -164,7 +175,7 @@ __global__ __launch_bounds__(256) void attention_tiles_bf16(const bf16_t *__rest
             float p[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                p[i] = exp2f(s[mt][e0 + i] - m_new);
+                p[i] = __builtin_amdgcn_exp2f(s[mt][e0 + i] - m_new);  // the bare instruction: no denormal care needed
                 l_run += p[i];
             }
             const u32x4 packed = {pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]),
