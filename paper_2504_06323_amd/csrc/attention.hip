@@ -29,38 +29,50 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     return r;
 }
 
-// A operand of S^T = K Q^T: keys row_base + lane % 32, the 8 head dimensions 16 kk + 8 (lane / 32) ...
-// K tile rows are 256 bytes (16 packets); packet c of row r sits at position c ^ (r % 16)
-__device__ __forceinline__ bf16x8 k_operand(const unsigned char *tile, int row_base, int kk, int lane) {
-    const int row = row_base + (lane & 31);
-    const int chunk = 2 * kk + (lane >> 5);
-    const u32x4 v = *reinterpret_cast<const u32x4 *>(tile + row * 256 + ((chunk ^ (row & 15)) << 4));
-    return __builtin_bit_cast(bf16x8, v);
+typedef __attribute__((address_space(3))) unsigned char lds_byte;
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+
+// A operand of S^T = K Q^T: keys 32 mt + lane % 32, the 8 head dimensions 16 kk + 8 (lane / 32) ...  K tile rows are
+// 256 bytes (16 packets); packet c of row r sits at position c ^ (r % 16).  The lane's byte offset for (mt = 0, kk);
+// other mt are a constant 8192 bytes further (32 rows, and r % 16 does not change).
+__device__ __forceinline__ uint32_t k_operand_offset(int kk, int lane) {
+    const int row = lane & 31, chunk = 2 * kk + (lane >> 5);
+    return static_cast<uint32_t>(row * 256 + ((chunk ^ (row & 15)) << 4));
 }
 
-// A operand of O^T = V^T P^T: head dimension col_base + lane % 32, and for the lane's half h = lane / 32 the keys
-// row_base + 4 h + {0, 1, 2, 3} and row_base + 8 + 4 h + {0, 1, 2, 3}: the keys whose probabilities sit in
-// accumulator elements v0 .. v0 + 7 of that half.  V tile rows are 256 bytes; packet c of row r at c ^ (4 (r % 4)).
-__device__ __forceinline__ bf16x8 v_operand(const unsigned char *tile, int row_base, int col_base, int lane) {
+// A operand of O^T = V^T P^T: head dimension 32 dt + lane % 32, and for the lane's half h = lane / 32 the keys
+// row_base + 4 h + {0, 1, 2, 3} (first read) and + 8 (second read): the keys whose probabilities sit in accumulator
+// elements v0 .. v0 + 7 of that half.  V tile rows are 256 bytes; packet c of row r at c ^ (4 (r % 4)).  The lane's
+// byte offset of the first read for (row_base = 0, dt); row_base (a multiple of 8) adds 256 row_base bytes.
+__device__ __forceinline__ uint32_t v_operand_offset(int dt, int lane) {
     const int s = lane & 15, g = lane >> 4;
-    const int row = row_base + 4 * (g >> 1) + (s >> 2);
-    const int col = col_base + 16 * (g & 1) + 4 * (s & 3);
-    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-    const unsigned char *p0 = tile + row * 256 + ((((col >> 3) ^ (4 * (row & 3)))) << 4) + (col & 4) * 2;
-    const int row1 = row + 8;
-    const unsigned char *p1 = tile + row1 * 256 + ((((col >> 3) ^ (4 * (row1 & 3)))) << 4) + (col & 4) * 2;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p0);
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)p1);
+    const int row = 4 * (g >> 1) + (s >> 2);
+    const int col = 32 * dt + 16 * (g & 1) + 4 * (s & 3);
+    return static_cast<uint32_t>(row * 256 + ((((col >> 3) ^ (4 * (row & 3)))) << 4) + (col & 4) * 2);
+}
+
+__device__ __forceinline__ bf16x8 read_k_operand(lds_byte *at) {
+    return __builtin_bit_cast(bf16x8, *reinterpret_cast<lds_u32x4 *>(at));
+}
+
+__device__ __forceinline__ bf16x8 read_v_operand(lds_byte *at) {
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_s16x4 *>(at));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_s16x4 *>(at + 8 * 256));
     const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
     return __builtin_bit_cast(bf16x8, both);
 }
 
-__global__ __launch_bounds__(256) void attention_tiles_bf16(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
+template <int V>
+struct Const {
+    static constexpr int value = V;
+};
+
+__global__ __launch_bounds__(256, 2) void attention_tiles_bf16(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
                                                             const bf16_t *__restrict__ v, bf16_t *__restrict__ o,
                                                             int seq_len, int heads, int kv_heads, int64_t ld_q,
                                                             int64_t ld_k, int64_t ld_v, int64_t ld_o, float scale_log2e) {
     __shared__ __attribute__((aligned(1024))) unsigned char ring[2][2][kTileBytes];  // [stage][K, V]
-    typedef __attribute__((address_space(3))) unsigned char lds_byte;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int q_tiles = (seq_len + kQueriesPerBlock - 1) / kQueriesPerBlock;
     // the blocks with the most keys go first
@@ -114,23 +126,33 @@ __global__ __launch_bounds__(256) void attention_tiles_bf16(const bf16_t *__rest
         for (int e = 0; e < 16; ++e) acc_o[dt][e] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;  // running maximum (in units of log2) and this lane's share of the sum
 
-    issue(0);
-    for (int tile = 0; tile < n_tiles; ++tile) {
+    // every LDS address below is a per-lane offset computed once plus a compile-time constant (the stage, the row
+    // base): two trips of the loop are written out so that the stage is one
+    lds_byte *const lds0 = (lds_byte *)&ring[0][0][0];
+    uint32_t k_off[8], v_off[4];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) k_off[kk] = k_operand_offset(kk, lane);
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt) v_off[dt] = v_operand_offset(dt, lane);
+    f32x16 zero16;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) zero16[e] = 0.f;
+
+    auto one_tile = [&](int tile, auto stage_c) {
+        constexpr int kStage = decltype(stage_c)::value * 2 * kTileBytes;
         MP_WAIT_VMCNT(0);  // this thread's loads of the tile have landed
         __syncthreads();   // ... and everyone's; and every wave is done with the previous tile,
         if (tile + 1 < n_tiles) issue(tile + 1);  // whose buffer takes the next one while this one is worked on
-        const unsigned char *kt = &ring[tile & 1][0][0], *vt = &ring[tile & 1][1][0];
-        if (tile * kKeysPerTile > q0 + 31) continue;  // uniform over the wave: every key is masked for all its queries
+        if (tile * kKeysPerTile > q0 + 31) return;  // uniform over the wave: every key is masked for all its queries
 
         // S^T for 64 keys x 32 queries
         f32x16 s[2];
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) s[mt][e] = 0.f;
-#pragma unroll
             for (int kk = 0; kk < 8; ++kk)
-                s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_operand(kt, 32 * mt, kk, lane), qreg[kk], s[mt], 0, 0, 0);
+                s[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(read_k_operand(lds0 + k_off[kk] + (kStage + 8192 * mt)),
+                                                                qreg[kk], kk == 0 ? zero16 : s[mt], 0, 0, 0);
         }
         // scale, causal mask (only the tiles that reach past this wave's first query need it: a uniform branch),
         // running maximum
@@ -184,8 +206,14 @@ __global__ __launch_bounds__(256) void attention_tiles_bf16(const bf16_t *__rest
             const int row_base = 32 * mt + 16 * (step & 1);
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
-                acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_operand(vt, row_base, 32 * dt, lane), pb, acc_o[dt], 0, 0, 0);
+                acc_o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    read_v_operand(lds0 + v_off[dt] + (kStage + kTileBytes + 256 * row_base)), pb, acc_o[dt], 0, 0, 0);
         }
+    };
+    issue(0);
+    for (int tile = 0; tile < n_tiles; tile += 2) {
+        one_tile(tile, Const<0>{});
+        if (tile + 1 < n_tiles) one_tile(tile + 1, Const<1>{});
     }
     __syncthreads();  // the tiles are dead: their memory stages the output
 
