@@ -71,7 +71,7 @@ def test_attention_plain_kernel_vs_oracle(lib, dtype, case):
 
 
 @pytest.mark.parametrize("case", [(2, 256, 4, 2, 128), (1, 384, 2, 2, 128), (3, 200, 4, 1, 128), (1, 128, 1, 1, 128),
-                                  (2, 2048, 2, 1, 128)])
+                                  (2, 2048, 2, 1, 128), (3, 1024, 8, 2, 128), (1, 1000, 4, 4, 128)])
 def test_attention_matrix_core_kernel_vs_oracle(lib, case):
     """bf16, 128-wide heads.  Probabilities enter the second product as bf16 (half an ulp each, averaging out over
     the keys of a query) and the output is rounded to bf16."""
