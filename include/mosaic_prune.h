@@ -288,10 +288,9 @@ int prune_struct_groups(const void *const *row_mats, const int64_t *row_per, con
                         void *const *row_outs, void *const *col_outs, void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------------------------------
- * The Hessian-based one-shot pruner that the paper's experiments run with the planner's targets
- * (Section 4.1.3 "Pruning Methods": the lowest-ranking parameters are pruned "using the inverse
- * Hessian matrix and a subsequent weight update"; Section 4.1.4 "Calibration": the same 128 samples
- * give the Hessian).  Built in stages; each stage is an entry point of its own.
+ * The Hessian-based one-shot pruner with weight compensation that the paper's experiments run with
+ * the planner's targets (Section 4.1.3, "Pruning Methods"; Section 4.1.4, "Calibration": the same
+ * 128 samples give the Hessian).  Built in stages; each stage is an entry point of its own.
  * ------------------------------------------------------------------------------------------------ */
 
 /*
@@ -334,8 +333,11 @@ int prune_hessian_factor(float *h, int64_t n, int64_t ld_h, double damp, uint8_t
  *   r: DEVICE fp32, the factor left by prune_hessian_factor in the upper triangle of [cols, cols], pitch ld_r.
  *   dead: DEVICE uint8 [cols], nullable: columns whose weights count as zero (from prune_hessian_factor).
  *   first_block, n_blocks: the range of 128-column blocks to process in this call (n_blocks < 0: all the rest).
- *     A projection may be swept in several calls, in order, starting at block 0, as long as v (or, when v is
- *     NULL, the workspace) is left untouched in between.
+ *     A projection may be swept in several calls, in order, starting at block 0.  Between the calls v (or, when v
+ *     is NULL, the workspace, which then holds it) must be left untouched.  The workspace also holds the changes
+ *     of the current group of four blocks: a call with first_block % 4 != 0 continues such a group and must be
+ *     given the workspace of the previous call, untouched; a call that starts a group (first_block % 4 == 0) with
+ *     a caller-owned v may be given any workspace.
  *   v: DEVICE fp32 [rows, cols] contiguous, nullable: the working matrix G.  For every column j not yet processed
  *     it holds sum over the finished columns i of (w[:, i] - w_out[:, i]) * R[i, j]; zeroed by the call that
  *     processes block 0.  Given by callers that sweep in several calls and want the state in a buffer of their own.

@@ -1,5 +1,5 @@
-// Factor of the damped Hessian for the one-shot pruner (Section 4.1.3, "Pruning Methods": pruning
-// "using the inverse Hessian matrix").  The published algorithm works with U, the upper Cholesky factor of
+// Factor of the damped Hessian for the Hessian-based one-shot pruner (Section 4.1.3, "Pruning
+// Methods").  The published algorithm works with U, the upper Cholesky factor of
 // H^-1 (H^-1 = U^T U).  Its inverse R = U^-1 is upper triangular too and satisfies H = R R^T, so it is a
 // Cholesky factorisation of H taken from the last row and column upwards -- one factorisation, no explicit
 // inverse of the n x n matrix -- and the sweep can be written in terms of R (see sweep.hip).

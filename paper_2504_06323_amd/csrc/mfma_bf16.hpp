@@ -16,8 +16,13 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 // later LDS read with a wait for all such loads in flight (it cannot tell the ring's stages apart), which undoes
 // the prefetch; the waits are placed by hand below.
 __device__ __forceinline__ void load_to_lds(const void *src, uint32_t lds_addr) {
-    // (one wait state between the scalar write of M0 and the load that reads it)
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(src) : "memory");
+    // (one wait state between the scalar write of M0 and the load that reads it).  M0 is declared as written:
+    // the compiler keeps values of its own there (the index of a dynamically indexed register array, the
+    // operand of its own LDS-DMA and message instructions) and must not assume they survive this statement.
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_addr), "v"(src)
+                 : "memory", "m0");
 }
 
 // s_waitcnt with only the vector-memory counter set (6 bits: [3:0] and [15:14]); the others left at "no wait"

@@ -6,9 +6,11 @@
 // 128-bit load per row for bf16) and walks down a stripe of rows keeping 8
 // private float accumulators, so nothing crosses lanes while streaming.  A
 // block covers 2048 adjacent channels (4 KB of every row it touches); the grid
-// is (channel tiles) x (row stripes) with thousands of blocks.  Each block
-// writes one row of partials; a second small kernel adds the stripes in a fixed
-// order in double and folds them into the caller's running sums.
+// is (channel tiles) x (row stripes), one resident block per compute unit.  A
+// thread sums at most 1024 rows in float before folding into a double, so the
+// error does not grow with the number of calibration tokens.  Each block writes
+// one row of partials; a second small kernel adds the stripes in a fixed order
+// in double and folds them into the caller's running sums.
 #include "common.hpp"
 
 namespace mp {
@@ -22,6 +24,7 @@ constexpr int kBlock = 256;
 constexpr int kTargetBlocks = 256;
 constexpr int kMinRowsPerBlock = 32;
 constexpr int kMaxStripes = 4096;
+constexpr int kFoldRows = 1024;  // rows summed in single precision before a fold into double (multiple of 8)
 
 template <typename T, int UNROLL, int BLOCK>
 __global__ __launch_bounds__(BLOCK) void colsumsq_partial_vec(const T *__restrict__ x, int64_t n_rows,
@@ -33,40 +36,53 @@ __global__ __launch_bounds__(BLOCK) void colsumsq_partial_vec(const T *__restric
     int64_t t1 = t0 + rows_per_block;
     if (t1 > n_rows) t1 = n_rows;
 
-    float acc[8];
+    // Single-precision accumulation never runs over more than kFoldRows rows: after that the eight sums are
+    // folded into doubles, so the rounding error of a channel does not grow with the length of the stripe.
+    double tot[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    for (int e = 0; e < 8; ++e) tot[e] = 0.0;
 
     const T *p = x + t0 * ld + c0;
     int64_t t = t0;
-    for (; t + UNROLL <= t1; t += UNROLL) {
-        Packet<T, 8> pk[UNROLL];
+    while (t < t1) {
+        const int64_t te = t + kFoldRows < t1 ? t + kFoldRows : t1;
+        float acc[8];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) pk[u].template load<true>(p + u * ld);
-        float s[8];
+        for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+        for (; t + UNROLL <= te; t += UNROLL) {
+            Packet<T, 8> pk[UNROLL];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) s[e] = 0.f;
+            for (int u = 0; u < UNROLL; ++u) pk[u].template load<true>(p + u * ld);
+            float s[8];
 #pragma unroll
-        for (int u = 0; u < UNROLL; ++u) {
+            for (int e = 0; e < 8; ++e) s[e] = 0.f;
+#pragma unroll
+            for (int u = 0; u < UNROLL; ++u) {
+                float v[8];
+                pk[u].to_float(v);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s[e] = fmaf(v[e], v[e], s[e]);
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] += s[e];
+            p += UNROLL * ld;
+        }
+        for (; t < te; ++t) {
+            Packet<T, 8> pk;
+            pk.template load<true>(p);
             float v[8];
-            pk[u].to_float(v);
+            pk.to_float(v);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) s[e] = fmaf(v[e], v[e], s[e]);
+            for (int e = 0; e < 8; ++e) acc[e] = fmaf(v[e], v[e], acc[e]);
+            p += ld;
         }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] += s[e];
-        p += UNROLL * ld;
+        for (int e = 0; e < 8; ++e) tot[e] += static_cast<double>(acc[e]);
     }
-    for (; t < t1; ++t) {
-        Packet<T, 8> pk;
-        pk.template load<true>(p);
-        float v[8];
-        pk.to_float(v);
+    float out[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] = fmaf(v[e], v[e], acc[e]);
-        p += ld;
-    }
-    store_floats(partials + static_cast<int64_t>(blockIdx.y) * n_cols + c0, acc);
+    for (int e = 0; e < 8; ++e) out[e] = static_cast<float>(tot[e]);
+    store_floats(partials + static_cast<int64_t>(blockIdx.y) * n_cols + c0, out);
 }
 
 // any width / pitch / alignment: one channel per thread, lanes on adjacent channels
@@ -80,23 +96,28 @@ __global__ __launch_bounds__(kBlock) void colsumsq_partial_scalar(const T *__res
     const int64_t t0 = static_cast<int64_t>(blockIdx.y) * rows_per_block;
     int64_t t1 = t0 + rows_per_block;
     if (t1 > n_rows) t1 = n_rows;
-    float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+    double tot = 0.0;  // folded every kFoldRows rows, as in the packet kernel
     const T *p = x + t0 * ld + c;
     int64_t t = t0;
-    for (; t + 4 <= t1; t += 4) {
-        const float v0 = widen(p[0]), v1 = widen(p[ld]), v2 = widen(p[2 * ld]), v3 = widen(p[3 * ld]);
-        a0 = fmaf(v0, v0, a0);
-        a1 = fmaf(v1, v1, a1);
-        a2 = fmaf(v2, v2, a2);
-        a3 = fmaf(v3, v3, a3);
-        p += 4 * ld;
+    while (t < t1) {
+        const int64_t te = t + kFoldRows < t1 ? t + kFoldRows : t1;
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+        for (; t + 4 <= te; t += 4) {
+            const float v0 = widen(p[0]), v1 = widen(p[ld]), v2 = widen(p[2 * ld]), v3 = widen(p[3 * ld]);
+            a0 = fmaf(v0, v0, a0);
+            a1 = fmaf(v1, v1, a1);
+            a2 = fmaf(v2, v2, a2);
+            a3 = fmaf(v3, v3, a3);
+            p += 4 * ld;
+        }
+        for (; t < te; ++t) {
+            const float v = widen(p[0]);
+            a0 = fmaf(v, v, a0);
+            p += ld;
+        }
+        tot += static_cast<double>((a0 + a1) + (a2 + a3));
     }
-    for (; t < t1; ++t) {
-        const float v = widen(p[0]);
-        a0 = fmaf(v, v, a0);
-        p += ld;
-    }
-    partials[static_cast<int64_t>(blockIdx.y) * n_cols + c] = (a0 + a1) + (a2 + a3);
+    partials[static_cast<int64_t>(blockIdx.y) * n_cols + c] = static_cast<float>(tot);
 }
 
 // sumsq[c] += sum over stripes of partials[s, c].  A block owns 64 adjacent channels; its 16 waves

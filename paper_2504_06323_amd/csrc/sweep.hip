@@ -1,6 +1,6 @@
-// The compensated left-to-right sweep of the Hessian-based one-shot pruner (Section 4.1.3, "Pruning Methods":
-// the lowest-ranking parameters are pruned "using the inverse Hessian matrix and a subsequent weight update"),
-// with the sparsity target that the Projection Planner gives the projection (Section 3.3).
+// The compensated left-to-right sweep of the Hessian-based one-shot pruner with weight compensation
+// (Section 4.1.3, "Pruning Methods"), with the sparsity target that the Projection Planner gives the
+// projection (Section 3.3).
 //
 // The published algorithm is written with U, the upper Cholesky factor of H^-1: in column j the error
 // e = (w_j - w'_j) / U_jj is spread to the right with row j of U.  Here it runs on R = U^-1 (H = R R^T, from

@@ -255,6 +255,28 @@ def test_sweep_ties_dead_channels_and_compensation(lib):
     assert obs.reconstruction_error(w0, got_w, h) <= 1.001 * obs.reconstruction_error(w0, want_w, h)
 
 
+def test_sweep_resumed_with_a_fresh_workspace_at_a_group_boundary(lib):
+    """What must survive between the calls of a split sweep: the working matrix v always, and the workspace only
+    while a group of four blocks is unfinished.  A caller that owns v and resumes at a multiple of four blocks may
+    hand over a different (here: poisoned) workspace and must get the bits of the one-call sweep."""
+    rows, cols, tokens, sparsity = 40, 1280, 2048, 0.5                    # ten blocks: groups 0-3, 4-7, 8-9
+    x = _acts(tokens, cols, torch.bfloat16, seed=5)
+    w = synth.random_matrix(rows, cols, torch.float32, seed=6, device=DEV, scale=0.05)
+    h = torch.zeros((cols, cols), dtype=torch.float32, device=DEV)
+    prune.hessian_accumulate(x, h)
+    prune.hessian_factor(h, 0.01)
+    whole = torch.empty_like(w)
+    prune.obs_sweep(w, h, sparsity, w_out=whole)
+    need = int(prune.load().prune_obs_sweep_workspace_bytes(rows, cols, 0))
+    v = torch.full((rows, cols), float("nan"), dtype=torch.float32, device=DEV)
+    split = torch.full_like(w, 7.0)
+    for first, count in ((0, 4), (4, 4), (8, 2)):
+        fresh = torch.full((need,), 0xA5, dtype=torch.uint8, device=DEV)
+        prune.obs_sweep(w, h, sparsity, w_out=split, first_block=first, n_blocks=count, v=v, ws=fresh)
+    _sync()
+    assert np.array_equal(to_np(split).view(np.uint32), to_np(whole).view(np.uint32))
+
+
 def _popcount32(a):
     a = a.astype(np.uint32)
     a = a - ((a >> 1) & 0x55555555)
