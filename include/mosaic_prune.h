@@ -45,7 +45,8 @@ typedef enum {
     PRUNE_ERR_SHAPE = -2,     /* non-positive extent, or ld smaller than the row width */
     PRUNE_ERR_DTYPE = -3,     /* dtype is not a prune_dtype */
     PRUNE_ERR_ALIGNMENT = -4, /* ws not 16-byte aligned, or a pointer not aligned to its element size */
-    PRUNE_ERR_WORKSPACE = -5, /* ws_bytes smaller than prune_workspace_bytes() */
+    PRUNE_ERR_WORKSPACE = -5, /* ws_bytes smaller than prune_workspace_bytes(), or (prune_stats_norms_static) the
+                                 problem needs more scratch than PRUNE_STATIC_SCRATCH_BYTES */
     PRUNE_ERR_RANGE = -6,     /* scalar argument outside its documented range */
     PRUNE_ERR_DEVICE = -7     /* the HIP runtime refused a launch */
 } prune_status;
@@ -107,6 +108,24 @@ int prune_stats_accumulate(const void *x, int dtype, int64_t n_tokens, int64_t n
  */
 int prune_stats_norms(const void *x, int dtype, int64_t n_tokens, int64_t n_channels, int64_t ld_x, float *sumsq,
                       float *norms, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * prune_stats_norms for callers that cannot allocate device memory and so have no workspace to pass:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments
+ * (minus the workspace), same kernels, same results bit for bit.  The per-stripe partial sums live in
+ * an array built into the library, PRUNE_STATIC_SCRATCH_BYTES per GPU, which each GPU the call runs on
+ * holds until the process ends.  The call allocates and frees nothing; its first call on a device looks
+ * up the address of that device's array.
+ * A shape whose partial sums do not fit (prune_workspace_bytes(PRUNE_OP_STATS, n_tokens, n_channels)
+ * above PRUNE_STATIC_SCRATCH_BYTES: more than 524288 channels) is refused with PRUNE_ERR_WORKSPACE and
+ * nothing is launched.  All calls on one GPU share the array: calls that overlap in time on one GPU
+ * (different streams, or different host threads) race and give wrong sums; calls on one stream, or
+ * otherwise ordered, are safe.  Nothing needs clearing between calls: every partial sum that is read
+ * was written by the same call.
+ */
+#define PRUNE_STATIC_SCRATCH_BYTES ((size_t)2 << 20)
+int prune_stats_norms_static(const void *x, int dtype, int64_t n_tokens, int64_t n_channels, int64_t ld_x,
+                             float *sumsq, float *norms, void *stream);
 
 /* norms[j] = sqrt(sumsq[j]) (correctly rounded float sqrt).  In place allowed. */
 int prune_stats_finalize(const float *sumsq, int64_t n_channels, float *norms, void *stream);

@@ -34,6 +34,7 @@ _SIGNATURES = {
     "prune_workspace_bytes": (_sz, [_int, _i64, _i64]),
     "prune_stats_accumulate": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _sz, _vp]),
     "prune_stats_norms": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp, _sz, _vp]),
+    "prune_stats_norms_static": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp]),
     "prune_stats_finalize": (_int, [_vp, _i64, _vp, _vp]),
     "prune_score": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _vp, _vp, _sz, _vp]),
     "prune_outlier_ratio": (_int, [_vp, _int, _i64, _i64, _i64, _vp, _vp, _f32, _vp, _vp, _vp, _vp]),
@@ -189,6 +190,14 @@ def stats_norms(x: torch.Tensor, sumsq: torch.Tensor, norms: torch.Tensor, ws: O
     _check("prune_stats_norms",
            load().prune_stats_norms(ptr, _dtype_code(x), t, c, ld, _vector(sumsq, "sumsq", torch.float32, c),
                                     _vector(norms, "norms", torch.float32, c), ws_ptr, ws_bytes, _stream(stream)))
+
+
+def stats_norms_static(x: torch.Tensor, sumsq: torch.Tensor, norms: torch.Tensor, stream=None) -> None:
+    """prune_stats_norms on the library's built-in scratch: no workspace, nothing allocated (prune_stats_norms_static)."""
+    ptr, t, c, ld = _matrix(x, "x")
+    _check("prune_stats_norms_static",
+           load().prune_stats_norms_static(ptr, _dtype_code(x), t, c, ld, _vector(sumsq, "sumsq", torch.float32, c),
+                                           _vector(norms, "norms", torch.float32, c), _stream(stream)))
 
 
 def stats_finalize(sumsq: torch.Tensor, norms: torch.Tensor, stream=None) -> None:

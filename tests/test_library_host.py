@@ -62,6 +62,14 @@ def test_error_paths_return_before_any_launch(lib):
     assert sn(fake, 1, 8, 8, 4, fake, fake, fake, 1 << 20, None) == E["shape"]
     assert sn(fake, 3, 8, 8, 8, fake, fake, fake, 1 << 20, None) == E["dtype"]
     assert sn(fake, 1, 8, 8, 8, fake, fake, fake, 4, None) == E["ws"]
+    ss = lib.prune_stats_norms_static                                           # the variant with built-in scratch
+    assert ss(fake, 3, 8, 8, 8, fake, fake, None) == E["dtype"]
+    assert ss(fake, 1, 8, 8, 4, fake, fake, None) == E["shape"]
+    assert ss(None, 1, 8, 8, 8, fake, fake, None) == E["null"]
+    assert ss(fake, 1, 8, 8, 8, fake, None, None) == E["null"]
+    assert ss(odd, 1, 8, 8, 8, fake, fake, None) == E["align"]
+    assert ss(fake, 1, 8, 600000, 600000, fake, fake, None) == E["ws"]          # partial sums beyond the 2 MiB array
+    assert prune.workspace_bytes(prune.OP_STATS, 1 << 20, 524288) <= 2 << 20 < prune.workspace_bytes(prune.OP_STATS, 8, 600000)
     assert lib.prune_stats_finalize(None, 8, fake, None) == E["null"]
     assert lib.prune_stats_finalize(fake, 0, fake, None) == E["shape"]
     sc = lib.prune_score
