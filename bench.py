@@ -1,18 +1,20 @@
-#!/usr/bin/env python3
 """Benchmark of the projection-pruning hot path on one MI355X.
 
-A step is one pass of the whole path over one synthetic LLaMA-7B-shaped layer
-(the workload the headline metric is quoted on): activation statistics for the
-four distinct projection inputs (128 x 2048 calibration tokens), metric sum and
-outlier count for the seven projections, the host planner, per-row selection
-and masking of the seven projections, then structured ranking and compaction
-of the MLP on the masked weights.  All inputs are resident in HBM before the
-timed region starts.  One JSON line goes to stdout; everything else to stderr.
+Default workload: the layers of the full 32-layer LLaMA-3-8B-shaped model (grouped-query k / v of 1024 x 4096,
+14336-wide feed-forward block, 128 x 2048 calibration tokens per layer).  A step is one pass of the whole path
+over one layer: activation statistics of its four distinct projection inputs, metric sums and outlier counts of
+its seven projections (the ranking, done once), then for every target of the sweep (30 / 50 / 70 %) the planner
+over the whole model's table of counts, per-row selection and masking of the seven projections, and structured
+ranking and compaction of the feed-forward block on the masked weights.  Successive steps take successive
+layers out of a ring of distinct layers resident in HBM (inputs are generated before the timed region).
+One JSON line goes to stdout; everything else to stderr.
 """
 from __future__ import annotations
 
 import argparse
 import json
+import math
+import mmap
 import os
 import sys
 import time
@@ -28,7 +30,11 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes(cfg, shapes, act_shapes, r):
+def storage_name(cfg):
+    return "bf16" if str(cfg.dtype).endswith("bfloat16") else "f32"
+
+
+def algorithmic_bytes(cfg, shapes, act_shapes, r, n_targets):
     """Bytes the method itself must move per step (what the roofline is priced on)."""
     es = 2 if str(cfg.dtype).endswith("bfloat16") else 4
     numel = sum(rw * c for _, rw, c, _ in shapes)
@@ -37,11 +43,11 @@ def algorithmic_bytes(cfg, shapes, act_shapes, r):
     count = numel * es
     select = numel * (2 * es) + numel // 8
     mlp = 3 * cfg.inter * cfg.hidden
-    struct_rank = mlp * es
+    struct_rank = mlp * es if r > 0 else 0
     kept_frac = (cfg.inter - r) / cfg.inter
-    compact = mlp * es + int(mlp * es * kept_frac)
+    compact = mlp * es + int(mlp * es * kept_frac) if r > 0 else 0
     return dict(stats=stats, score=score, count=count, select=select, struct_rank=struct_rank, compact=compact,
-                total=stats + score + count + select + struct_rank + compact)
+                total=stats + score + count + n_targets * (select + struct_rank + compact))
 
 
 def measured_traffic(workload):
@@ -57,41 +63,126 @@ def measured_traffic(workload):
     return None
 
 
-def cpu_baseline(cfg, shapes, weights, acts, frac_den=8):
-    """Time the CPU oracle, as it stands, on a 1/frac_den sample of the same layer."""
-    import numpy as np
-    import torch
-    from oracle import mosaic_oracle as orc
+def mean_sigma(xs):
+    m = sum(xs) / len(xs)
+    return m, math.sqrt(sum((x - m) ** 2 for x in xs) / max(1, len(xs) - 1))
 
-    n_seqs = max(1, cfg.n_seqs // frac_den)
+
+# ---------------------------------------------------------------------------------------------------------------
+# CPU baseline: the oracle as it stands on a sample of the same layer, once on one core and once with the same
+# calls dealt to all host cores (a plain parallel loop over channel slices, projections and row blocks).  The
+# worker processes are forked before the GPU is touched and sit idle until the GPU part is over; the sample is
+# handed to them through shared memory.
+
+_CPU = {}
+
+
+def _shared_array(shape, dtype="float32"):
+    import numpy as np
+    count = 1
+    for d in shape:
+        count *= int(d)
+    buf = mmap.mmap(-1, max(16, count * np.dtype(dtype).itemsize))      # anonymous and shared: survives fork
+    return np.frombuffer(buf, dtype=dtype, count=count).reshape(shape)
+
+
+def cpu_prepare(cfg, shapes, act_shapes, den, workers):
+    """Allocate the shared sample buffers and fork the worker pool (call before the GPU is initialised)."""
+    import multiprocessing as mp
+    n_seqs = max(1, cfg.n_seqs // den)
     t_rows = n_seqs * cfg.seq_len
-    host = lambda t: t.detach().cpu().to(torch.float32).numpy()
-    xs = {a: host(x[:t_rows]) for a, x in acts.items()}
-    ws = {n: host(w[::frac_den]) for n, w in weights.items()}
-    sampled = sum(w.size for w in ws.values())
+    _CPU.update(cfg=cfg, shapes=shapes, den=den, n_seqs=n_seqs,
+                x={a: _shared_array((t_rows, ch)) for a, ch in act_shapes.items()},
+                norms={a: _shared_array((ch,), "float64") for a, ch in act_shapes.items()},
+                w={n: _shared_array((len(range(0, rw, den)), c)) for n, rw, c, _ in shapes},
+                masked={n: _shared_array((len(range(0, rw, den)), c)) for n, rw, c, _ in shapes},
+                down_cols=_shared_array((cfg.hidden, len(range(0, cfg.inter, den)))))
+    pool = mp.get_context("fork").Pool(workers) if workers > 1 else None
+    _CPU.update(pool=pool, workers=workers)
+
+
+def _cpu_task(task):
+    from oracle import mosaic_oracle as orc
+    kind = task[0]
+    if kind == "norms":
+        _, a, c0, c1 = task
+        _CPU["norms"][a][c0:c1] = orc.column_norms(_CPU["x"][a][:, c0:c1])
+        return None
+    if kind == "rank":
+        _, n, a, alpha = task
+        omega = orc.weight_metric(_CPU["w"][n], _CPU["norms"][a])
+        return orc.outlier_stats(omega, alpha)[2]
+    if kind == "prune":
+        _, n, a, r0, r1, k = task
+        w = _CPU["w"][n][r0:r1]
+        _CPU["masked"][n][r0:r1] = orc.prune_projection(w, orc.weight_metric(w, _CPU["norms"][a]), k)[0]
+        return None
+    raise ValueError(kind)
+
+
+def _cpu_leg(run_map, slices):
+    """The whole path on the sample through run_map (the builtin map, or a pool's)."""
+    import numpy as np
+    from oracle import mosaic_oracle as orc
+    cfg, shapes = _CPU["cfg"], _CPU["shapes"]
     t0 = time.perf_counter()
-    norms = {a: orc.column_norms(x) for a, x in xs.items()}
-    ratios, omegas = [], {}
-    for n, rw, c, a in shapes:
-        omega = orc.weight_metric(ws[n], norms[a])
-        _, _, ratio, _ = orc.outlier_stats(omega, cfg.alpha)
-        ratios.append(ratio)
-        omegas[n] = omega
+    tasks = []
+    for a, x in _CPU["x"].items():
+        step = max(1, -(-x.shape[1] // slices))
+        tasks += [("norms", a, c0, min(c0 + step, x.shape[1])) for c0 in range(0, x.shape[1], step)]
+    list(run_map(_cpu_task, tasks))
+    ratios = list(run_map(_cpu_task, [("rank", n, a, cfg.alpha) for n, _, _, a in shapes]))
     s, _ = orc.plan_sparsity(np.array(ratios).reshape(1, -1), cfg.p, cfg.lam, "global")
-    masked = {}
-    for i, (n, rw, c, a) in enumerate(shapes):
-        masked[n], _ = orc.prune_projection(ws[n], omegas[n], orc.zeros_per_row(s[0, i], c))
-    # structured part on the sample: every frac_den-th MLP channel forms the sampled MLP
-    gate, up = masked["gate"], masked["up"]
-    down = host(weights["down"][:, ::frac_den])
+    tasks = []
+    for i, (n, _, c, a) in enumerate(shapes):
+        rows = _CPU["w"][n].shape[0]
+        step = max(1, -(-rows // slices))
+        tasks += [("prune", n, a, r0, min(r0 + step, rows), orc.zeros_per_row(s[0, i], c)) for r0 in range(0, rows, step)]
+    list(run_map(_cpu_task, tasks))
+    # structured part on the sample: every den-th feed-forward channel forms the sampled block
+    gate, up, down = _CPU["masked"]["gate"], _CPU["masked"]["up"], _CPU["down_cols"]
     g = orc.group_magnitude(gate, up, down)
     kept = orc.struct_rank(g, int(cfg.struct_frac * g.shape[0]))
     orc.struct_compact(gate, up, down, kept)
-    dt = time.perf_counter() - t0
-    return {"value": sampled / dt, "unit": "weights/s", "cores": 1, "kind": "oracle",
-            "sample": f"1/{frac_den} of the layer: {n_seqs} of {cfg.n_seqs} calibration sequences for the activation "
-                      f"statistics, every {frac_den}th output row of each projection ({sampled} weights); "
-                      f"NumPy float64, {dt:.1f} s"}
+    return time.perf_counter() - t0
+
+
+def cpu_baseline(weights, acts):
+    """Fill the shared sample from the tensors the GPU path ran on, then time the two legs."""
+    import torch
+    cfg, den = _CPU["cfg"], _CPU["den"]
+    for a, x in acts.items():
+        dst = _CPU["x"][a]
+        for r0 in range(0, dst.shape[0], 8192):          # piecewise: no second full-size float32 copy on the device
+            dst[r0:r0 + 8192] = x[r0:min(r0 + 8192, dst.shape[0])].to(torch.float32).cpu().numpy()
+    for n, w in weights.items():
+        _CPU["w"][n][:] = w[::den].to(torch.float32).cpu().numpy()
+    _CPU["down_cols"][:] = weights["down"][:, ::den].to(torch.float32).cpu().numpy()
+    sampled = sum(w.size for w in _CPU["w"].values())
+    workers, pool = _CPU["workers"], _CPU["pool"]
+    t_one = _cpu_leg(map, 1)
+    t_all = _cpu_leg(pool.map, 2 * workers) if pool is not None else t_one
+    if pool is not None:
+        pool.close()
+        pool.join()
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return {"value": sampled / t_all, "unit": "weights/s", "cores": workers, "kind": "oracle",
+            "sample": f"1/{den} of one layer of the workload: {_CPU['n_seqs']} of {cfg.n_seqs} calibration sequences "
+                      f"for the activation statistics, every {den}th output row of each projection ({sampled} "
+                      f"weights), one target sparsity; NumPy float64; {t_all:.1f} s on {workers} worker processes "
+                      f"(the same oracle calls dealt out over channel slices, projections and row blocks), "
+                      f"{t_one:.1f} s on one core",
+            "single_core": {"value": sampled / t_one, "unit": "weights/s", "cores": 1, "seconds": round(t_one, 2)},
+            "seconds": round(t_all, 2), "nproc": os.cpu_count(), "affinity": len(os.sched_getaffinity(0)),
+            "cpu_model": model}
 
 
 def run_hessian_stage(args):
@@ -427,6 +518,257 @@ def run_layer_stage(args):
     print(json.dumps(out), flush=True)
 
 
+def measure_ceilings(torch, prune, dev, n_bytes=2 << 30, trials=5):
+    """Streaming rates of the plainest kernels on this card, in this run: read-only and copy, best grid of a few."""
+    src = torch.empty(n_bytes // 4, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    out = {}
+    for mode, name, moved in ((prune.PROBE_READ, "read", n_bytes), (prune.PROBE_COPY, "copy", 2 * n_bytes)):
+        best = (0.0, 0.0, 0)
+        for blocks in (256, 512, 1024, 2048, 4096, 8192):
+            for _ in range(2):
+                prune.bandwidth_probe(src, dst, mode, blocks)
+            ts = []
+            for _ in range(trials):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                prune.bandwidth_probe(src, dst, mode, blocks)
+                e1.record()
+                e1.synchronize()
+                ts.append(e0.elapsed_time(e1))
+            m, sd = mean_sigma(ts)
+            gbps = moved / (m * 1e-3) / 1e9
+            if gbps > best[0]:
+                best = (gbps, moved / ((m + sd) * 1e-3) / 1e9, blocks)
+        out[name] = {"gbps": round(best[0], 1), "blocks": best[2], "bytes_moved": moved}
+    del src, dst
+    return out
+
+
+def run_prune_stage(args):
+    import torch
+    from paper_2504_06323_amd import pipeline, prune, synth
+
+    cfg = synth.CONFIGS[args.workload]
+    shapes = synth.projection_shapes(cfg)
+    act_shapes = synth.activation_shapes(cfg)
+    n_proj = len(shapes)
+    numel = synth.layer_numel(cfg)
+    struct_frac = cfg.struct_frac if cfg.struct_frac > 0 else args.struct_frac
+    r = int(struct_frac * cfg.inter)
+    targets = list(cfg.p_sweep) if cfg.p_sweep else [cfg.p]
+    resident = max(1, min(args.resident_layers, cfg.n_layers))
+    table_layers = cfg.n_layers if args.table_layers < 0 else max(resident, min(args.table_layers, cfg.n_layers))
+
+    if not args.no_cpu_baseline:       # fork the oracle's workers while this process has not touched the GPU
+        cpu_prepare(cfg, shapes, act_shapes, args.cpu_sample_den, min(16, len(os.sched_getaffinity(0))))
+
+    if not torch.cuda.is_available():
+        log("bench.py needs a GPU")
+        sys.exit(2)
+    prune.load()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    # the whole model's table of outlier counts (Algorithm 1's R_LLM), the planner's inputs and outputs: on the device
+    n_table = table_layers * n_proj
+    t_count = torch.zeros(n_table, dtype=torch.int64, device=dev)
+    t_numel = torch.tensor([rw * c for _, rw, c, _ in shapes] * table_layers, dtype=torch.int64, device=dev)
+    t_cols = torch.tensor([c for _, _, c, _ in shapes] * table_layers, dtype=torch.int64, device=dev)
+    t_sparsity = torch.zeros(n_table, dtype=torch.float64, device=dev)
+    t_ks = torch.zeros(n_table, dtype=torch.int32, device=dev)
+    t_flags = torch.zeros(2, dtype=torch.int32, device=dev)
+    proj_inputs = {n: a for n, _, _, a in shapes}
+
+    # Inputs: `resident` distinct layers stay in HBM (weights and all four activation tensors); the other layers of
+    # the table are generated, ranked once for their row of counts, and dropped again.
+    t0 = time.perf_counter()
+    ring, first = [], None
+    for layer in range(table_layers):
+        weights = {n: synth.make_weight(cfg, layer, n, dev) for n, _, _, _ in shapes}
+        acts = {a: synth.make_activation(cfg, layer, a, dev) for a in act_shapes}
+        st = pipeline.LayerState.create(weights, proj_inputs, act_shapes, cfg.n_tokens, share_outputs_with=first)
+        first = first or st
+        st.count = t_count[layer * n_proj:(layer + 1) * n_proj]
+        pipeline.rank_layer(st, acts, cfg.alpha)
+        if layer < resident:
+            ring.append((layer, st, acts))
+        else:
+            torch.cuda.synchronize()
+            del weights, acts, st
+    torch.cuda.synchronize()
+    log(f"inputs generated in {time.perf_counter() - t0:.1f} s: {table_layers} layers ranked for the table of counts, "
+        f"{resident} resident ({numel} weights and {sum(cfg.n_tokens * c for c in act_shapes.values())} activation "
+        f"elements each)")
+    res = pipeline.alloc_struct(first, r) if r > 0 else None
+    names = list(act_shapes)
+    stats_bytes = sum(cfg.n_tokens * c * (2 if storage_name(cfg) == "bf16" else 4) + c * 8 for c in act_shapes.values())
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    stats_events = []   # (start, stop) around the statistics launches of every timed step
+    pass_events = []    # marks between the passes, recorded in extra steps after the timed region
+
+    def step(i: int, record: bool, breakdown: bool = False):
+        """One pass of the whole path over the next layer of the ring.  record: one HIP-event pair around the
+        statistics launches (the roofline figure).  breakdown: marks between all passes; every event costs the
+        stream a few microseconds, so these steps run after the timed region, not inside it."""
+        layer, st, acts = ring[i % len(ring)]
+        marks = [] if breakdown else None
+        mark = (lambda: (marks.append(ev()), marks[-1].record())) if breakdown else (lambda: None)
+        mark()
+        # ranking (independent of the target): done once per layer
+        if record:
+            e0, e1 = ev(), ev()
+            e0.record()
+        for a in names:
+            prune.stats_norms(acts[a], st.sumsq[a], st.norms[a], ws=st.ws)
+        if record:
+            e1.record()
+            stats_events.append((e0, e1))
+        mark()
+        prune.score_outlier_batch([st.weights[n] for n in st.names], [st.norms[proj_inputs[n]] for n in st.names],
+                                  cfg.alpha, st.score_sum, st.count, taus=st.tau, ws=st.ws)
+        mark()
+        # pruning, once per target of the sweep, reusing the ranking
+        for p in targets:
+            if args.host_plan:          # the step waits for the table of counts on the host
+                _, ks_all, _ = pipeline.plan(t_count.tolist(), t_numel.tolist(), t_cols.tolist(), table_layers, n_proj,
+                                             p, cfg.lam)
+                ks = ks_all[layer * n_proj:(layer + 1) * n_proj]
+                mark()
+                pipeline.prune_layer(st, ks)
+            else:                       # the planner runs on the device over the whole table, behind the ranking
+                prune.plan_sparsity_device(t_count, t_numel, t_cols, table_layers, n_proj, p, cfg.lam, t_sparsity,
+                                           t_ks, t_flags)
+                mark()
+                prune.select_mask_batch([st.weights[n] for n in st.names],
+                                        [st.norms[proj_inputs[n]] for n in st.names], None,
+                                        w_outs=[st.pruned[n] for n in st.names],
+                                        mask_bits=[st.mask_bits.get(n) for n in st.names],
+                                        ks_dev=t_ks[layer * n_proj:(layer + 1) * n_proj])
+            mark()
+            if r > 0:
+                pipeline.struct_layer(st, r, res)
+            mark()
+        if breakdown:
+            pass_events.append(marks)
+
+    if args.calibration_copy_mib > 0:
+        src = torch.ones(args.calibration_copy_mib * (1 << 20) // 4, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            prune.bandwidth_probe(src, dst, prune.PROBE_COPY, 2048)
+        torch.cuda.synchronize()
+        del src, dst
+
+    for i in range(args.warmup):
+        step(i, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    # after the clock has stopped: the device planner against the host planner on the same table, for every target
+    counts = t_count.tolist()
+    for p in targets:
+        prune.plan_sparsity_device(t_count, t_numel, t_cols, table_layers, n_proj, p, cfg.lam, t_sparsity, t_ks, t_flags)
+        _, ks_host, _ = pipeline.plan(counts, t_numel.tolist(), t_cols.tolist(), table_layers, n_proj, p, cfg.lam)
+        if t_ks.tolist() != ks_host or t_flags.tolist()[1] != 0:
+            raise RuntimeError(f"device plan differs from host plan at p = {p}")
+    ks_last = ks_host
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    ab = algorithmic_bytes(cfg, shapes, act_shapes, r, len(targets))
+    n_break = max(5, min(args.steps, 10))
+    for i in range(n_break):      # the per-pass breakdown, outside the timed region
+        step(i, False, breakdown=True)
+    torch.cuda.synchronize()
+    ceilings = measure_ceilings(torch, prune, dev)
+
+    spans = [a.elapsed_time(b) / len(names) for a, b in stats_events]
+    avg_ms, sd_ms = mean_sigma(spans)
+    avg_bytes = stats_bytes / len(names)
+    achieved = avg_bytes / (avg_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "colsumsq_partial_vec (activation statistics)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(cfg.name),
+                "avg_launch_ms": round(avg_ms, 4), "avg_launch_ms_sigma": round(sd_ms, 4),
+                "avg_launch_bytes": int(avg_bytes), "launches": len(stats_events) * len(names),
+                "frac_of_read_ceiling": round(achieved / ceilings["read"]["gbps"], 4)}
+
+    # per-pass figures from the marked steps: [start | stats | score+outlier | (plan | select | struct) per target]
+    samples = {"stats": [], "score_outlier": [], "plan": [], "select": [], "struct": [], "step": []}
+    for m in pass_events:
+        d = [m[j].elapsed_time(m[j + 1]) for j in range(len(m) - 1)]
+        samples["stats"].append(d[0])
+        samples["score_outlier"].append(d[1])
+        for t in range(len(targets)):
+            samples["plan"].append(d[2 + 3 * t])
+            samples["select"].append(d[3 + 3 * t])
+            samples["struct"].append(d[4 + 3 * t])
+        samples["step"].append(m[0].elapsed_time(m[-1]))
+    pass_bytes = {"stats": ab["stats"], "score_outlier": ab["score"] + ab["count"], "plan": 0, "select": ab["select"],
+                  "struct": ab["struct_rank"] + ab["compact"]}
+    pass_ceiling = {"stats": "read", "score_outlier": "read", "select": "copy", "struct": "copy"}
+    passes = {}
+    for name, xs in samples.items():
+        if name == "step" or (name == "struct" and r == 0):
+            continue
+        m, sd = mean_sigma(xs)
+        entry = {"ms": round(m, 4), "ms_sigma": round(sd, 4), "trials": len(xs), "bytes": pass_bytes[name]}
+        if pass_bytes[name]:
+            gbps = pass_bytes[name] / (m * 1e-3) / 1e9
+            entry.update(gbps=round(gbps, 1), frac_of_peak=round(gbps / HBM_PEAK_GBPS, 4),
+                         frac_of_ceiling=round(gbps / ceilings[pass_ceiling[name]]["gbps"], 4),
+                         ceiling=pass_ceiling[name])
+        passes[name] = entry
+    step_m, step_sd = mean_sigma(samples["step"])
+    log(f"step {ms_per_step:.3f} ms (marked steps {step_m:.3f} +- {step_sd:.3f}) | " +
+        " | ".join(f"{k} {v['ms']:.3f} ms" + (f" ({v['gbps']:.0f} GB/s)" if "gbps" in v else "") for k, v in passes.items()))
+    log(f"ceilings: read {ceilings['read']['gbps']:.0f} GB/s, copy {ceilings['copy']['gbps']:.0f} GB/s")
+    log(f"outlier counts of layer 0 {counts[:n_proj]}; zeros per row at p = {targets[-1]}: {ks_last[:n_proj]}; "
+        f"removed MLP channels {r}")
+
+    out = {
+        "metric": "projection weights pruned/s (GB/s scored+masked) and % of HBM peak, 1 GPU",
+        "value": numel * args.steps / elapsed,
+        "unit": "weights/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_sigma": round(step_sd, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: layers of the {cfg.n_layers}-layer model, {storage_name(cfg)} storage, hidden "
+                               f"{cfg.hidden}, q/o {cfg.q_out}, k/v {cfg.kv_out}, intermediate {cfg.inter}, "
+                               f"{cfg.n_seqs} x {cfg.seq_len} calibration tokens per layer, {len(names)} distinct activation "
+                               f"tensors; a step = one layer: ranking once, then for each target in {targets}: "
+                               f"planner over the {table_layers} x {n_proj} table, select + mask, "
+                               f"{r} of {cfg.inter} MLP channels removed structurally; {resident} distinct layers "
+                               f"resident and cycled, alpha {cfg.alpha}, lambda {cfg.lam}",
+                   "weights_per_step": numel,
+                   "algorithmic_bytes_per_step": ab["total"],
+                   "storage_dtype": storage_name(cfg),
+                   "targets": targets,
+                   "layers_resident": resident,
+                   "layers_in_table": table_layers},
+        "algorithmic_gbps": round(ab["total"] / elapsed * args.steps / 1e9, 1),
+        "hbm_frac_whole_step": round(ab["total"] / elapsed * args.steps / 1e9 / HBM_PEAK_GBPS, 4),
+        "roofline": roofline,
+        "passes": passes,
+        "ceilings": ceilings,
+    }
+    if not args.no_cpu_baseline:
+        layer0, st0, acts0 = ring[0]
+        out["cpu_baseline"] = cpu_baseline(st0.weights, acts0)
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--stage", default="prune", choices=["prune", "hessian", "obs", "mlp", "layer"],
@@ -438,178 +780,40 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="llama7b_layer")
+    ap.add_argument("--workload", default=None,
+                    help="default: llama3_8b_full for the prune stage, llama7b_layer for the other stages")
+    ap.add_argument("--resident-layers", type=int, default=8,
+                    help="distinct layers kept in HBM and cycled through by the steps (capped at the model's layers)")
+    ap.add_argument("--table-layers", type=int, default=-1,
+                    help="layers in the planner's table of counts (default: all layers of the model); the ones that "
+                         "are not resident are generated and ranked once before the timed region")
+    ap.add_argument("--struct-frac", type=float, default=0.2,
+                    help="fraction of MLP channels removed structurally when the workload itself names none")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--host-plan", action="store_true",
                     help="run the projection planner on the host (the step then waits for the outlier counts)")
-    ap.add_argument("--cpu-sample-den", type=int, default=2)
+    ap.add_argument("--cpu-sample-den", type=int, default=4)
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
-                    help="before the warm-up, run a plain float32 copy kernel (read N MiB, write N MiB) three "
-                         "times so that a rocprofv3 --pmc run of this command carries a kernel of known traffic")
+                    help="before the warm-up, run the plain copy kernel (read N MiB, write N MiB) three times so "
+                         "that a rocprofv3 --pmc run of this command carries a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py measures one GPU: every box of this build has one MI355X and the path has no "
             "multi-GPU leg. Run with --gpus 1.")
         sys.exit(2)
+    if args.workload is None:
+        args.workload = "llama3_8b_full" if args.stage == "prune" else "llama7b_layer"
 
     if args.stage == "hessian":
         run_hessian_stage(args)
-        return
-    if args.stage == "obs":
+    elif args.stage == "obs":
         run_obs_stage(args)
-        return
-    if args.stage == "mlp":
+    elif args.stage == "mlp":
         run_mlp_stage(args)
-        return
-    if args.stage == "layer":
+    elif args.stage == "layer":
         run_layer_stage(args)
-        return
-
-    import torch
-    from paper_2504_06323_amd import pipeline, prune, synth
-
-    if not torch.cuda.is_available():
-        log("bench.py needs a GPU")
-        sys.exit(2)
-    prune.load()
-    dev = "cuda:0"
-    torch.cuda.set_device(0)
-    cfg = synth.CONFIGS[args.workload]
-    shapes = synth.projection_shapes(cfg)
-    act_shapes = synth.activation_shapes(cfg)
-    numel = synth.layer_numel(cfg)
-    r = int(cfg.struct_frac * cfg.inter)
-
-    t0 = time.perf_counter()
-    weights = {n: synth.make_weight(cfg, 0, n, dev) for n, _, _, _ in shapes}
-    acts = {a: synth.make_activation(cfg, 0, a, dev) for a in act_shapes}
-    torch.cuda.synchronize()
-    log(f"inputs generated in {time.perf_counter() - t0:.1f} s: {numel} weights, "
-        f"{sum(x.numel() for x in acts.values())} activation elements")
-
-    st = pipeline.LayerState.create(weights, {n: a for n, _, _, a in shapes}, act_shapes, cfg.n_tokens)
-    res = pipeline.alloc_struct(st, r)
-    numels = [rw * c for _, rw, c, _ in shapes]
-    cols = [c for _, _, c, _ in shapes]
-    names = list(act_shapes)
-    ev = lambda: torch.cuda.Event(enable_timing=True)
-    stats_events = []   # (start, stop, bytes, launches) around the statistics launches of every timed step
-    pass_events = []    # per-step boundaries for the stderr breakdown
-
-    def step(record: bool, breakdown: bool = False):
-        """One pass of the whole path.  record: one HIP-event pair around the statistics launches (the
-        roofline figure).  breakdown: marks between the passes as well; each event costs the stream a few
-        microseconds, so these steps are run after the timed region, not inside it."""
-        marks = [ev() for _ in range(5)] if breakdown else None
-        if breakdown:
-            marks[0].record()
-        # phase 1: ranking (independent of p)
-        if record:
-            e0, e1 = ev(), ev()
-            e0.record()
-        for a in names:
-            prune.stats_norms(acts[a], st.sumsq[a], st.norms[a], ws=st.ws)
-        if record:
-            e1.record()
-            stats_events.append((e0, e1, sum(acts[a].numel() * acts[a].element_size() + acts[a].shape[1] * 8
-                                             for a in names), len(names)))
-        if breakdown:
-            marks[1].record()
-        prune.score_outlier_batch([st.weights[n] for n in st.names],
-                                  [st.norms[st.proj_inputs[n]] for n in st.names], cfg.alpha, st.score_sum,
-                                  st.count, taus=st.tau, ws=st.ws)
-        if breakdown:
-            marks[2].record()
-        if args.host_plan:
-            counts = st.count.tolist()      # 7 integers cross to the host, the step waits for them
-            _, ks, _ = pipeline.plan(counts, numels, cols, 1, len(shapes), cfg.p, cfg.lam)
-        else:
-            counts = ks = None              # the planner runs on the device, behind the ranking
-            pipeline.plan_device(st, cfg.p, cfg.lam)
-        # phase 2: pruning
-        pipeline.prune_layer(st, ks)
-        if breakdown:
-            marks[3].record()
-        pipeline.struct_layer(st, r, res)
-        if breakdown:
-            marks[4].record()
-            pass_events.append(marks)
-        return counts, ks
-
-    if args.calibration_copy_mib > 0:
-        src = torch.ones(args.calibration_copy_mib * (1 << 20) // 4, dtype=torch.float32, device=dev)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            torch.mul(src, 1.0, out=dst)
-        torch.cuda.synchronize()
-        del src, dst
-
-    for _ in range(args.warmup):
-        step(False)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        counts, ks = step(True)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-
-    if not args.host_plan:   # read the plan back once, after the clock has stopped, and hold it against the host planner
-        counts, ks = st.count.tolist(), st.ks_dev.tolist()
-        _, ks_host, _ = pipeline.plan(counts, numels, cols, 1, len(shapes), cfg.p, cfg.lam)
-        if ks != ks_host or st.plan_flags.tolist()[1] != 0:
-            raise RuntimeError(f"device plan {ks} differs from host plan {ks_host}")
-
-    ms_per_step = 1e3 * elapsed / args.steps
-    ab = algorithmic_bytes(cfg, shapes, act_shapes, r)
-    for _ in range(min(args.steps, 10)):     # the per-pass breakdown for stderr, outside the timed region
-        step(False, breakdown=True)
-    torch.cuda.synchronize()
-    n_launches = sum(n for _, _, _, n in stats_events)
-    avg_ms = sum(a.elapsed_time(b) for a, b, _, _ in stats_events) / n_launches
-    avg_bytes = sum(n for _, _, n, _ in stats_events) / n_launches
-    achieved = avg_bytes / (avg_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "colsumsq_partial_vec (activation statistics)",
-                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": measured_traffic(cfg.name),
-                "avg_launch_ms": round(avg_ms, 4), "avg_launch_bytes": int(avg_bytes),
-                "launches": n_launches}
-
-    seg = [[m[i].elapsed_time(m[i + 1]) for i in range(4)] for m in pass_events]
-    mean = lambda j: sum(s[j] for s in seg) / len(seg)
-    gb = lambda key: ab[key] / 1e9
-    log(f"step {ms_per_step:.3f} ms | stats {mean(0):.3f} ms ({gb('stats') / mean(0) * 1e3:.0f} GB/s) | "
-        f"score+count {mean(1):.3f} ms ({(gb('score') + gb('count')) / mean(1) * 1e3:.0f} GB/s) | "
-        f"plan+select {mean(2):.3f} ms ({gb('select') / mean(2) * 1e3:.0f} GB/s) | "
-        f"struct {mean(3):.3f} ms ({(gb('struct_rank') + gb('compact')) / mean(3) * 1e3:.0f} GB/s)")
-    log(f"outlier counts {counts}; zeros per row {ks}; removed MLP channels {r}")
-
-    out = {
-        "metric": "projection weights pruned/s (GB/s scored+masked) and % of HBM peak, 1 GPU",
-        "value": numel * args.steps / elapsed,
-        "unit": "weights/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4),
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "f32",
-        "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: one LLaMA-7B-shaped layer, bf16 storage, hidden {cfg.hidden}, "
-                               f"intermediate {cfg.inter}, {cfg.n_seqs} x {cfg.seq_len} calibration tokens, "
-                               f"4 distinct activation tensors, alpha {cfg.alpha}, target sparsity {cfg.p}, "
-                               f"{r} of {cfg.inter} MLP channels removed structurally",
-                   "weights_per_step": numel,
-                   "algorithmic_bytes_per_step": ab["total"],
-                   "storage_dtype": "bf16"},
-        "algorithmic_gbps": round(ab["total"] / elapsed * args.steps / 1e9, 1),
-        "hbm_frac_whole_step": round(ab["total"] / elapsed * args.steps / 1e9 / HBM_PEAK_GBPS, 4),
-        "roofline": roofline,
-    }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, shapes, weights, acts, args.cpu_sample_den)
-    print(json.dumps(out), flush=True)
+    else:
+        run_prune_stage(args)
 
 
 if __name__ == "__main__":

@@ -434,6 +434,21 @@ int prune_causal_attention(const void *q, const void *k, const void *v, void *o,
                            int64_t seq_len, int64_t heads, int64_t kv_heads, int64_t head_dim, int64_t ld_q, int64_t ld_k,
                            int64_t ld_v, int64_t ld_o, void *stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * Measurement aid (nothing of the paper): the streaming rates this card delivers to the plainest
+ * kernels, which the benchmark reports beside the published HBM peak so that every pass of the path
+ * can be held against both (the paper reports means over repeated trials, Section 4.1.5; so does the
+ * benchmark).
+ *   PRUNE_PROBE_READ: reads `bytes` from src in 128-bit non-temporal loads; dst receives one checksum
+ *     word per thread, prune_bandwidth_probe_sink_bytes(blocks) bytes.
+ *   PRUNE_PROBE_COPY: dst[0 .. bytes) = src[0 .. bytes).
+ * src, dst: DEVICE, 16-byte aligned, not overlapping; bytes a positive multiple of 16; blocks: the
+ * number of 256-thread workgroups that share the range (1 .. 1048576).  One launch on `stream`.
+ * ------------------------------------------------------------------------------------------------ */
+typedef enum { PRUNE_PROBE_READ = 0, PRUNE_PROBE_COPY = 1 } prune_probe_mode;
+size_t prune_bandwidth_probe_sink_bytes(int blocks);
+int prune_bandwidth_probe(const void *src, void *dst, size_t bytes, int mode, int blocks, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

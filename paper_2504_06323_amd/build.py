@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(CSRC, "libmosaic_prune.so")
 OBJ_DIR = os.path.join(CSRC, "_build")
 SOURCES = ["stats.hip", "score.hip", "rank_batch.hip", "select.hip", "structured.hip", "groups.hip",
            "plan_device.hip", "hessian.hip", "factor.hip", "sweep.hip", "mlp.hip", "layer.hip", "attention.hip",
-           "noalloc.hip", "host.cpp"]
+           "noalloc.hip", "probe.hip", "host.cpp"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

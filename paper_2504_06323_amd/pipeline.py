@@ -47,7 +47,10 @@ class LayerState:
 
     @classmethod
     def create(cls, weights: Dict[str, torch.Tensor], proj_inputs: Dict[str, str],
-               act_channels: Dict[str, int], act_tokens: int, want_mask_bits: bool = True) -> "LayerState":
+               act_channels: Dict[str, int], act_tokens: int, want_mask_bits: bool = True,
+               share_outputs_with: Optional["LayerState"] = None) -> "LayerState":
+        """share_outputs_with: another layer's state of the same shapes whose masked copies, keep-bits and
+        workspace this one reuses (layers processed one after the other need only one set)."""
         dev = next(iter(weights.values())).device
         st = cls(weights=weights, proj_inputs=proj_inputs, device=dev)
         st.names = tuple(weights)
@@ -63,6 +66,9 @@ class LayerState:
         st.sparsity_dev = torch.zeros(n, dtype=torch.float64, device=dev)
         st.ks_dev = torch.zeros(n, dtype=torch.int32, device=dev)
         st.plan_flags = torch.zeros(2, dtype=torch.int32, device=dev)
+        if share_outputs_with is not None:
+            st.pruned, st.mask_bits, st.ws = share_outputs_with.pruned, share_outputs_with.mask_bits, share_outputs_with.ws
+            return st
         need = 256
         for a, ch in act_channels.items():
             need = max(need, prune.workspace_bytes(prune.OP_STATS, max(act_tokens, 1), ch))
@@ -204,6 +210,7 @@ def hessian_layer(ob: ObsState, acts: Dict[str, torch.Tensor], damp: float = 0.0
     """H = X^T X for every distinct projection input (one after the other: each fills the chip), each followed by
     damping and factorisation in place on a stream of its own."""
     main = torch.cuda.current_stream()
+    wait_factored(ob, main)     # a factorisation of an earlier call may still be running on these buffers
     order = sorted(range(len(acts)), key=lambda i: -list(acts.values())[i].shape[1])   # widest first: its
     names = list(acts)                                   # factorisation is the longest and overlaps the other Hessians
     for slot, i in enumerate(order):
@@ -226,6 +233,14 @@ def hessian_layer(ob: ObsState, acts: Dict[str, torch.Tensor], damp: float = 0.0
         done = torch.cuda.Event()
         done.record(side)
         ob.factored[a] = done
+
+
+def wait_factored(ob: ObsState, stream=None) -> None:
+    """Order `stream` (default: the current one) behind every factorisation hessian_layer has enqueued on its side
+    streams: needed before that stream reads or overwrites ob.hessian, ob.dead or ob.info."""
+    stream = torch.cuda.current_stream() if stream is None else stream
+    for done in ob.factored.values():
+        stream.wait_event(done)
 
 
 def obs_prune_layer(st: LayerState, ob: ObsState, sparsities: Sequence[float], in_place: bool = False) -> None:

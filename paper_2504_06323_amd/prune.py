@@ -60,6 +60,8 @@ _SIGNATURES = {
     "prune_struct_groups_workspace_bytes": (_sz, [_vp, _vp, _int, _vp, _vp, _int, _i64]),
     "prune_struct_groups": (_int, [_vp, _vp, _vp, _int, _vp, _vp, _vp, _int, _int, _i64, _u32, _vp, _vp, _vp, _vp,
                                    _vp, _sz, _vp]),
+    "prune_bandwidth_probe_sink_bytes": (_sz, [_int]),
+    "prune_bandwidth_probe": (_int, [_vp, _vp, _sz, _int, _int, _vp]),
     "prune_struct_compact": (_int, [_vp, _vp, _vp, _int, _i64, _i64, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
 }
 
@@ -524,6 +526,21 @@ def causal_attention(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, n_seqs: 
            load().prune_causal_attention(qp, kp, vp, op, _dtype_code(q), n_seqs, seq_len, heads, kv_heads, head_dim,
                                          ld_q, ld_k, ld_v, ld_o, _stream(stream)))
     return o
+
+
+PROBE_READ, PROBE_COPY = 0, 1
+
+
+def bandwidth_probe(src: torch.Tensor, dst: torch.Tensor, mode: int, blocks: int, stream=None) -> None:
+    """One plain streaming pass over src: read-only (dst gets checksums) or a copy into dst (prune_bandwidth_probe)."""
+    nbytes = src.numel() * src.element_size()
+    need = int(load().prune_bandwidth_probe_sink_bytes(blocks)) if mode == PROBE_READ else nbytes
+    if not (src.is_cuda and dst.is_cuda and src.is_contiguous() and dst.is_contiguous()):
+        raise ValueError("src and dst must be contiguous GPU tensors")
+    if dst.numel() * dst.element_size() < need:
+        raise ValueError(f"dst needs {need} bytes")
+    _check("prune_bandwidth_probe",
+           load().prune_bandwidth_probe(src.data_ptr(), dst.data_ptr(), nbytes, int(mode), int(blocks), _stream(stream)))
 
 
 def struct_compact(gate: torch.Tensor, up: torch.Tensor, down: torch.Tensor, r: int, group_mag: torch.Tensor,
