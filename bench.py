@@ -640,11 +640,7 @@ def run_prune_stage(args):
                 prune.plan_sparsity_device(t_count, t_numel, t_cols, table_layers, n_proj, p, cfg.lam, t_sparsity,
                                            t_ks, t_flags)
                 mark()
-                prune.select_mask_batch([st.weights[n] for n in st.names],
-                                        [st.norms[proj_inputs[n]] for n in st.names], None,
-                                        w_outs=[st.pruned[n] for n in st.names],
-                                        mask_bits=[st.mask_bits.get(n) for n in st.names],
-                                        ks_dev=t_ks[layer * n_proj:(layer + 1) * n_proj])
+                pipeline.prune_layer(st, None, ks_dev=t_ks[layer * n_proj:(layer + 1) * n_proj])
             mark()
             if r > 0:
                 pipeline.struct_layer(st, r, res)

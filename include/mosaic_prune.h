@@ -237,6 +237,10 @@ int prune_select_mask(const void *w, void *w_out, int dtype, int64_t rows, int64
  * k_dev (nullable): DEVICE pointer to this projection's k, read by the kernels when they run (for
  * example an element of prune_plan_sparsity_device's zeros_per_row_out); when set, the field k is
  * ignored and a value above cols counts as cols.
+ * row_sumsq (nullable): DEVICE float [rows]; receives, for every row, the sum of the squares of the row
+ * as it is written to w_out (float arithmetic, fixed order).  For the gate and up projections these
+ * are the row terms of prune_struct_compact's group magnitude, formed here while the masked row is
+ * still in registers instead of by another pass over the two matrices.
  */
 typedef struct {
     const void *w;
@@ -246,6 +250,7 @@ typedef struct {
     uint32_t k;
     uint32_t *mask_bits; /* nullable */
     const uint32_t *k_dev; /* nullable */
+    float *row_sumsq; /* nullable */
 } prune_select_item;
 
 /*
@@ -273,10 +278,15 @@ int prune_select_mask_batch(const prune_select_item *items, int n_items, int dty
  * gate, up are [inter, hidden], down is [hidden, inter]; all inputs and
  * outputs are contiguous.  Pass all three outputs or none (rank only).
  * 0 <= r < inter.  Outputs must not overlap inputs.
+ * gate_rowsq, up_rowsq (DEVICE float [inter], both or neither): the row sums of squares of gate and up
+ * when the caller already has them (prune_select_item.row_sumsq of the masking pass that produced the
+ * two matrices); the call then reads gate and up only for the gather.  They must belong to the gate
+ * and up handed in: the call does not check.
  */
 int prune_struct_compact(const void *gate, const void *up, const void *down, int dtype, int64_t inter,
-                         int64_t hidden, uint32_t r, float *group_mag, int32_t *kept_idx, void *gate_out,
-                         void *up_out, void *down_out, void *ws, size_t ws_bytes, void *stream);
+                         int64_t hidden, uint32_t r, const float *gate_rowsq, const float *up_rowsq,
+                         float *group_mag, int32_t *kept_idx, void *gate_out, void *up_out, void *down_out,
+                         void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Structured removal of coupled groups that span several projections (Section

@@ -41,7 +41,7 @@ def _run(cmd):
 def build(verbose: bool = True, jobs: int = 8) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(OBJ_DIR, exist_ok=True)
-    base = [hipcc] + HIPCC_FLAGS + ["-I", INCLUDE, "-I", CSRC]
+    base = [hipcc] + HIPCC_FLAGS + os.environ.get("MP_EXTRA_FLAGS", "").split() + ["-I", INCLUDE, "-I", CSRC]
     objs = [os.path.join(OBJ_DIR, os.path.splitext(s)[0] + ".o") for s in SOURCES]
     cmds = [base + ["-x", "hip", "-c", os.path.join(CSRC, s), "-o", o] for s, o in zip(SOURCES, objs)]
     if verbose:

@@ -62,6 +62,15 @@ struct Packet<bf16_t, 8> {
 #pragma unroll
         for (int i = 0; i < 4; ++i) raw[i] &= (km[2 * i] & 0x0000ffffu) | (km[2 * i + 1] & 0xffff0000u);
     }
+    // acc + sum of the squares of the eight elements, in element order (products of bf16 are exact in float; the
+    // two-element dot-product instruction is not used: its sum does not keep float precision)
+    __device__ __forceinline__ float add_squares(float acc) const {
+        float v[8];
+        to_float(v);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc = fmaf(v[i], v[i], acc);
+        return acc;
+    }
 };
 
 template <>
@@ -90,6 +99,14 @@ struct Packet<float, 8> {
     __device__ __forceinline__ void apply_keep_words(const uint32_t (&km)[8]) {
 #pragma unroll
         for (int i = 0; i < 8; ++i) raw[i >> 2][i & 3] &= km[i];
+    }
+    __device__ __forceinline__ float add_squares(float acc) const {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float v = __uint_as_float(raw[i >> 2][i & 3]);
+            acc = fmaf(v, v, acc);
+        }
+        return acc;
     }
 };
 

@@ -19,7 +19,8 @@ template <typename T, int BLOCK, int NCHUNK, bool FROM_SCORES>
 __device__ __forceinline__ void select_one_row(const T *wrow, T *orow, uint32_t cols,
                                                const float *__restrict__ norms, const float *__restrict__ srow,
                                                uint32_t k, int idx_bits, uint8_t *__restrict__ mrow,
-                                               uint32_t mask_row_bytes, SelectSmem<BLOCK> &sm) {
+                                               uint32_t mask_row_bytes, SelectSmem<BLOCK> &sm,
+                                               float *__restrict__ row_sumsq = nullptr) {
     const uint32_t tid = threadIdx.x;
     // All loads of the row are issued before anything waits on them.  A packet past the end of a
     // ragged row re-reads packet 0 (always valid) and is ignored later, so no load sits behind a branch.
@@ -73,6 +74,7 @@ __device__ __forceinline__ void select_one_row(const T *wrow, T *orow, uint32_t 
 
     const bool whole_bins = bound.idx == 0xffffffffu;  // uniform: no tie to split by column
     const uint32_t force_keep = nothing ? 0xffffffffu : 0u;  // without a search the flags decide
+    float sq = 0.f;  // squares of what this thread leaves in the row
 #pragma unroll
     for (int c = 0; c < NCHUNK; ++c) {
         const uint32_t col0 = (c * BLOCK + tid) * 8;
@@ -99,10 +101,30 @@ __device__ __forceinline__ void select_one_row(const T *wrow, T *orow, uint32_t 
                 pk[c].apply_keep(keep);
             }
             pk[c].store(orow + col0);
+            if (row_sumsq) sq = pk[c].add_squares(sq);
             if (mrow) {
                 mrow[col0 >> 3] = static_cast<uint8_t>(keep);
                 if (col0 + 8 == cols)  // owner of the last packet clears the padding of the last word
                     for (uint32_t b = (cols >> 3); b < mask_row_bytes; ++b) mrow[b] = 0;
+            }
+        }
+    }
+    if (row_sumsq) {
+        // Sum of squares of the masked row, as stored: thread sums in packet order, a fixed tree inside each
+        // wave, the waves in index order.  The waves meet once more for it, at the very end of the row, where
+        // the block would wait for its last wave anyway.
+        constexpr int NW = BLOCK / kWave;
+        sq = wave_sum(sq);
+        if constexpr (NW == 1) {
+            if (tid == 0) *row_sumsq = sq;
+        } else {
+            if ((tid & (kWave - 1)) == 0) sm.wave_tot[tid / kWave] = __float_as_uint(sq);
+            __syncthreads();
+            if (tid == 0) {
+                float total = 0.f;
+#pragma unroll
+                for (int i = 0; i < NW; ++i) total += __uint_as_float(sm.wave_tot[i]);
+                *row_sumsq = total;
             }
         }
     }
@@ -135,6 +157,7 @@ struct SelectItem {
     uint32_t cols, k, mask_row_bytes, row0;  // row0: first block of this projection
     int idx_bits, pad;
     const uint32_t *k_dev;  // when set: k is read from here (and capped at cols)
+    float *row_sumsq;       // when set: [rows], receives the sum of squares of every masked row
 };
 
 struct SelectArgs {
@@ -155,7 +178,7 @@ __global__ __launch_bounds__(BLOCK, (BLOCK == 64 ? 4 : NCHUNK <= 3 ? 8 : 6)) voi
                                             static_cast<T *>(it.w_out) + row * it.ld_out, it.cols, it.norms, nullptr,
                                             k, it.idx_bits,
                                             it.mask_bytes ? it.mask_bytes + row * it.mask_row_bytes : nullptr,
-                                            it.mask_row_bytes, sm);
+                                            it.mask_row_bytes, sm, it.row_sumsq ? it.row_sumsq + row : nullptr);
 }
 
 // any width / pitch / alignment; keys are recomputed from memory on every digit pass
@@ -222,6 +245,29 @@ __global__ __launch_bounds__(256) void fill_keep_all(uint32_t *__restrict__ mask
         const int64_t live = cols - q * 32;
         mask_words[i] = live >= 32 ? 0xffffffffu : ((1u << live) - 1u);
     }
+}
+
+// sum of squares of every row of a matrix (for projections that do not go through the packet kernels)
+template <typename T>
+__global__ __launch_bounds__(256) void rows_sumsq_plain(const T *__restrict__ w, int64_t rows, int64_t cols, int64_t ld,
+                                                        float *__restrict__ out) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t row = static_cast<int64_t>(blockIdx.x) * (256 / kWave) + threadIdx.x / kWave;
+    if (row >= rows) return;  // whole waves leave together
+    float acc = 0.f;
+    for (int64_t j = lane; j < cols; j += kWave) {
+        const float v = widen(w[row * ld + j]);
+        acc = fmaf(v, v, acc);
+    }
+    acc = wave_sum(acc);
+    if (lane == 0) out[row] = acc;
+}
+
+template <typename T>
+int launch_rows_sumsq_plain(const void *w, int64_t rows, int64_t cols, int64_t ld, float *out, hipStream_t stream) {
+    hipLaunchKernelGGL(rows_sumsq_plain<T>, dim3(static_cast<unsigned>(ceil_div(rows, 256 / kWave))), dim3(256), 0, stream,
+                       static_cast<const T *>(w), rows, cols, ld, out);
+    return launch_status();
 }
 
 // waves per row grow with the row width so that a thread holds at most 4 packets (32 keys)
@@ -385,6 +431,7 @@ extern "C" int prune_select_mask_batch(const prune_select_item *items, int n_ite
                                        q.k_dev ? 0u : q.k, q.mask_bits);
         if (st != PRUNE_OK) return st;
         if (q.k_dev && !aligned_to(q.k_dev, 4)) return PRUNE_ERR_ALIGNMENT;
+        if (q.row_sumsq && !aligned_to(q.row_sumsq, 4)) return PRUNE_ERR_ALIGNMENT;
     }
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     // projections that share a kernel variant go into one launch; the rest take the single-projection path
@@ -403,6 +450,12 @@ extern "C" int prune_select_mask_batch(const prune_select_item *items, int n_ite
                            : dtype == PRUNE_BF16 ? launch_generic_device_k<bf16_t>(q, stream)
                                                  : launch_generic_device_k<float>(q, stream);
             if (st != PRUNE_OK) return st;
+            if (q.row_sumsq) {  // the sums of the rows just written
+                const int st2 = dtype == PRUNE_BF16
+                                    ? launch_rows_sumsq_plain<bf16_t>(q.w_out, q.rows, q.cols, q.ld_out, q.row_sumsq, stream)
+                                    : launch_rows_sumsq_plain<float>(q.w_out, q.rows, q.cols, q.ld_out, q.row_sumsq, stream);
+                if (st2 != PRUNE_OK) return st2;
+            }
             done[i] = true;
             continue;
         }
@@ -445,6 +498,7 @@ extern "C" int prune_select_mask_batch(const prune_select_item *items, int n_ite
             it.idx_bits = index_bits_for(r.cols);
             it.pad = 0;
             it.k_dev = r.k_dev;
+            it.row_sumsq = r.row_sumsq;
             total_rows += r.rows;
             done[j] = true;
         }

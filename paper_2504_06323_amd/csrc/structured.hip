@@ -45,6 +45,13 @@ __global__ __launch_bounds__(kBlock) void row_sumsq_pair(const T *__restrict__ g
     if (lane == 0) g[c] = sg + su;
 }
 
+// g[c] = a[c] + b[c]: the row terms of the group magnitude when the caller brings them along
+__global__ __launch_bounds__(kBlock) void pair_sum(const float *__restrict__ a, const float *__restrict__ b, int64_t n,
+                                                   float *__restrict__ g) {
+    const int64_t i = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x;
+    if (i < n) g[i] = a[i] + b[i];
+}
+
 // One block: select the r smallest (g, c) pairs, write the other channels' indices ascending.
 __global__ __launch_bounds__(kRankBlock) void rank_channels(const float *__restrict__ g, int64_t inter, uint32_t r,
                                                             int idx_bits, int32_t *__restrict__ kept_idx,
@@ -356,11 +363,14 @@ int launch_gather_cols(const T *src, T *dst, const int32_t *kept, int64_t n_rows
 
 template <typename T>
 int struct_dispatch(const T *gate, const T *up, const T *down, int64_t inter, int64_t hidden, uint32_t r,
-                    float *group_mag, int32_t *kept_idx, T *gate_out, T *up_out, T *down_out, void *ws,
-                    hipStream_t stream) {
+                    const float *gate_rowsq, const float *up_rowsq, float *group_mag, int32_t *kept_idx, T *gate_out,
+                    T *up_out, T *down_out, void *ws, hipStream_t stream) {
     const int waves_per_block = kBlock / kWave;
     const dim3 rgrid(static_cast<unsigned>(ceil_div(inter, waves_per_block)));
-    if (packet_ok(gate, hidden, hidden) && packet_ok(up, hidden, hidden))
+    if (gate_rowsq)
+        hipLaunchKernelGGL(pair_sum, dim3(static_cast<unsigned>(ceil_div(inter, kBlock))), dim3(kBlock), 0, stream,
+                           gate_rowsq, up_rowsq, inter, group_mag);
+    else if (packet_ok(gate, hidden, hidden) && packet_ok(up, hidden, hidden))
         hipLaunchKernelGGL((row_sumsq_pair<T, 8>), rgrid, dim3(kBlock), 0, stream, gate, up, inter, hidden, group_mag);
     else
         hipLaunchKernelGGL((row_sumsq_pair<T, 1>), rgrid, dim3(kBlock), 0, stream, gate, up, inter, hidden, group_mag);
@@ -394,29 +404,32 @@ size_t struct_workspace_bytes(int64_t inter, int64_t hidden) { return colsum_wor
 }  // namespace mp
 
 extern "C" int prune_struct_compact(const void *gate, const void *up, const void *down, int dtype, int64_t inter,
-                                    int64_t hidden, uint32_t r, float *group_mag, int32_t *kept_idx, void *gate_out,
-                                    void *up_out, void *down_out, void *ws, size_t ws_bytes, void *stream_) {
+                                    int64_t hidden, uint32_t r, const float *gate_rowsq, const float *up_rowsq,
+                                    float *group_mag, int32_t *kept_idx, void *gate_out, void *up_out, void *down_out,
+                                    void *ws, size_t ws_bytes, void *stream_) {
     using namespace mp;
     if (!valid_dtype(dtype)) return PRUNE_ERR_DTYPE;
     if (inter <= 0 || hidden <= 0 || inter > 0x7fffffff || ceil_div(hidden, 16) > 65535) return PRUNE_ERR_SHAPE;
     if (!gate || !up || !down || !group_mag || !kept_idx || !ws) return PRUNE_ERR_NULL;
     const int n_out = (gate_out ? 1 : 0) + (up_out ? 1 : 0) + (down_out ? 1 : 0);
     if (n_out != 0 && n_out != 3) return PRUNE_ERR_NULL;
+    if ((gate_rowsq == nullptr) != (up_rowsq == nullptr)) return PRUNE_ERR_NULL;
     if (static_cast<int64_t>(r) >= inter) return PRUNE_ERR_RANGE;
     const size_t es = elem_size(dtype);
     if (!aligned_to(gate, es) || !aligned_to(up, es) || !aligned_to(down, es) || !aligned_to(group_mag, 4) ||
-        !aligned_to(kept_idx, 4) || !aligned_to(ws, 16) ||
+        !aligned_to(kept_idx, 4) || !aligned_to(ws, 16) || (gate_rowsq && !aligned_to(gate_rowsq, 4)) ||
+        (up_rowsq && !aligned_to(up_rowsq, 4)) ||
         (n_out && (!aligned_to(gate_out, es) || !aligned_to(up_out, es) || !aligned_to(down_out, es))))
         return PRUNE_ERR_ALIGNMENT;
     if (ws_bytes < struct_workspace_bytes(inter, hidden)) return PRUNE_ERR_WORKSPACE;
     hipStream_t stream = static_cast<hipStream_t>(stream_);
     if (dtype == PRUNE_BF16)
         return struct_dispatch(static_cast<const bf16_t *>(gate), static_cast<const bf16_t *>(up),
-                               static_cast<const bf16_t *>(down), inter, hidden, r, group_mag, kept_idx,
+                               static_cast<const bf16_t *>(down), inter, hidden, r, gate_rowsq, up_rowsq, group_mag, kept_idx,
                                static_cast<bf16_t *>(gate_out), static_cast<bf16_t *>(up_out),
                                static_cast<bf16_t *>(down_out), ws, stream);
     return struct_dispatch(static_cast<const float *>(gate), static_cast<const float *>(up),
-                           static_cast<const float *>(down), inter, hidden, r, group_mag, kept_idx,
+                           static_cast<const float *>(down), inter, hidden, r, gate_rowsq, up_rowsq, group_mag, kept_idx,
                            static_cast<float *>(gate_out), static_cast<float *>(up_out),
                            static_cast<float *>(down_out), ws, stream);
 }

@@ -37,6 +37,8 @@ class LayerState:
     tau: torch.Tensor = None            # [n_proj] float32
     pruned: Dict[str, torch.Tensor] = field(default_factory=dict)   # masked copies (phase 2 output)
     mask_bits: Dict[str, torch.Tensor] = field(default_factory=dict)
+    rowsq: Dict[str, torch.Tensor] = field(default_factory=dict)    # gate / up: row sums of squares of the masked copies
+    rowsq_valid: bool = False                                        # set by prune_layer, cleared by whoever rewrites pruned
     ws: torch.Tensor = None
     names: Tuple[str, ...] = ()
     numels_dev: torch.Tensor = None     # [n_proj] int64, constant
@@ -67,7 +69,8 @@ class LayerState:
         st.ks_dev = torch.zeros(n, dtype=torch.int32, device=dev)
         st.plan_flags = torch.zeros(2, dtype=torch.int32, device=dev)
         if share_outputs_with is not None:
-            st.pruned, st.mask_bits, st.ws = share_outputs_with.pruned, share_outputs_with.mask_bits, share_outputs_with.ws
+            o = share_outputs_with
+            st.pruned, st.mask_bits, st.ws, st.rowsq = o.pruned, o.mask_bits, o.ws, o.rowsq
             return st
         need = 256
         for a, ch in act_channels.items():
@@ -81,6 +84,8 @@ class LayerState:
         if "gate" in weights:
             inter, hidden = weights["gate"].shape
             need = max(need, prune.workspace_bytes(prune.OP_STRUCT, inter, hidden))
+            if "up" in weights:
+                st.rowsq = {n: torch.empty(inter, dtype=torch.float32, device=dev) for n in ("gate", "up")}
         st.ws = torch.empty(need, dtype=torch.uint8, device=dev)
         return st
 
@@ -131,14 +136,21 @@ def plan_device(st: LayerState, p: float, lam: float, scope: int = prune.SCOPE_G
                                st.ks_dev, st.plan_flags, scope=scope)
 
 
-def prune_layer(st: LayerState, ks: Optional[Sequence[int]], in_place: bool = False) -> None:
+def prune_layer(st: LayerState, ks: Optional[Sequence[int]], in_place: bool = False,
+                ks_dev: Optional[torch.Tensor] = None) -> None:
     """Phase 2, unstructured: zero the k lowest-metric entries per row of every projection.
-    ks = None takes the zeros per row that plan_device left in st.ks_dev."""
+    ks = None takes the zeros per row from ks_dev (default: what plan_device left in st.ks_dev).
+    The masking pass also leaves the row sums of squares of the masked gate and up in st.rowsq, which
+    struct_layer hands to the structured pass."""
     names = st.names
+    if ks_dev is None and ks is None:
+        ks_dev = st.ks_dev
     prune.select_mask_batch([st.weights[n] for n in names], [st.norms[st.proj_inputs[n]] for n in names],
                             None if ks is None else [int(k) for k in ks],
                             w_outs=None if in_place else [st.pruned[n] for n in names],
-                            mask_bits=[st.mask_bits.get(n) for n in names], ks_dev=st.ks_dev if ks is None else None)
+                            mask_bits=[st.mask_bits.get(n) for n in names], ks_dev=ks_dev if ks is None else None,
+                            row_sumsq=[st.rowsq.get(n) for n in names])
+    st.rowsq_valid = bool(st.rowsq) and not in_place     # the sums describe st.pruned
 
 
 @dataclass
@@ -164,8 +176,10 @@ def alloc_struct(st: LayerState, r: int, compact: bool = True) -> StructResult:
 def struct_layer(st: LayerState, r: int, out: StructResult, masked: bool = True) -> None:
     """Phase 2, structured: rank MLP channels on the (masked) weights, drop r, compact."""
     src = st.pruned if masked else st.weights
+    have = masked and st.rowsq_valid
     prune.struct_compact(src["gate"], src["up"], src["down"], r, out.group_mag, out.kept_idx,
-                         out.gate, out.up, out.down, ws=st.ws)
+                         out.gate, out.up, out.down, ws=st.ws, gate_rowsq=st.rowsq["gate"] if have else None,
+                         up_rowsq=st.rowsq["up"] if have else None)
 
 
 # ----------------------------------------------------------------------------------------------------------------
@@ -263,6 +277,7 @@ def obs_prune_layer(st: LayerState, ob: ObsState, sparsities: Sequence[float], i
         done = torch.cuda.Event()
         done.record(side)
         main.wait_event(done)
+    st.rowsq_valid = False      # st.pruned no longer holds what the masking pass summed
 
 
 # ----------------------------------------------------------------------------------------------------------------

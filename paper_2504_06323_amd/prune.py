@@ -62,7 +62,8 @@ _SIGNATURES = {
                                    _vp, _sz, _vp]),
     "prune_bandwidth_probe_sink_bytes": (_sz, [_int]),
     "prune_bandwidth_probe": (_int, [_vp, _vp, _sz, _int, _int, _vp]),
-    "prune_struct_compact": (_int, [_vp, _vp, _vp, _int, _i64, _i64, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "prune_struct_compact": (_int, [_vp, _vp, _vp, _int, _i64, _i64, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz,
+                                    _vp]),
 }
 
 
@@ -76,7 +77,7 @@ class SelectItem(ctypes.Structure):
     """Mirror of the C struct prune_select_item."""
 
     _fields_ = [("w", _vp), ("w_out", _vp), ("rows", _i64), ("cols", _i64), ("ld_w", _i64), ("ld_out", _i64),
-                ("norms", _vp), ("k", _u32), ("mask_bits", _vp), ("k_dev", _vp)]
+                ("norms", _vp), ("k", _u32), ("mask_bits", _vp), ("k_dev", _vp), ("row_sumsq", _vp)]
 
 
 class PruneError(RuntimeError):
@@ -337,11 +338,13 @@ def select_mask(w: torch.Tensor, norms: Optional[torch.Tensor], k: int, w_out: O
 def select_mask_batch(ws_: Sequence[torch.Tensor], norms: Sequence[torch.Tensor], ks: Optional[Sequence[int]],
                       w_outs: Optional[Sequence[Optional[torch.Tensor]]] = None,
                       mask_bits: Optional[Sequence[Optional[torch.Tensor]]] = None, stream=None,
-                      ks_dev: Optional[torch.Tensor] = None) -> None:
+                      ks_dev: Optional[torch.Tensor] = None,
+                      row_sumsq: Optional[Sequence[Optional[torch.Tensor]]] = None) -> None:
     """prune_select_mask for several projections, same-width projections sharing a launch
     (prune_select_mask_batch).  In place where w_outs (or an entry of it) is None.
     The k of projection i is ks[i], or, when ks_dev (int32 / uint32 GPU tensor, one entry per
-    projection) is given, whatever ks_dev[i] holds when the kernels run."""
+    projection) is given, whatever ks_dev[i] holds when the kernels run.  row_sumsq[i] (float32 [rows],
+    optional) receives the sum of squares of every masked row of projection i."""
     n = len(ws_)
     if (ks is None) == (ks_dev is None):
         raise ValueError("give either ks or ks_dev")
@@ -371,7 +374,9 @@ def select_mask_batch(ws_: Sequence[torch.Tensor], norms: Sequence[torch.Tensor]
         arr[i] = SelectItem(ptr, out_ptr, rows, cols, ld, ld_out, _vector(norms[i], "norms", torch.float32, cols),
                             0 if ks is None else int(ks[i]),
                             None if mb is None else _vector(mb, "mask_bits", mb.dtype, rows * ((cols + 31) // 32)),
-                            None if k_base is None else k_base + 4 * i)
+                            None if k_base is None else k_base + 4 * i,
+                            None if row_sumsq is None or row_sumsq[i] is None
+                            else _vector(row_sumsq[i], "row_sumsq", torch.float32, rows))
     _check("prune_select_mask_batch", load().prune_select_mask_batch(arr, n, code, None, 0, _stream(stream)))
 
 
@@ -546,8 +551,10 @@ def bandwidth_probe(src: torch.Tensor, dst: torch.Tensor, mode: int, blocks: int
 def struct_compact(gate: torch.Tensor, up: torch.Tensor, down: torch.Tensor, r: int, group_mag: torch.Tensor,
                    kept_idx: torch.Tensor, gate_out: Optional[torch.Tensor] = None,
                    up_out: Optional[torch.Tensor] = None, down_out: Optional[torch.Tensor] = None,
-                   ws: Optional[torch.Tensor] = None, stream=None) -> None:
-    """Rank MLP channels by group magnitude, drop the r lowest, gather the rest (prune_struct_compact)."""
+                   ws: Optional[torch.Tensor] = None, stream=None, gate_rowsq: Optional[torch.Tensor] = None,
+                   up_rowsq: Optional[torch.Tensor] = None) -> None:
+    """Rank MLP channels by group magnitude, drop the r lowest, gather the rest (prune_struct_compact).
+    gate_rowsq / up_rowsq: the row sums of squares of gate and up when a masking pass already produced them."""
     for t, name in ((gate, "gate"), (up, "up"), (down, "down")):
         if not (t.is_cuda and t.is_contiguous() and t.dim() == 2 and t.dtype == gate.dtype):
             raise ValueError(f"{name} must be a contiguous 2-D GPU tensor of the common dtype")
@@ -567,7 +574,9 @@ def struct_compact(gate: torch.Tensor, up: torch.Tensor, down: torch.Tensor, r: 
     ws_ptr, ws_bytes, _keep = _workspace(ws, workspace_bytes(OP_STRUCT, inter, hidden), gate.device)
     _check("prune_struct_compact",
            load().prune_struct_compact(gate.data_ptr(), up.data_ptr(), down.data_ptr(), _dtype_code(gate), inter,
-                                       hidden, int(r), _vector(group_mag, "group_mag", torch.float32, inter),
+                                       hidden, int(r), _vector(gate_rowsq, "gate_rowsq", torch.float32, inter),
+                                       _vector(up_rowsq, "up_rowsq", torch.float32, inter),
+                                       _vector(group_mag, "group_mag", torch.float32, inter),
                                        _vector(kept_idx, "kept_idx", torch.int32, n_kept), outs[0], outs[1], outs[2],
                                        ws_ptr, ws_bytes, _stream(stream)))
 

@@ -369,6 +369,60 @@ def test_toy_layer_end_to_end(lib):
     assert np.array_equal(to_np(res.down), wd)
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("shape,k", [((96, 4096), 2048), ((40, 5120), 3000), ((33, 1000), 400), ((64, 14336), 7000),
+                                     ((50, 256), 0), ((20, 77), 30), ((9, 4096), 4096)])
+def test_select_row_sums_of_squares(lib, dtype, shape, k):
+    """The masking pass also hands out the sum of squares of every masked row (the row terms of the structured
+    pass's group magnitude): against the oracle on the stored masked rows, for the packet kernels, the any-shape
+    kernel and the copy-through path."""
+    rows, cols = shape
+    w = synth.random_matrix(rows, cols, dtype, seed=rows + cols, device=DEV, scale=0.02, zero_frac=0.1)
+    norms = (torch.rand(cols, device=DEV) * 3 + 0.5).float()
+    out = torch.full_like(w, 7.0)
+    sums = torch.full((rows,), float("nan"), dtype=torch.float32, device=DEV)
+    prune.select_mask_batch([w], [norms], [k], w_outs=[out], row_sumsq=[sums])
+    _sync()
+    masked = to_np(out).astype(np.float64)
+    want = (masked * masked).sum(axis=1)
+    got = to_np(sums).astype(np.float64)
+    assert np.count_nonzero(masked == 0, axis=1).min() >= k
+    assert np.max(np.abs(got - want)) <= 2e-6 * np.max(want) + 1e-30
+    sums2 = torch.empty_like(sums)
+    prune.select_mask_batch([w], [norms], [k], w_outs=[out], row_sumsq=[sums2])
+    _sync()
+    assert np.array_equal(to_np(sums).view(np.uint32), to_np(sums2).view(np.uint32))          # reproducible
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_struct_with_row_sums_from_the_masking_pass(lib, dtype):
+    """prune_struct_compact given the row sums agrees with the call that forms them itself: magnitudes to
+    rounding, and -- ranking the magnitudes each call reports -- both with the oracle."""
+    inter, hidden, r = 688, 256, 137
+    gate, up = (synth.random_matrix(inter, hidden, dtype, seed=s, device=DEV, scale=0.02) for s in (1, 2))
+    down = synth.random_matrix(hidden, inter, dtype, seed=3, device=DEV, scale=0.02)
+    norms = torch.ones(hidden, dtype=torch.float32, device=DEV)
+    mg, mu = torch.empty_like(gate), torch.empty_like(up)
+    sg, su = (torch.empty(inter, dtype=torch.float32, device=DEV) for _ in range(2))
+    prune.select_mask_batch([gate, up], [norms, norms], [hidden // 2, hidden // 2], w_outs=[mg, mu], row_sumsq=[sg, su])
+    res = []
+    for given in (False, True):
+        g = torch.empty(inter, dtype=torch.float32, device=DEV)
+        kept = torch.empty(inter - r, dtype=torch.int32, device=DEV)
+        outs = [torch.empty((inter - r, hidden), dtype=dtype, device=DEV), torch.empty((inter - r, hidden), dtype=dtype, device=DEV),
+                torch.empty((hidden, inter - r), dtype=dtype, device=DEV)]
+        prune.struct_compact(mg, mu, down, r, g, kept, *outs, gate_rowsq=sg if given else None, up_rowsq=su if given else None)
+        _sync()
+        want_g = orc.group_magnitude(to_np(mg), to_np(mu), to_np(down))
+        assert rel_err(to_np(g), want_g) < 2e-6
+        want_kept = orc.struct_rank(to_np(g), r)
+        assert np.array_equal(to_np(kept), want_kept)
+        wg, wu, wd = orc.struct_compact(to_np(mg), to_np(mu), to_np(down), want_kept)
+        assert np.array_equal(to_np(outs[0]), wg) and np.array_equal(to_np(outs[1]), wu) and np.array_equal(to_np(outs[2]), wd)
+        res.append(to_np(g))
+    assert rel_err(res[0], res[1]) < 1e-6
+
+
 # ----------------------------------------------------------------- planner on the device
 
 @pytest.mark.parametrize("scope", ["global", "category"])

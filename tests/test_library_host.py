@@ -204,10 +204,12 @@ def test_error_paths_return_before_any_launch(lib):
     assert ad(fake, fake, fake, 1, 8, 8, 8, 4, 8, None) == E["shape"]
     assert ad(fake, None, fake, 1, 8, 8, 8, 8, 8, None) == E["null"]
     st = lib.prune_struct_compact
-    assert st(fake, fake, fake, 1, 8, 8, 8, fake, fake, None, None, None, fake, 1 << 20, None) == E["rng"]  # r >= inter
-    assert st(fake, fake, fake, 1, 8, 8, 1, fake, fake, fake, None, None, fake, 1 << 20, None) == E["null"]  # 1 of 3 outs
-    assert st(fake, fake, fake, 1, 8, 8, 1, fake, fake, None, None, None, fake, 0, None) == E["ws"]
-    assert st(fake, fake, None, 1, 8, 8, 1, fake, fake, None, None, None, fake, 1 << 20, None) == E["null"]
+    assert st(fake, fake, fake, 1, 8, 8, 8, None, None, fake, fake, None, None, None, fake, 1 << 20, None) == E["rng"]  # r >= inter
+    assert st(fake, fake, fake, 1, 8, 8, 1, None, None, fake, fake, fake, None, None, fake, 1 << 20, None) == E["null"]  # 1 of 3 outs
+    assert st(fake, fake, fake, 1, 8, 8, 1, None, None, fake, fake, None, None, None, fake, 0, None) == E["ws"]
+    assert st(fake, fake, None, 1, 8, 8, 1, None, None, fake, fake, None, None, None, fake, 1 << 20, None) == E["null"]
+    assert st(fake, fake, fake, 1, 8, 8, 1, fake, None, fake, fake, None, None, None, fake, 1 << 20, None) == E["null"]  # one row-sum vector of two
+    assert st(fake, fake, fake, 1, 8, 8, 1, odd, fake, fake, fake, None, None, None, fake, 1 << 20, None) == E["align"]
     sg = lib.prune_struct_groups
     P = lambda *v: (ctypes.c_void_p * len(v))(*v)
     I = lambda *v: (ctypes.c_int64 * len(v))(*v)
