@@ -12,6 +12,7 @@ namespace mp {
 namespace {
 
 constexpr int kPlanBlock = 256;
+constexpr int kPlanStage = 2048;  // entries of a group that are staged in LDS for the ordered sum
 
 __device__ __forceinline__ double block_min_max(double v, bool take_max, double *scratch) {
     const int tid = threadIdx.x;
@@ -38,6 +39,7 @@ __global__ __launch_bounds__(kPlanBlock) void plan_kernel(const unsigned long lo
                                                           uint32_t *__restrict__ zeros_per_row,
                                                           int *__restrict__ flags) {
     __shared__ double scratch[kPlanBlock];
+    __shared__ double stage[kPlanStage];
     __shared__ double mean_sh;
     __shared__ int clamped_sh, invalid_sh;
     const int tid = threadIdx.x;
@@ -69,14 +71,31 @@ __global__ __launch_bounds__(kPlanBlock) void plan_kernel(const unsigned long lo
             __syncthreads();
             continue;
         }
+        // the normalised ratios also go to LDS when the group fits, so that the one thread that adds them up
+        // in index order reads them at LDS latency, eight loads at a time, not one global load per addition
+        const bool staged = per_group <= kPlanStage;
         for (int j = tid; j < per_group; j += kPlanBlock) {
             const int i = g + j * n_groups;
-            sparsity[i] = (sparsity[i] - lo) / (hi - lo);
+            const double v = (sparsity[i] - lo) / (hi - lo);
+            sparsity[i] = v;
+            if (staged) stage[j] = v;
         }
         __syncthreads();
         if (tid == 0) {
             double mean_hat = 0.0;
-            for (int j = 0; j < per_group; ++j) mean_hat += sparsity[g + j * n_groups];
+            if (staged) {
+                int j = 0;
+                for (; j + 8 <= per_group; j += 8) {
+                    double v[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) v[u] = stage[j + u];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) mean_hat += v[u];
+                }
+                for (; j < per_group; ++j) mean_hat += stage[j];
+            } else {
+                for (int j = 0; j < per_group; ++j) mean_hat += sparsity[g + j * n_groups];
+            }
             mean_sh = mean_hat / static_cast<double>(per_group);
         }
         __syncthreads();

@@ -44,7 +44,7 @@ __global__ __launch_bounds__(kProbeBlock) void probe_copy(const u32x4 *__restric
 #pragma unroll
         for (int u = 0; u < kProbeUnroll; ++u) {
             const int64_t i = base + u * kProbeBlock + threadIdx.x;
-            if (i < n_packets) dst[i] = v[u];
+            if (i < n_packets) __builtin_nontemporal_store(v[u], dst + i);
         }
     }
 }

@@ -38,10 +38,10 @@ def _popcount32(a):
     return (a * 0x01010101 >> 24) & 0xFF
 
 
-def _check_norms(x, norms_gpu, seed):
+def _check_norms(x, norms_gpu, seed, n_channels=24):
     """Sampled channels (plus the largest-norm ones, i.e. the planted outliers) against the oracle."""
     c = x.shape[1]
-    idx = np.union1d(_sample(c, 24, seed), np.argsort(to_np(norms_gpu))[-4:])
+    idx = np.union1d(_sample(c, n_channels, seed), np.argsort(to_np(norms_gpu))[-4:])
     cols = to_np(x[:, torch.as_tensor(idx, device=x.device)])
     want = orc.column_norms(cols)
     got = to_np(norms_gpu)[idx]
@@ -81,13 +81,25 @@ def _check_mask(w, m32, k, w_out, mask_bits, seed, n_rows=12):
     assert np.array_equal(out[idx], orc.apply_mask(w_np[idx], pruned))
 
 
-def _run_layer(cfg_name, check_struct=True):
+def _check_sampled_rows(w, norms, k, w_out, mask_bits, seed, n_rows):
+    """Sampled rows only: the oracle's stable-sort selection on the kernel-precision metric of those rows."""
+    rows, cols = w.shape
+    idx = _sample(rows, n_rows, seed)
+    sel = torch.as_tensor(idx, device=w.device)
+    w_np, out = to_np(w[sel]), to_np(w_out[sel])
+    m32 = _metric_f32(w_np, to_np(norms))
+    pruned = orc.select_smallest_per_row(m32, k)
+    assert np.array_equal(out, orc.apply_mask(w_np, pruned))
+    assert np.array_equal(to_np(mask_bits[sel]).view(np.uint32), orc.pack_keep_bits(pruned))
+
+
+def _run_layer(cfg_name, check_struct=True, layer=0):
     cfg = synth.CONFIGS[cfg_name]
     shapes = synth.projection_shapes(cfg)
     act_shapes = synth.activation_shapes(cfg)
-    print(f"[fullsize] {cfg_name}: generating inputs", flush=True)
-    weights = {n: synth.make_weight(cfg, 0, n, DEV) for n, _, _, _ in shapes}
-    acts = {a: synth.make_activation(cfg, 0, a, DEV) for a in act_shapes}
+    print(f"[fullsize] {cfg_name}: generating inputs of layer {layer}", flush=True)
+    weights = {n: synth.make_weight(cfg, layer, n, DEV) for n, _, _, _ in shapes}
+    acts = {a: synth.make_activation(cfg, layer, a, DEV) for a in act_shapes}
     st = pipeline.LayerState.create(weights, {n: a for n, _, _, a in shapes}, act_shapes, cfg.n_tokens)
     print(f"[fullsize] {cfg_name}: phase 1", flush=True)
     pipeline.rank_layer(st, acts, cfg.alpha)
@@ -164,37 +176,86 @@ def test_llama3_8b_layer_gqa_composite(lib):
 
 @pytest.mark.timeout(600)
 def test_llama2_13b_stress_layer(lib):
-    """configs[4], one layer: 256 x 4096 calibration tokens, x100 outlier channels, 60 % + 30 %."""
+    """configs[4], layers 0 and 39: 256 x 4096 calibration tokens, x100 outlier channels, 60 % + 30 %."""
     _run_layer("llama2_13b_stress")
+    _run_layer("llama2_13b_stress", layer=39, check_struct=False)
+
+
+def test_long_calibration_statistic_error_does_not_grow(lib):
+    """One million tokens, a channel a hundred times larger than the rest: single-precision sums are folded into
+    doubles every 1024 rows, so the statistic of the large channel stays within 2e-6 of the float64 oracle."""
+    cfg = synth.CONFIGS["llama2_13b_stress"]
+    x = synth.make_activation(cfg, 1, "attn_in", DEV)                  # [1048576, 5120]
+    c = x.shape[1]
+    sumsq, norms = (torch.empty(c, dtype=torch.float32, device=DEV) for _ in range(2))
+    prune.stats_norms(x, sumsq, norms)
+    torch.cuda.synchronize()
+    big = np.argsort(to_np(norms))[-5:]                                # the planted x100 channels
+    idx = np.union1d(big, _sample(c, 16, 7))
+    cols = to_np(x[:, torch.as_tensor(idx, device=x.device)])
+    want = orc.column_sumsq(cols)
+    got = to_np(sumsq)[idx].astype(np.float64)
+    err = np.abs(got - want) / want
+    assert err.max() < 2e-6, err.max()
+    assert (to_np(norms)[big] > 50 * np.median(to_np(norms))).all()     # these are the planted ones
+
+
+def _popcount_rows(bits):
+    """Keep-bits per row, counted on the device (int32 words)."""
+    b = bits.to(torch.int64) & 0xFFFFFFFF
+    b = b - ((b >> 1) & 0x55555555)
+    b = (b & 0x33333333) + ((b >> 2) & 0x33333333)
+    b = (b + (b >> 4)) & 0x0F0F0F0F
+    return ((b * 0x01010101) >> 24 & 0xFF).sum(dim=1)
+
+
+def _check_mask_on_device(w, w_out, mask_bits, k):
+    """Properties that hold at any size, evaluated on the GPU for every row of a projection: exactly k entries
+    pruned (by the keep-bits), pruned entries zero, survivors bit-identical."""
+    rows, cols = w.shape
+    assert bool((_popcount_rows(mask_bits) == cols - k).all())
+    shifts = torch.arange(32, device=w.device, dtype=torch.int32)
+    keep = ((mask_bits[:, :, None] >> shifts) & 1).reshape(rows, -1)[:, :cols].bool()
+    a, b = w.view(torch.int16), w_out.view(torch.int16)
+    assert bool((b[~keep] == 0).all())
+    assert bool((a[keep] == b[keep]).all())
 
 
 @pytest.mark.timeout(900)
 def test_full_model_llama3_8b_sweep(lib):
-    """configs[3]: 32 layers, 224 projections ranked once, pruned at 30 / 50 / 70 % reusing the ranking."""
+    """configs[3]: 32 layers, 224 projections ranked once, pruned at 30 / 50 / 70 % reusing the ranking.
+
+    Every layer: norms on sampled channels, threshold and bit-exact outlier count of all seven projections
+    (the host forms the kernel-precision metric), and at every target the any-size mask properties on the device
+    for every row of every projection.  Sampled-row oracle selection on every layer at one target (p = 0.5) and
+    on layers 0 and 31 at all three."""
     cfg = synth.CONFIGS["llama3_8b_full"]
     shapes = synth.projection_shapes(cfg)
     act_shapes = synth.activation_shapes(cfg)
     proj_inputs = {n: a for n, _, _, a in shapes}
     n_proj = len(shapes)
-    checked_layers = (0, 31)
-    states, counts, metrics = [], [], {}
+    end_layers = (0, cfg.n_layers - 1)
+    states, counts = [], []
     for layer in range(cfg.n_layers):
         if layer % 8 == 0:
             print(f"[fullsize] full model: ranking layer {layer}", flush=True)
         weights = {n: synth.make_weight(cfg, layer, n, DEV) for n, _, _, _ in shapes}
         acts = {a: synth.make_activation(cfg, layer, a, DEV) for a in act_shapes}
         st = pipeline.LayerState.create(weights, proj_inputs, act_shapes, cfg.n_tokens,
-                                        want_mask_bits=layer in checked_layers)
-        if states:                       # one masked copy and one workspace serve every layer
-            st.pruned, st.ws = states[0].pruned, states[0].ws
+                                        share_outputs_with=states[0] if states else None)
         pipeline.rank_layer(st, acts, cfg.alpha)
         torch.cuda.synchronize()
-        if layer in checked_layers:
-            for i, a in enumerate(act_shapes):
-                _check_norms(acts[a], st.norms[a], seed=1000 * layer + i)
-            ssums, taus, cnts = st.score_sum.tolist(), to_np(st.tau), st.count.tolist()
-            for i, (n, r, c, a) in enumerate(shapes):
-                metrics[(layer, n)] = _check_rank(weights[n], st.norms[a], cfg.alpha, ssums[i], cnts[i], taus[i])
+        for i, a in enumerate(act_shapes):
+            _check_norms(acts[a], st.norms[a], seed=1000 * layer + i, n_channels=24 if layer in end_layers else 6)
+        ssums, taus, cnts = st.score_sum.tolist(), to_np(st.tau), st.count.tolist()
+        for i, (n, r, c, a) in enumerate(shapes):
+            if layer in end_layers:                       # the float64 oracle as well
+                _check_rank(weights[n], st.norms[a], cfg.alpha, ssums[i], cnts[i], taus[i])
+            else:                                         # threshold and bit-exact count in the kernel's precision
+                m32 = _metric_f32(to_np(weights[n]), to_np(st.norms[a]))
+                assert taus[i] == orc.threshold_f32(cfg.alpha, ssums[i], m32.size)
+                assert cnts[i] == orc.count_above(m32, taus[i])
+                assert abs(ssums[i] - float(m32.sum(dtype=np.float64))) <= 1e-6 * ssums[i]
         del acts
         states.append(st)
         counts += st.count.tolist()
@@ -212,9 +273,41 @@ def test_full_model_llama3_8b_sweep(lib):
         for layer, st in enumerate(states):
             lk = ks[layer * n_proj:(layer + 1) * n_proj]
             pipeline.prune_layer(st, lk)                      # phase 2 only: the ranking is reused
-            if layer in checked_layers:
+            for i, (n, r, c, a) in enumerate(shapes):
+                _check_mask_on_device(st.weights[n], st.pruned[n], st.mask_bits[n], lk[i])
+            if layer in end_layers or p == 0.5:
                 torch.cuda.synchronize()
                 for i, (n, r, c, a) in enumerate(shapes):
-                    _check_mask(st.weights[n], metrics[(layer, n)], lk[i], st.pruned[n], st.mask_bits[n],
-                                seed=layer * 10 + i, n_rows=6)
+                    if layer in end_layers:
+                        m32 = _metric_f32(to_np(st.weights[n]), to_np(st.norms[a]))
+                        _check_mask(st.weights[n], m32, lk[i], st.pruned[n], st.mask_bits[n], seed=layer * 10 + i, n_rows=6)
+                    else:
+                        _check_sampled_rows(st.weights[n], st.norms[a], lk[i], st.pruned[n], st.mask_bits[n],
+                                            seed=layer * 10 + i, n_rows=3)
         torch.cuda.synchronize()
+
+
+def test_scaling_the_activations_by_two_changes_nothing_that_is_counted(lib):
+    """A power-of-two factor on the activations scales every norm and metric exactly, so outlier counts, zeros per
+    row and masks must be bit-identical (the norm needs no normalisation by tokens or samples)."""
+    cfg = synth.CONFIGS["llama3_8b_layer"]
+    shapes = synth.projection_shapes(cfg)
+    act_shapes = synth.activation_shapes(cfg)
+    weights = {n: synth.make_weight(cfg, 3, n, DEV) for n, _, _, _ in shapes}
+    results = []
+    for factor in (1.0, 2.0):
+        acts = {a: synth.make_activation(cfg, 3, a, DEV, n_seqs=8) * factor for a in act_shapes}
+        st = pipeline.LayerState.create(weights, {n: a for n, _, _, a in shapes}, act_shapes, 8 * cfg.seq_len)
+        pipeline.rank_layer(st, acts, cfg.alpha)
+        pipeline.plan_device(st, cfg.p, cfg.lam)
+        pipeline.prune_layer(st, None)
+        torch.cuda.synchronize()
+        results.append((st.count.tolist(), st.ks_dev.tolist(), {n: st.mask_bits[n].clone() for n in st.names},
+                        {a: to_np(st.norms[a]) for a in act_shapes}))
+        del acts
+    (c1, k1, m1, n1), (c2, k2, m2, n2) = results
+    assert c1 == c2 and k1 == k2
+    for n in m1:
+        assert torch.equal(m1[n], m2[n])
+    for a in n1:
+        assert np.array_equal(n2[a], 2.0 * n1[a])
