@@ -45,20 +45,24 @@ def test_rotary_vs_oracle(lib, dtype):
     assert np.max(np.abs(to_np(x).astype(np.float64) - want)) <= (ULP[dtype] + 5e-5) * np.max(np.abs(want))
 
 
-def _attention_case(dtype, n_seqs, seq_len, heads, kv_heads, d, seed):
+def _attention_case(dtype, n_seqs, seq_len, heads, kv_heads, d, seed, elem_ulp=2.0 ** -8):
     tokens = n_seqs * seq_len
     q, k, v = _mat(tokens, heads * d, dtype, seed), _mat(tokens, kv_heads * d, dtype, seed + 1), _mat(tokens, kv_heads * d, dtype, seed + 2)
     o = prune.causal_attention(q, k, v, n_seqs, seq_len, heads, kv_heads, d)
     _sync()
     got = to_np(o).astype(np.float64).reshape(n_seqs, seq_len, heads, d)
     q64, k64, v64 = (to_np(t).astype(np.float64) for t in (q, k, v))
-    worst = 0.0
+    worst, worst_elem = 0.0, 0.0
     for b in range(n_seqs):
         sl = slice(b * seq_len, (b + 1) * seq_len)
-        want = lay.causal_attention(q64[sl].reshape(seq_len, heads, d), k64[sl].reshape(seq_len, kv_heads, d),
-                                    v64[sl].reshape(seq_len, kv_heads, d))
-        worst = max(worst, float(np.max(np.abs(got[b] - want))))
-    return worst, float(np.max(np.abs(v64)))
+        q3, k3 = q64[sl].reshape(seq_len, heads, d), k64[sl].reshape(seq_len, kv_heads, d)
+        want = lay.causal_attention(q3, k3, v64[sl].reshape(seq_len, kv_heads, d))
+        # the same probabilities applied to |v|: the scale of what was added up for each output element
+        mix = lay.causal_attention(q3, k3, np.abs(v64[sl]).reshape(seq_len, kv_heads, d))
+        err = np.abs(got[b] - want)
+        worst = max(worst, float(np.max(err)))
+        worst_elem = max(worst_elem, float(np.max(err / (elem_ulp * (np.abs(want) + mix) + 1e-30))))
+    return worst, float(np.max(np.abs(v64))), worst_elem
 
 
 @pytest.mark.parametrize("dtype,case", [(torch.bfloat16, (2, 100, 4, 2, 64)), (torch.float32, (2, 100, 4, 2, 64)),
@@ -66,7 +70,7 @@ def _attention_case(dtype, n_seqs, seq_len, heads, kv_heads, d, seed):
                                         (torch.float32, (2, 64, 2, 1, 128))])
 def test_attention_plain_kernel_vs_oracle(lib, dtype, case):
     """Shapes that take the any-shape kernel (fp32, or heads that are not 128 wide)."""
-    worst, vmax = _attention_case(dtype, *case, seed=10)
+    worst, vmax, _ = _attention_case(dtype, *case, seed=10)
     assert worst <= (ULP[dtype] + 2e-5) * vmax * 4
 
 
@@ -75,8 +79,11 @@ def test_attention_plain_kernel_vs_oracle(lib, dtype, case):
 def test_attention_matrix_core_kernel_vs_oracle(lib, case):
     """bf16, 128-wide heads.  Probabilities enter the second product as bf16 (half an ulp each, averaging out over
     the keys of a query) and the output is rounded to bf16."""
-    worst, vmax = _attention_case(torch.bfloat16, *case, seed=20)
+    worst, vmax, worst_elem = _attention_case(torch.bfloat16, *case, seed=20)
     assert worst <= 2.0 ** -7 * vmax
+    # element by element: the rounding of the output (half a bf16 ulp of its value) plus the rounding of the
+    # probabilities that entered the second product as bf16 (half an ulp each, of sum_t p_t |v_t|), 2^-8 for both
+    assert worst_elem <= 1.0, worst_elem
     q = _mat(case[0] * case[1], case[2] * 128, torch.bfloat16, 30)
     k = _mat(case[0] * case[1], case[3] * 128, torch.bfloat16, 31)
     v = _mat(case[0] * case[1], case[3] * 128, torch.bfloat16, 32)
