@@ -80,7 +80,38 @@ __device__ __forceinline__ void select_one_row(const T *wrow, T *orow, uint32_t 
         const uint32_t col0 = (c * BLOCK + tid) * 8;
         if (col0 < cols) {
             uint32_t keep = 0;
-            if (whole_bins) {
+            if constexpr (sizeof(T) == 2) {
+                if (whole_bins && search) {
+                    // The common case, eight elements in 24 instructions: a compare of the key with the bound
+                    // (kept iff key > bound; a NaN key, bit 31 set, counts as kept), a conditional move that
+                    // zeroes the element's half of its word in place, and an add-with-carry that shifts the
+                    // compare's result into the keep-bits (elements 7 ... 0, so that element e lands in bit e).
+                    uint32_t r0 = pk[c].raw[0], r1 = pk[c].raw[1], r2 = pk[c].raw[2], r3 = pk[c].raw[3];
+                    const uint32_t zero = 0u, b = __builtin_amdgcn_readfirstlane(bound.key);
+#define MP_KEEP_STEP(KEY, REG, HALF)                                                                              \
+    "v_cmp_lt_u32_e32 vcc, %[b], " KEY "\n\t"                                                                      \
+    "v_cndmask_b32_sdwa " REG ", %[z], " REG ", vcc dst_sel:" HALF " dst_unused:UNUSED_PRESERVE src0_sel:" HALF    \
+    " src1_sel:" HALF "\n\t"                                                                                       \
+    "v_addc_co_u32_e32 %[kp], vcc, %[kp], %[kp], vcc\n\t"
+                    asm volatile(MP_KEEP_STEP("%[k7]", "%[r3]", "WORD_1") MP_KEEP_STEP("%[k6]", "%[r3]", "WORD_0")
+                                 MP_KEEP_STEP("%[k5]", "%[r2]", "WORD_1") MP_KEEP_STEP("%[k4]", "%[r2]", "WORD_0")
+                                 MP_KEEP_STEP("%[k3]", "%[r1]", "WORD_1") MP_KEEP_STEP("%[k2]", "%[r1]", "WORD_0")
+                                 MP_KEEP_STEP("%[k1]", "%[r0]", "WORD_1") MP_KEEP_STEP("%[k0]", "%[r0]", "WORD_0")
+                                 : [kp] "+&v"(keep), [r0] "+&v"(r0), [r1] "+&v"(r1), [r2] "+&v"(r2), [r3] "+&v"(r3)
+                                 : [b] "s"(b), [z] "v"(zero), [k0] "v"(key[c][0]), [k1] "v"(key[c][1]),
+                                   [k2] "v"(key[c][2]), [k3] "v"(key[c][3]), [k4] "v"(key[c][4]),
+                                   [k5] "v"(key[c][5]), [k6] "v"(key[c][6]), [k7] "v"(key[c][7])
+                                 : "vcc");
+#undef MP_KEEP_STEP
+                    pk[c].raw[0] = r0;
+                    pk[c].raw[1] = r1;
+                    pk[c].raw[2] = r2;
+                    pk[c].raw[3] = r3;
+                }
+            }
+            if (sizeof(T) == 2 && whole_bins && search) {
+                // done above
+            } else if (whole_bins) {
                 // key > bound  <=>  bound - key is negative (keys and bound are below 2^31, or a NaN key
                 // with bit 31, which then counts as kept): the sign, spread over the word, is the mask
                 uint32_t km[8];
