@@ -10,16 +10,21 @@ Section 4.1.4 "Calibration").  The trained checkpoints and the calibration
 corpus are not available, so random tensors with planted heavy-tailed outlier
 channels stand in for them.
 
-Every tensor is a pure function of (SEED_BASE, config id, layer, tensor id,
-chunk id) and of the device kind it is generated on; a test always hands the
-*same bytes* to both sides, so generator arithmetic never enters parity.
+Every tensor is a pure function of (SEED_BASE, config id, layer, tensor id):
+the random numbers come from the counter-based generator of counter_rng.py,
+which exists as NumPy code (tensors asked for on the host) and as a HIP kernel
+(tensors asked for on the GPU) with identical results, so the same call gives
+the same bytes wherever it runs.
 """
 from __future__ import annotations
 
 from dataclasses import dataclass, field
 from typing import Dict, List, Optional, Tuple
 
+import numpy as np
 import torch
+
+from . import counter_rng
 
 SEED_BASE = 250406323
 
@@ -123,65 +128,86 @@ def activation_shapes(cfg: LayerConfig) -> Dict[str, int]:
     return {"attn_in": cfg.hidden, "o_in": cfg.q_out, "mlp_in": cfg.hidden, "down_in": cfg.inter}
 
 
-def _generator(device: torch.device, seed: int) -> torch.Generator:
-    g = torch.Generator(device=device)
-    g.manual_seed(seed)
-    return g
-
-
 def outlier_count(frac: float, n: int) -> int:
     return max(1, int(round(frac * n)))
 
 
-def _outlier_indices(n: int, frac: float, seed: int) -> torch.Tensor:
-    """First entries of a seeded permutation (always drawn on the host)."""
-    g = torch.Generator(device="cpu")
-    g.manual_seed(seed)
-    return torch.randperm(n, generator=g)[: outlier_count(frac, n)]
+def _outlier_indices(n: int, frac: float, seed: int) -> np.ndarray:
+    """The first entries of a seeded permutation of 0 .. n-1 (a partial Fisher-Yates shuffle, always on the host)."""
+    m = outlier_count(frac, n)
+    draws = counter_rng.bits32(m, 0, seed)
+    perm = np.arange(n, dtype=np.int64)
+    for j in range(m):
+        t = j + int(draws[j]) % (n - j)
+        perm[j], perm[t] = perm[t], perm[j]
+    return perm[:m].copy()
+
+
+_HOST_CHUNK_ROWS_ELEMS = 1 << 22   # elements generated per NumPy pass on the host (bounds the float64 temporaries)
+
+
+def _fill(rows: int, cols: int, dtype: torch.dtype, device: torch.device, seed: int, scale: float,
+          col_scale: Optional[np.ndarray], kind: Optional[np.ndarray]) -> torch.Tensor:
+    """[rows, cols] tensor of the generator's values (see counter_rng.fill_normal_host for the element rule)."""
+    if dtype not in (torch.float32, torch.bfloat16):
+        raise ValueError(f"unsupported dtype {dtype}")
+    if device.type == "cpu":
+        out = torch.empty((rows, cols), dtype=dtype)
+        step = max(1, _HOST_CHUNK_ROWS_ELEMS // max(cols, 1))
+        for r0 in range(0, rows, step):
+            r1 = min(rows, r0 + step)
+            blk = counter_rng.fill_normal_host(r1 - r0, cols, seed, 0, scale, col_scale, kind, first_row=r0)
+            out[r0:r1] = torch.from_numpy(blk).to(dtype)   # float32 -> bfloat16 rounds to nearest even, as the kernel does
+        return out
+    lib = counter_rng.device_lib()
+    with torch.cuda.device(device):
+        out = torch.empty((rows, cols), dtype=dtype, device=device)
+        cs = None if col_scale is None else torch.from_numpy(np.ascontiguousarray(col_scale, dtype=np.float32)).to(device)
+        kd = None if kind is None else torch.from_numpy(np.ascontiguousarray(kind, dtype=np.uint8)).to(device)
+        rc = lib.synth_fill_normal(out.data_ptr(), 1 if dtype == torch.bfloat16 else 0, rows, cols, cols, seed, 0,
+                                   None if cs is None else cs.data_ptr(), None if kd is None else kd.data_ptr(),
+                                   float(scale), torch.cuda.current_stream().cuda_stream)
+        if rc != 0:
+            raise RuntimeError("synth_fill_normal refused its arguments or the launch failed")
+        if cs is not None:
+            cs.record_stream(torch.cuda.current_stream())
+        if kd is not None:
+            kd.record_stream(torch.cuda.current_stream())
+    return out
 
 
 def make_weight(cfg: LayerConfig, layer: int, proj: str, device="cpu") -> torch.Tensor:
-    """Projection weight [rows, cols], iid N(0, 0.02^2) with planted outlier input channels."""
+    """Projection weight [rows, cols], iid N(0, 0.02^2) with planted outlier input channels: columns ten times
+    larger ("scale10") or drawn from a Student-t law with three degrees of freedom ("student_t3")."""
     device = torch.device(device)
     rows, cols = {n: (r, c) for n, r, c, _ in projection_shapes(cfg)}[proj]
     tid = _PROJ_IDS[proj]
-    g = _generator(device, stream_seed(cfg.config_id, layer, tid, 0))
-    w = torch.empty((rows, cols), dtype=torch.float32, device=device)
-    w.normal_(0.0, 0.02, generator=g)
-    idx = _outlier_indices(cols, cfg.w_outlier_frac, stream_seed(cfg.config_id, layer, tid, 1)).to(device)
+    idx = _outlier_indices(cols, cfg.w_outlier_frac, stream_seed(cfg.config_id, layer, tid, 1))
+    col_scale = kind = None
     if cfg.w_outlier_kind == "scale10":
-        w[:, idx] *= 10.0
+        col_scale = np.ones(cols, dtype=np.float32)
+        col_scale[idx] = 10.0
     elif cfg.w_outlier_kind == "student_t3":
-        z = torch.empty((4, rows, idx.numel()), dtype=torch.float32, device=device)
-        z.normal_(0.0, 1.0, generator=g)
-        t3 = z[0] / torch.sqrt((z[1] ** 2 + z[2] ** 2 + z[3] ** 2) / 3.0)
-        w[:, idx] = 0.02 * t3
+        kind = np.zeros(cols, dtype=np.uint8)
+        kind[idx] = 1
     else:
         raise ValueError(cfg.w_outlier_kind)
-    return w.to(cfg.dtype).contiguous()
+    return _fill(rows, cols, cfg.dtype, device, stream_seed(cfg.config_id, layer, tid, 0), 0.02, col_scale, kind)
 
 
 def make_activation(cfg: LayerConfig, layer: int, which: str, device="cpu",
-                    n_seqs: Optional[int] = None, seqs_per_chunk: int = 16) -> torch.Tensor:
-    """Calibration activation [n_seqs * seq_len, channels], iid N(0,1) with scaled outlier channels.
-
-    Generated chunk by chunk (a chunk is `seqs_per_chunk` sequences) so the
-    temporary footprint stays small for multi-GB tensors.
-    """
+                    n_seqs: Optional[int] = None) -> torch.Tensor:
+    """Calibration activation [n_seqs * seq_len, channels], iid N(0,1) with scaled outlier channels.  A tensor of
+    fewer sequences is a prefix of the full one."""
     device = torch.device(device)
     ch = activation_shapes(cfg)[which]
     tid = _INPUT_IDS[which]
     n_seqs = cfg.n_seqs if n_seqs is None else n_seqs
-    t_total = n_seqs * cfg.seq_len
-    x = torch.empty((t_total, ch), dtype=cfg.dtype, device=device)
-    idx = _outlier_indices(ch, cfg.x_outlier_frac, stream_seed(cfg.config_id, layer, tid, 1 << 20)).to(device)
-    for c, s0 in enumerate(range(0, n_seqs, seqs_per_chunk)):
-        s1 = min(n_seqs, s0 + seqs_per_chunk)
-        g = _generator(device, stream_seed(cfg.config_id, layer, tid, c))
-        blk = x[s0 * cfg.seq_len: s1 * cfg.seq_len]
-        blk.normal_(0.0, 1.0, generator=g)
-        blk[:, idx] *= cfg.x_outlier_scale
-    return x
+    idx = _outlier_indices(ch, cfg.x_outlier_frac, stream_seed(cfg.config_id, layer, tid, 1))
+    col_scale = np.ones(ch, dtype=np.float32)
+    col_scale[idx] = cfg.x_outlier_scale
+    return _fill(n_seqs * cfg.seq_len, ch, cfg.dtype, device, stream_seed(cfg.config_id, layer, tid, 0), 1.0,
+                 col_scale, None)
 
 
 def layer_numel(cfg: LayerConfig) -> int:
@@ -190,13 +216,23 @@ def layer_numel(cfg: LayerConfig) -> int:
 
 def random_matrix(rows: int, cols: int, dtype: torch.dtype, seed: int, device="cpu",
                   scale: float = 1.0, zero_frac: float = 0.0) -> torch.Tensor:
-    """Free-form seeded matrix for edge-case tests (ragged shapes, planted zeros)."""
+    """Free-form seeded matrix for edge-case tests (ragged shapes, planted zeros): N(0, scale^2) entries, each
+    replaced by zero when its 32-bit draw from a second seed falls below zero_frac * 2^32."""
     device = torch.device(device)
-    g = _generator(device, stream_seed(99, 0, seed, 0))
-    m = torch.empty((rows, cols), dtype=torch.float32, device=device)
-    m.normal_(0.0, scale, generator=g)
+    if rows == 0 or cols == 0:
+        return torch.zeros((rows, cols), dtype=dtype, device=device)
+    m = _fill(rows, cols, dtype, device, stream_seed(99, 0, seed, 0), scale, None, None)
     if zero_frac > 0.0:
-        u = torch.empty((rows, cols), dtype=torch.float32, device=device)
-        u.uniform_(0.0, 1.0, generator=g)
-        m[u < zero_frac] = 0.0
-    return m.to(dtype).contiguous()
+        limit = min(int(zero_frac * 4294967296.0), 4294967295)
+        zseed = stream_seed(99, 0, seed, 1)
+        if device.type == "cpu":
+            draws = torch.from_numpy(counter_rng.bits32(rows * cols, 0, zseed).astype(np.int64))
+        else:
+            with torch.cuda.device(device):
+                raw = torch.empty(rows * cols, dtype=torch.int32, device=device)
+                if counter_rng.device_lib().synth_fill_bits(raw.data_ptr(), rows * cols, zseed, 0,
+                                                            torch.cuda.current_stream().cuda_stream) != 0:
+                    raise RuntimeError("synth_fill_bits refused its arguments or the launch failed")
+                draws = raw.to(torch.int64) & 0xFFFFFFFF
+        m[(draws < limit).view(rows, cols)] = 0.0
+    return m
