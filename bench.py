@@ -286,10 +286,15 @@ def run_obs_stage(args):
         s, _, _ = pipeline.plan(st.count.tolist(), numels, cols, 1, len(shapes), cfg.p, cfg.lam)
         if record:
             m[1].record()
-        pipeline.hessian_layer(ob, acts, on_big=(lambda e: gram_events.append(e)) if record else None, big=big)
-        if record:
-            m[2].record()
-        pipeline.obs_prune_layer(st, ob, s)
+        if args.obs_two_phases:
+            pipeline.hessian_layer(ob, acts, on_big=(lambda e: gram_events.append(e)) if record else None, big=big)
+            if record:
+                m[2].record()
+            pipeline.obs_prune_layer(st, ob, s)
+        else:
+            if record:
+                m[2].record()
+            pipeline.obs_layer(st, ob, acts, s, on_big=(lambda e: gram_events.append(e)) if record else None, big=big)
         if record:
             m[3].record()
             marks_all.append(m)
@@ -318,7 +323,9 @@ def run_obs_stage(args):
            "config": {"workload": f"{cfg.name}: one layer, {numel} weights in bf16, {cfg.n_tokens} calibration tokens, "
                                   f"target sparsity {cfg.p}, planner targets {[round(v, 4) for v in s]}, "
                                   f"achieved sparsity {zeros / numel:.4f}"},
-           "ms_rank_and_plan": round(seg[0], 3), "ms_hessians_and_factors": round(seg[1], 3), "ms_sweeps": round(seg[2], 3),
+           "ms_rank_and_plan": round(seg[0], 3),
+           **({"ms_hessians_and_factors": round(seg[1], 3), "ms_sweeps": round(seg[2], 3)} if args.obs_two_phases
+              else {"ms_hessians_factors_and_sweeps_as_one_schedule": round(seg[2], 3)}),
            "roofline": {"bound": "mfma", "kernel": f"gram_tiles_bf16 + gram_reduce on [{acts[big].shape[0]}, {acts[big].shape[1]}]",
                         "achieved": round(achieved, 1), "peak": 2500.0, "unit": "TFLOP/s",
                         "frac": round(achieved / 2500.0, 4), "traffic": None, "avg_launch_ms": round(launch_ms, 4),
@@ -336,7 +343,8 @@ def run_obs_stage(args):
                                "sample": f"projection {name}: 256 of {weights[name].shape[0]} rows, 8192 of {cfg.n_tokens} "
                                          f"calibration tokens (the Hessian and its factor cost the same for any number "
                                          f"of rows); NumPy float64, {dt:.1f} s"}
-    log(f"obs stage: {ms:.2f} ms per layer | rank+plan {seg[0]:.2f} | hessians+factors {seg[1]:.2f} | sweeps {seg[2]:.2f}")
+    log(f"obs stage: {ms:.2f} ms per layer | rank+plan {seg[0]:.2f} | " + (f"hessians+factors {seg[1]:.2f} | sweeps {seg[2]:.2f}"
+        if args.obs_two_phases else f"hessians, factors and sweeps as one schedule {seg[2]:.2f}"))
     print(json.dumps(out), flush=True)
 
 
@@ -786,6 +794,9 @@ def main():
     ap.add_argument("--struct-frac", type=float, default=0.2,
                     help="fraction of MLP channels removed structurally when the workload itself names none")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--obs-two-phases", action="store_true",
+                    help="obs stage: all Hessians and factors, then all sweeps (two timed segments) instead of one "
+                         "schedule in which the sweeps of a projection input start as soon as its factor is there")
     ap.add_argument("--host-plan", action="store_true",
                     help="run the projection planner on the host (the step then waits for the outlier counts)")
     ap.add_argument("--cpu-sample-den", type=int, default=4)

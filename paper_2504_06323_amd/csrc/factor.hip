@@ -8,7 +8,8 @@
 // to the diagonal; (2) blocked right-looking factorisation from the last 128-column block to the first: factor
 // the diagonal block in LDS (and invert that 128 x 128 triangle), turn the column panel above it into R's
 // panel with one product, and downdate the leading part with the panel's outer product.  The products run on
-// the fp32 matrix cores.  R overwrites the upper triangle of h; the strictly lower triangle is left as it was.
+// the fp32 matrix cores.  R overwrites the upper triangle of h; what the strictly lower triangle holds afterwards is
+// unspecified.
 #include "gemm_f32.hpp"
 #include "tri_inverse.hpp"
 
@@ -18,6 +19,7 @@ namespace {
 
 constexpr int kNB = kTriN;          // block size of the factorisation
 constexpr int kDiagPitch = kTriPitch;
+constexpr int kFactorGroup = 4;     // panels whose downdates of the far part of H are applied together
 
 // dead[j] = (h_jj == 0); those get h_jj = 1; then h_jj += damp * mean(diag).  One block; the mean is a double sum in
 // a fixed order.
@@ -50,86 +52,153 @@ __global__ __launch_bounds__(1024) void damp_diagonal(float *__restrict__ h, int
 // over the upper triangle, and inv(R_bb) (upper triangular, zeros below) to dinv [kNB x kNB] (pitch kNB, the part
 // beyond sz zero-filled).  A pivot that is not positive is reported in *info (1-based column) and poisons the
 // block with NaN rather than stopping.
+//
+// The 128 columns are taken in eight groups of 16, last group first.  For a group: sixteen lanes of the first wave
+// factor its 16 x 16 diagonal block and invert it, a row per lane, exchanging values lane to lane (no memory, no
+// barrier: 16 dependent steps of a square root and a division each, the latency-bound core of the whole
+// factorisation); then all threads turn the 16 columns above the block into R's columns with that inverse and
+// downdate the groups to the left with the outer product of those columns.  Three barriers per group instead of
+// two per column.
 __global__ __launch_bounds__(256) void factor_diagonal_block(float *__restrict__ h, int64_t ld, int64_t c0, int sz,
                                                              float *__restrict__ dinv, int *__restrict__ info) {
     __shared__ float d[kNB][kDiagPitch];
     __shared__ float u[kNB][kDiagPitch];
-    __shared__ float col[kNB];
-    __shared__ float piv;
+    constexpr int kG = 16, kPanelPitch = 20;  // 80-byte rows: 16-byte aligned, eight rows cover all banks
+    static_assert(3 * kG * kG + 2 * kNB * kPanelPitch <= kNB * kDiagPitch, "the scratch fits into u");
+    // u is not needed before the inversion at the end: until then it holds what the groups exchange
+    float *scratch = &u[0][0];
+    float (*blk)[kG] = reinterpret_cast<float (*)[kG]>(scratch);                     // a group's diagonal block
+    float (*rb)[kG] = reinterpret_cast<float (*)[kG]>(scratch + kG * kG);            // its factor
+    float (*ub)[kG] = reinterpret_cast<float (*)[kG]>(scratch + 2 * kG * kG);        // the factor's inverse
+    float (*pd)[kPanelPitch] = reinterpret_cast<float (*)[kPanelPitch]>(scratch + 3 * kG * kG);   // columns above it
+    float (*pp)[kPanelPitch] = reinterpret_cast<float (*)[kPanelPitch]>(scratch + 3 * kG * kG + kNB * kPanelPitch);
     const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
-    // The factorisation keeps the block in registers: thread (ty, tx) of a 16 x 16 grid owns the entries
-    // (ty + 16 a, tx + 16 b), a, b = 0..7; only the scaled column of a step travels through LDS, so no step waits
-    // on a read-modify-write of LDS.
+    // Thread (ty, tx) of a 16 x 16 grid owns the entries (ty + 16 a, tx + 16 b), a, b = 0..7, in registers.  Rows
+    // and columns past sz carry a unit diagonal, which leaves the live part as it is.
     float t[8][8];
 #pragma unroll
     for (int a = 0; a < 8; ++a)
 #pragma unroll
         for (int b2 = 0; b2 < 8; ++b2) {
             const int i = ty + 16 * a, k = tx + 16 * b2;
-            t[a][b2] = (i < sz && k < sz && i <= k) ? h[(c0 + i) * ld + c0 + k] : 0.f;
+            t[a][b2] = (i < sz && k < sz && i <= k) ? h[(c0 + i) * ld + c0 + k] : (i == k && i >= sz) ? 1.f : 0.f;
         }
-    for (int e = tid; e < kNB * kDiagPitch; e += 256) {
-        (&d[0][0])[e] = 0.f;
-        (&u[0][0])[e] = 0.f;
-    }
-    if (tid < kNB) col[tid] = 0.f;
-    __syncthreads();
-    // last column first: r_jj = sqrt(d_jj); R[i][j] = d[i][j] / r_jj (i < j); d[i][k] -= R[i][j] R[k][j] (i <= k < j).
-    // The 16-wide group jb of column j is a compile-time constant of the unrolled outer loop, so every register
-    // of t is addressed statically; jt = j % 16 runs inside.
-    const int last = sz - 1;
+    for (int e = tid; e < kNB * kDiagPitch; e += 256) (&d[0][0])[e] = 0.f;
+    float uinv[8];  // this thread's entry of the inverse of every group's diagonal block
 #pragma unroll
     for (int jb = 7; jb >= 0; --jb) {
-        if (jb > (last >> 4)) continue;  // uniform: groups past the live part
-        for (int jt = (jb == (last >> 4) ? (last & 15) : 15); jt >= 0; --jt) {
-            const int j = 16 * jb + jt;
-            if (ty == jt && tx == jt) {
-                const float pivot = t[jb][jb];
-                if (!(pivot > 0.f) && info) atomicMax(info, static_cast<int>(c0) + j + 1);
-                piv = sqrtf(pivot);
-            }
-            __syncthreads();
-            const float rjj = piv;
-            if (tx == jt) {
+        blk[ty][tx] = ty <= tx ? t[jb][jb] : 0.f;
 #pragma unroll
-                for (int a = 0; a <= jb; ++a) {
-                    const int i = ty + 16 * a;
-                    if (i < j) t[a][jb] = t[a][jb] / rjj;
-                    if (i == j) t[a][jb] = rjj;
-                    if (i <= j) col[i] = t[a][jb];
+        for (int a = 0; a < jb; ++a) pd[ty + 16 * a][tx] = t[a][jb];
+        __syncthreads();
+        if (tid < kG) {
+            // lane i holds row i of the block; last column first: r_jj = sqrt(d_jj), R[i][j] = d[i][j] / r_jj (i < j),
+            // d[i][k] -= R[i][j] R[k][j] (i <= k < j).  Entries below the diagonal are carried along and never read.
+            const int lane = tid;
+            float r[kG], w[kG];
+#pragma unroll
+            for (int q = 0; q < kG; q += 4) {
+                const f32x4 v = *reinterpret_cast<const f32x4 *>(&blk[lane][q]);
+                r[q] = v[0];
+                r[q + 1] = v[1];
+                r[q + 2] = v[2];
+                r[q + 3] = v[3];
+            }
+#pragma unroll
+            for (int j = kG - 1; j >= 0; --j) {
+                const float pivot = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, r[j]), j));
+                if (!(pivot > 0.f) && info && lane == 0) atomicMax(info, static_cast<int>(c0) + 16 * jb + j + 1);
+                const float rjj = sqrtf(pivot);
+                r[j] = lane < j ? r[j] / rjj : lane == j ? rjj : 0.f;
+#pragma unroll
+                for (int k = 0; k < j; ++k) {
+                    const float rkj = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, r[j]), k));
+                    r[k] = fmaf(-r[j], rkj, r[k]);
                 }
             }
-            __syncthreads();
-            // Entries (i <= k < j) must be downdated.  Entries below the diagonal are never read, so they may be
-            // updated along with the rest (with whatever col holds for them); the one condition left is k < j in
-            // the column group of j itself.
-            float ci[8], ck[8];
+            // row i of W = R^-1 from W R = I, column by column: w_ik = (delta_ik - sum_{m < k} w_im r_mk) / r_kk
+            // (zero for k < i by itself)
 #pragma unroll
-            for (int a = 0; a <= jb; ++a) {
-                ci[a] = col[ty + 16 * a];
-                ck[a] = col[tx + 16 * a];
+            for (int k = 0; k < kG; ++k) {
+                float acc = lane == k ? 1.f : 0.f;
+#pragma unroll
+                for (int m = 0; m < k; ++m) {
+                    const float rmk = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, r[k]), m));
+                    acc = fmaf(-w[m], rmk, acc);
+                }
+                const float rkk = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, r[k]), k));
+                w[k] = acc / rkk;
             }
-            ck[jb] = tx < jt ? ck[jb] : 0.f;
 #pragma unroll
-            for (int b2 = 0; b2 <= jb; ++b2)
-#pragma unroll
-                for (int a = 0; a <= jb; ++a) t[a][b2] = fmaf(-ci[a], ck[b2], t[a][b2]);
-            // (the next step's writes to col and piv come after its first barrier, which every thread reaches only
-            // after these reads)
+            for (int q = 0; q < kG; q += 4) {
+                *reinterpret_cast<f32x4 *>(&rb[lane][q]) = f32x4{r[q], r[q + 1], r[q + 2], r[q + 3]};
+                *reinterpret_cast<f32x4 *>(&ub[lane][q]) = f32x4{w[q], w[q + 1], w[q + 2], w[q + 3]};
+            }
         }
+        __syncthreads();
+        t[jb][jb] = rb[ty][tx];
+        uinv[jb] = ub[ty][tx];
+        if (jb > 0) {
+            // R[i][c] = sum_m D[i][m] W[c][m] for the rows i above the block (W is zero left of its diagonal)
+            float wrow[kG];
+#pragma unroll
+            for (int q = 0; q < kG; q += 4) {
+                const f32x4 v = *reinterpret_cast<const f32x4 *>(&ub[tx][q]);
+                wrow[q] = v[0];
+                wrow[q + 1] = v[1];
+                wrow[q + 2] = v[2];
+                wrow[q + 3] = v[3];
+            }
+#pragma unroll
+            for (int a = 0; a < jb; ++a) {
+                float acc = 0.f;
+#pragma unroll
+                for (int q = 0; q < kG; q += 4) {
+                    const f32x4 v = *reinterpret_cast<const f32x4 *>(&pd[ty + 16 * a][q]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc = fmaf(v[e], wrow[q + e], acc);
+                }
+                t[a][jb] = acc;
+                pp[ty + 16 * a][tx] = acc;
+            }
+            __syncthreads();
+            // d[i][k] -= sum_m R[i][m] R[k][m] for the groups to the left (entries below the diagonal are never
+            // read, so they are updated along with the rest)
+#pragma unroll
+            for (int q = 0; q < kG; q += 4) {
+                f32x4 ci[7], ck[7];
+#pragma unroll
+                for (int a = 0; a < jb; ++a) {
+                    ci[a] = *reinterpret_cast<const f32x4 *>(&pp[ty + 16 * a][q]);
+                    ck[a] = *reinterpret_cast<const f32x4 *>(&pp[tx + 16 * a][q]);
+                }
+#pragma unroll
+                for (int a = 0; a < jb; ++a)
+#pragma unroll
+                    for (int b2 = 0; b2 < jb; ++b2)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) t[a][b2] = fmaf(-ci[a][e], ck[b2][e], t[a][b2]);
+            }
+        }
+        // (the next group's writes to blk and pd come before its first barrier; blk was last read before this
+        // group's second barrier and pd before its third, which every thread has passed by then)
     }
+    __syncthreads();  // all reads of the scratch are done: u can be cleared
+    for (int e = tid; e < kNB * kDiagPitch; e += 256) (&u[0][0])[e] = 0.f;
+    __syncthreads();
 #pragma unroll
     for (int a = 0; a < 8; ++a)
 #pragma unroll
         for (int b2 = 0; b2 < 8; ++b2) {
             const int i = ty + 16 * a, k = tx + 16 * b2;
-            if (i < sz && k < sz && i <= k) {
-                h[(c0 + i) * ld + c0 + k] = t[a][b2];
+            if (i <= k) {
                 d[i][k] = t[a][b2];
+                if (i < sz && k < sz) h[(c0 + i) * ld + c0 + k] = t[a][b2];
             }
+            if (a == b2) u[i][k] = uinv[a];
         }
     __syncthreads();
-    invert_upper_triangle(d, u, sz, tid);
+    invert_upper_triangle<true>(d, u, sz, tid);
     for (int e = tid; e < kNB * kNB; e += 256) dinv[e] = u[e / kNB][e % kNB];
 }
 
@@ -156,6 +225,12 @@ extern "C" int prune_hessian_factor(float *h, int64_t n, int64_t ld_h, double da
     float *dinv = static_cast<float *>(ws);
     hipLaunchKernelGGL(damp_diagonal, dim3(1), dim3(1024), 0, stream, h, n, ld_h, damp, dead, info);
     if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
+    // Panels are taken in groups of kFactorGroup (aligned in the matrix).  A finished panel downdates at once only
+    // the columns of its own group that are still to be factored; the part left of the group receives the whole
+    // group's outer products in one product with a four times longer inner dimension once the group is done.  The
+    // downdate is a read-modify-write of the leading part of H with little arithmetic per byte, so this cuts most of
+    // the factorisation's memory traffic by four.  (The panels of a group lie side by side in h, so the long product
+    // reads them in place.)
     const int64_t n_blocks = ceil_div(n, kNB);
     for (int64_t b = n_blocks - 1; b >= 0; --b) {
         const int64_t c0 = b * kNB;
@@ -167,9 +242,19 @@ extern "C" int prune_hessian_factor(float *h, int64_t n, int64_t ld_h, double da
         // panel: R[0:m, block] = H[0:m, block] * inv(R_bb)^T, in place (a block of the product owns whole rows)
         int st = launch_gemm_f32<kBNK>(m, sz, sz, 1.f, h + c0, ld_h, dinv, kNB, 0.f, h + c0, ld_h, false, stream);
         if (st != PRUNE_OK) return st;
-        // downdate: H[0:m, 0:m] -= P P^T (upper tiles)
-        st = launch_gemm_f32<kBNK>(m, m, sz, -1.f, h + c0, ld_h, h + c0, ld_h, 1.f, h, ld_h, true, stream);
-        if (st != PRUNE_OK) return st;
+        const int64_t g0 = (b - b % kFactorGroup) * kNB;  // first column of the panel's group
+        if (g0 < c0) {
+            // H[0:m, g0:m] -= P P[g0:m]^T: the columns of the group still to come (upper tiles)
+            st = launch_gemm_f32<kBNK>(m, static_cast<int>(c0 - g0), sz, -1.f, h + c0, ld_h, h + g0 * ld_h + c0, ld_h, 1.f,
+                                       h + g0, ld_h, true, stream, static_cast<int>(g0));
+            if (st != PRUNE_OK) return st;
+        } else if (g0 > 0) {
+            // the group is complete: H[0:g0, 0:g0] -= P_group P_group^T (upper tiles), P_group = R[0:g0, g0:group end)
+            const int64_t group_end = g0 + kFactorGroup * kNB < n ? g0 + kFactorGroup * kNB : n;
+            st = launch_gemm_f32<kBNK>(static_cast<int>(g0), static_cast<int>(g0), static_cast<int>(group_end - g0), -1.f,
+                                       h + g0, ld_h, h + g0, ld_h, 1.f, h, ld_h, true, stream);
+            if (st != PRUNE_OK) return st;
+        }
     }
     return PRUNE_OK;
 }

@@ -24,12 +24,14 @@ template <int BL>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, float alpha, const float *A, int64_t lda,
                                                        const float *B, int64_t ldb, float beta, float *C,
                                                        int64_t ldc,
-                                                       int upper_tiles_only) {
+                                                       int upper_from) {
     __shared__ __attribute__((aligned(16))) float smem[2][kTileK][kPitch];
     float (&sa)[kTileK][kPitch] = smem[0];
     float (&sb)[kTileK][kPitch] = smem[1];
     const int m0 = blockIdx.y * kTileMN, n0 = blockIdx.x * kTileMN;
-    if (upper_tiles_only && n0 + kTileMN <= m0) return;  // tile strictly below the diagonal: not needed
+    // upper_from >= 0: column j of C is column upper_from + j of a square matrix whose row i is row i of C, and
+    // tiles strictly below that matrix's diagonal are not needed
+    if (upper_from >= 0 && upper_from + n0 + kTileMN <= m0) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
     f32x16 acc[2][2];
 #pragma unroll
@@ -179,16 +181,19 @@ inline bool gemm_operands_ok(const void *a, int64_t lda, const void *b, int64_t 
 }
 
 // C = beta * C + alpha * A * op(B) on `stream`; upper_tiles_only skips the 128 x 128 tiles strictly below
-// the diagonal of C (for symmetric updates of which only the upper triangle is used).  M, N < 2^31 / 128.
+// the diagonal of C (for symmetric updates of which only the upper triangle is used); when C is a block of
+// columns of a square matrix that starts at column upper_col0 (and at row 0), the diagonal meant is that
+// matrix's.  M, N < 2^31 / 128.
 template <int BL>
 inline int launch_gemm_f32(int M, int N, int K, float alpha, const float *A, int64_t lda, const float *B, int64_t ldb,
-                           float beta, float *C, int64_t ldc, bool upper_tiles_only, hipStream_t stream) {
+                           float beta, float *C, int64_t ldc, bool upper_tiles_only, hipStream_t stream,
+                           int upper_col0 = 0) {
     if (M <= 0 || N <= 0) return PRUNE_OK;
     const dim3 grid(static_cast<unsigned>(ceil_div(N, gemm_detail::kTileMN)),
                     static_cast<unsigned>(ceil_div(M, gemm_detail::kTileMN)));
     if (grid.y > 65535) return PRUNE_ERR_SHAPE;
     hipLaunchKernelGGL(gemm_detail::gemm_f32_kernel<BL>, grid, dim3(256), 0, stream, M, N, K, alpha, A, lda, B, ldb,
-                       beta, C, ldc, upper_tiles_only ? 1 : 0);
+                       beta, C, ldc, upper_tiles_only ? upper_col0 : -1);
     return launch_status();
 }
 

@@ -11,6 +11,9 @@ constexpr int kTriPitch = kTriN + 1;
 // d holds the triangle R (sz x sz live part, zeros elsewhere, visible to the block); u is all zero.  On exit u holds
 // R^-1 in its live sz x sz part and zeros elsewhere (visible to the block); d is used as scratch below its diagonal
 // and gets a unit diagonal past sz.  All 256 threads of the block must call.
+// HAVE_DIAG: the caller has already put the inverses of the eight 16 x 16 diagonal blocks into u (and a unit
+// diagonal past sz into d and u); the first level is then skipped.
+template <bool HAVE_DIAG = false>
 __device__ __forceinline__ void invert_upper_triangle(float (&d)[kTriN][kTriPitch], float (&u)[kTriN][kTriPitch], int sz,
                                                       int tid) {
     constexpr int kNB = kTriN;
@@ -19,18 +22,20 @@ __device__ __forceinline__ void invert_upper_triangle(float (&d)[kTriN][kTriPitc
     //   inv [A B; 0 D] = [inv A, -inv A * B * inv D; 0, inv D]
     // with the intermediate B * inv D parked in the unused lower triangle of d.  Rows and columns past sz carry a
     // unit diagonal, which leaves the live part unchanged.
-    if (tid < kNB && tid >= sz) d[tid][tid] = 1.f;
-    __syncthreads();
-    if (tid < kNB) {
-        const int j = tid, lo = j & ~15;
-        u[j][j] = 1.f / d[j][j];
-        for (int i = j - 1; i >= lo; --i) {
-            float acc = 0.f;
-            for (int k = i + 1; k <= j; ++k) acc = fmaf(d[i][k], u[k][j], acc);
-            u[i][j] = -acc / d[i][i];
+    if constexpr (!HAVE_DIAG) {
+        if (tid < kNB && tid >= sz) d[tid][tid] = 1.f;
+        __syncthreads();
+        if (tid < kNB) {
+            const int j = tid, lo = j & ~15;
+            u[j][j] = 1.f / d[j][j];
+            for (int i = j - 1; i >= lo; --i) {
+                float acc = 0.f;
+                for (int k = i + 1; k <= j; ++k) acc = fmaf(d[i][k], u[k][j], acc);
+                u[i][j] = -acc / d[i][i];
+            }
         }
+        __syncthreads();
     }
-    __syncthreads();
     for (int s = 16, ls = 4; s < kNB; s *= 2, ++ls) {
         // Every pair of this level is an s x s product, cut into 4 x 4 micro-tiles: (kNB / 2s) (s / 4)^2 = 8 s
         // micro-tiles, one per thread (s = 64 uses all 256).  Zeros below the diagonals of inv(A) and inv(D)

@@ -199,6 +199,7 @@ class ObsState:
     info: torch.Tensor                      # [n_activations] int32, 0 = factorisation went through
     ws: List[torch.Tensor]                  # one workspace per stream
     factor_ws: torch.Tensor                 # scratch of the factorisations on stream 0 (ws[0] belongs to the Hessian kernel)
+    gram_ws: torch.Tensor                   # the Hessian kernel's partial sums when sweeps run beside it (obs_layer)
     streams: List["torch.cuda.Stream"]
     factored: Dict[str, "torch.cuda.Event"] = field(default_factory=dict)
 
@@ -217,6 +218,8 @@ class ObsState:
                    ws=[torch.empty(need, dtype=torch.uint8, device=dev) for _ in range(n_streams)],
                    factor_ws=torch.empty(int(prune.load().prune_hessian_factor_workspace_bytes(128)),
                                          dtype=torch.uint8, device=dev),
+                   gram_ws=torch.empty(max(prune.hessian_workspace_bytes(act_tokens, ch) for ch in act_channels.values()),
+                                       dtype=torch.uint8, device=dev),
                    streams=[torch.cuda.Stream(device=dev) for _ in range(n_streams)])
 
 
@@ -278,6 +281,67 @@ def obs_prune_layer(st: LayerState, ob: ObsState, sparsities: Sequence[float], i
         done.record(side)
         main.wait_event(done)
     st.rowsq_valid = False      # st.pruned no longer holds what the masking pass summed
+
+
+def obs_layer(st: LayerState, ob: ObsState, acts: Dict[str, torch.Tensor], sparsities: Sequence[float],
+              damp: float = 0.01, in_place: bool = False, on_big=None, big: str = "") -> None:
+    """hessian_layer and obs_prune_layer as one schedule.  The Hessians are accumulated on the calling stream one
+    after the other (each fills the chip), the narrow ones first; as soon as one is there, its factorisation and
+    then the sweeps of the projections that read it are queued on the side streams, where they run beside the
+    Hessians still to come: a factorisation and a sweep are long chains of short kernels that leave most of the chip
+    idle.  Each task goes to the side stream with the least work queued so far (by a rough cost: panels of 128
+    columns times rows).  The calling stream waits for all of them at the end."""
+    main = torch.cuda.current_stream()
+    wait_factored(ob, main)
+    names = sorted(acts, key=lambda a: acts[a].shape[1])
+    load = [0.0] * len(ob.streams)
+    used = set()
+
+    def pick() -> int:
+        i = min(range(len(load)), key=lambda j: load[j])
+        used.add(i)
+        return i
+
+    for idx_a, a in enumerate(names):
+        x = acts[a]
+        ch = x.shape[1]
+        ob.hessian[a].zero_()
+        timed = on_big is not None and a == big
+        if timed:
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(main)
+        prune.hessian_accumulate(x, ob.hessian[a], ws=ob.gram_ws)
+        if timed:
+            e1.record(main)
+            on_big((e0, e1))
+        ready = torch.cuda.Event()
+        ready.record(main)
+        slot = pick()
+        side = ob.streams[slot]
+        side.wait_event(ready)
+        i_info = list(acts).index(a)
+        prune.hessian_factor(ob.hessian[a], damp, dead=ob.dead[a], info=ob.info[i_info:i_info + 1], ws=ob.ws[slot],
+                             stream=side)
+        done = torch.cuda.Event()
+        done.record(side)
+        ob.factored[a] = done
+        load[slot] += (ch / 128.0) * 1.6 * (ch / 4096.0) ** 0.5
+        readers = sorted((n for n in st.names if st.proj_inputs[n] == a), key=lambda n: -st.weights[n].numel())
+        for k, name in enumerate(readers):
+            w = st.weights[name]
+            slot_s = slot if k == 0 else pick()        # the first sweep follows its factor on the same stream
+            side_s = ob.streams[slot_s]
+            if slot_s != slot:
+                side_s.wait_event(done)
+            prune.obs_sweep(w, ob.hessian[a], float(sparsities[st.names.index(name)]),
+                            w_out=None if in_place else st.pruned[name], dead=ob.dead[a],
+                            mask_bits=st.mask_bits.get(name), ws=ob.ws[slot_s], stream=side_s)
+            load[slot_s] += (w.shape[1] / 128.0) * (1.0 + w.shape[0] / 8192.0)
+    for i in sorted(used):
+        fin = torch.cuda.Event()
+        fin.record(ob.streams[i])
+        main.wait_event(fin)
+    st.rowsq_valid = False
 
 
 # ----------------------------------------------------------------------------------------------------------------

@@ -358,9 +358,11 @@ def test_obs_fullsize_q_projection(lib):
     assert e_obs < e_plain
 
 
-def test_pipeline_streams_give_the_same_bits(lib):
-    """The layer-level helpers spread factorisations and sweeps over several streams: the results must be those of
-    plain one-after-the-other calls on the current stream, bit for bit, also when a step is repeated."""
+@pytest.mark.parametrize("fused", [False, True])
+def test_pipeline_streams_give_the_same_bits(lib, fused):
+    """The layer-level helpers spread factorisations and sweeps over several streams (fused: as one schedule in which
+    sweeps run beside the Hessians still to come): the results must be those of plain one-after-the-other calls on
+    the current stream, bit for bit, also when a step is repeated."""
     from paper_2504_06323_amd import pipeline
     cfg = synth.CONFIGS["toy"]
     shapes = synth.projection_shapes(cfg)
@@ -371,8 +373,11 @@ def test_pipeline_streams_give_the_same_bits(lib):
     ob = pipeline.ObsState.create(st, act_shapes, cfg.n_tokens)
     targets = [0.3 + 0.05 * i for i in range(len(shapes))]
     for _ in range(2):
-        pipeline.hessian_layer(ob, acts)
-        pipeline.obs_prune_layer(st, ob, targets)
+        if fused:
+            pipeline.obs_layer(st, ob, acts, targets)
+        else:
+            pipeline.hessian_layer(ob, acts)
+            pipeline.obs_prune_layer(st, ob, targets)
     _sync()
     assert ob.info.tolist() == [0] * len(acts)
     for i, (n, rows, cols, a) in enumerate(shapes):
