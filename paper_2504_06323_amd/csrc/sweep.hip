@@ -13,7 +13,7 @@
 // published sweep's weights at that moment are W_block + G_block inv(R_bb) (R_bb the diagonal block of R; this is
 // the block form of U = R^-1), so the saliencies (w / U_jj)^2 of a block need one 128 x 128 triangular inverse and
 // one small product per block.
-// Per block of 128 columns: (1) T = G_block inv(R_bb) on the matrix cores, saliency ((w + T) R_jj)^2; (2) the
+// Per block of 128 columns: (1) T = G_block inv(R_bb), saliency ((w + T) R_jj)^2, in one kernel; (2) the
 // floor(s * rows * width) smallest saliencies of the block are found exactly by a radix search over all rows
 // together (ties by row-major position); (3) one wave walks the 128 columns in order for four rows at a time, the
 // block of R in LDS; (4) fp32 matrix-core products add D R[finished, later] to G: after every block for the rest
@@ -75,28 +75,56 @@ __global__ __launch_bounds__(1024) void select_reset(uint32_t *hist) {
 }
 
 // Saliency of the block's entries at the moment the block starts, ((w + t) * R_jj)^2 with t = G_block inv(R_bb),
-// stored for the later passes and for the sweep, and the first pass of the radix search over them (16 rows a block).
+// stored for the later passes and for the sweep, and the first pass of the radix search over them.  A block takes
+// 16 rows: their part of G goes to LDS, a thread owns one column for eight of the rows and walks the column of
+// inv(R_bb) once (sums in ascending order of the inner index, fused multiply-adds).
 template <typename T>
 __global__ __launch_bounds__(256) void saliency_first_pass(const T *__restrict__ w, int64_t ld_w,
                                                            const float *__restrict__ r, int64_t ld_r,
-                                                           const uint8_t *__restrict__ dead, const float *__restrict__ t,
-                                                           int64_t rows, int64_t c0, int width, float *__restrict__ sal,
+                                                           const uint8_t *__restrict__ dead, const float *__restrict__ g,
+                                                           int64_t ldg, const float *__restrict__ dinv, int64_t rows,
+                                                           int64_t c0, int width, float *__restrict__ sal,
                                                            int64_t ld_sal, uint32_t *__restrict__ hist) {
     __shared__ uint32_t h[kHistBins];
+    __shared__ __attribute__((aligned(16))) float gs[16][kSB];
     const int tid = threadIdx.x;
     for (int b = tid; b < kHistBins; b += 256) h[b] = 0u;
-    __syncthreads();
     const int64_t r0 = static_cast<int64_t>(blockIdx.x) * 16;
     for (int e = tid; e < 16 * kSB; e += 256) {
         const int64_t row = r0 + (e >> 7);
         const int col = e & (kSB - 1);
-        if (row < rows && col < width) {
-            const bool off = dead && dead[c0 + col];
-            const float current = (off ? 0.f : widen(w[row * ld_w + c0 + col])) + t[row * kSB + col];
-            const float scaled = __fmul_rn(current, r[(c0 + col) * ld_r + c0 + col]);
-            const float s2 = __fmul_rn(scaled, scaled);
-            sal[row * ld_sal + col] = s2;
-            atomicAdd(&h[saliency_key(s2) >> 20], 1u);
+        gs[e >> 7][col] = (row < rows && col < width) ? g[row * ldg + c0 + col] : 0.f;
+    }
+    __syncthreads();
+    const int col = tid & (kSB - 1), rh = tid >> 7;  // rows r0 + rh + 2 q, q = 0..7
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    // inv(R_bb) is upper triangular and zero padded: the terms past the column's own index add nothing, and the
+    // width is a multiple of four
+#pragma unroll 2
+    for (int m = 0; m < width; m += 4) {
+        float dv[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) dv[u] = dinv[(m + u) * kSB + col];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const f32x4 gv = *reinterpret_cast<const f32x4 *>(&gs[rh + 2 * q][m]);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc[q] = fmaf(gv[u], dv[u], acc[q]);
+        }
+    }
+    if (col < width) {
+        const bool off = dead && dead[c0 + col];
+        const float rjj = r[(c0 + col) * ld_r + c0 + col];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int64_t row = r0 + rh + 2 * q;
+            if (row < rows) {
+                const float current = (off ? 0.f : widen(w[row * ld_w + c0 + col])) + acc[q];
+                const float scaled = __fmul_rn(current, rjj);
+                const float s2 = __fmul_rn(scaled, scaled);
+                sal[row * ld_sal + col] = s2;
+                atomicAdd(&h[saliency_key(s2) >> 20], 1u);
+            }
         }
     }
     __syncthreads();
@@ -293,8 +321,9 @@ __global__ __launch_bounds__(256) void sweep_block(const T *w, int64_t ld_w, T *
             pm1[q] = __ballot(p1);
             o0[q] = o1[q] = d0[q] = d1[q] = 0.f;
         }
-        for (int j = 0; j < n0; ++j) {  // columns 0..63 of the block
-            const float ri = rinv[j], rl0 = lane > j ? rb[j][lane] : 0.f, rl1 = rb[j][lane + 64];
+        // columns 0..63 of the block; the rows of R for four columns are fetched from LDS before the first of them is
+        // needed, so that a column's chain of dependent operations does not start with an LDS round trip
+        auto col_lo = [&](int j, float ri, float rl0, float rl1) {
 #pragma unroll
             for (int q = 0; q < NR; ++q) {
                 const float vj = lane_value(v0[q], j), wj = lane_value(w0[q], j);
@@ -307,9 +336,8 @@ __global__ __launch_bounds__(256) void sweep_block(const T *w, int64_t ld_w, T *
                 v0[q] = fmaf(dj, rl0, v0[q]);
                 v1[q] = fmaf(dj, rl1, v1[q]);
             }
-        }
-        for (int j = 64; j < width; ++j) {  // columns 64..127
-            const float ri = rinv[j], rl1 = lane + 64 > j ? rb[j][lane + 64] : 0.f;
+        };
+        auto col_hi = [&](int j, float ri, float rl1) {  // columns 64..127
 #pragma unroll
             for (int q = 0; q < NR; ++q) {
                 const float vj = lane_value(v1[q], j - 64), wj = lane_value(w1[q], j - 64);
@@ -321,7 +349,31 @@ __global__ __launch_bounds__(256) void sweep_block(const T *w, int64_t ld_w, T *
                 }
                 v1[q] = fmaf(dj, rl1, v1[q]);
             }
+        };
+        int j = 0;
+        for (; j + 4 <= n0; j += 4) {
+            float ri[4], rl0[4], rl1[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                ri[u] = rinv[j + u];
+                rl0[u] = lane > j + u ? rb[j + u][lane] : 0.f;
+                rl1[u] = rb[j + u][lane + 64];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) col_lo(j + u, ri[u], rl0[u], rl1[u]);
         }
+        for (; j < n0; ++j) col_lo(j, rinv[j], lane > j ? rb[j][lane] : 0.f, rb[j][lane + 64]);
+        for (j = 64; j + 4 <= width; j += 4) {
+            float ri[4], rl1[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                ri[u] = rinv[j + u];
+                rl1[u] = lane + 64 > j + u ? rb[j + u][lane + 64] : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) col_hi(j + u, ri[u], rl1[u]);
+        }
+        for (; j < width; ++j) col_hi(j, rinv[j], lane + 64 > j ? rb[j][lane + 64] : 0.f);
 #pragma unroll
         for (int q = 0; q < NR; ++q) {
             const int64_t row = base + q;
@@ -342,7 +394,7 @@ __global__ __launch_bounds__(256) void sweep_block(const T *w, int64_t ld_w, T *
 }
 
 struct SweepLayout {
-    size_t v, d, t, sal, dinv, hist, state, row_eq, row_before, total;
+    size_t v, d, sal, dinv, hist, state, row_eq, row_before, total;
 };
 
 SweepLayout sweep_layout(int64_t rows, int64_t cols, bool own_v) {
@@ -353,8 +405,6 @@ SweepLayout sweep_layout(int64_t rows, int64_t cols, bool own_v) {
     at += own_v ? up(static_cast<size_t>(rows) * cols * 4) : 0;
     l.d = at;
     at += up(static_cast<size_t>(rows) * kGroup * kSB * 4);
-    l.t = at;
-    at += up(static_cast<size_t>(rows) * kSB * 4);
     l.sal = at;
     at += up(static_cast<size_t>(rows) * kSB * 4);
     l.dinv = at;
@@ -377,7 +427,6 @@ int sweep_run(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld_w, in
               float *saliency, uint32_t *mask_bits, char *ws, const SweepLayout &l, hipStream_t stream) {
     float *dgroup = reinterpret_cast<float *>(ws + l.d);  // D of the current group of blocks, [rows, kGroup * kSB]
     constexpr int64_t ld_d = kGroup * kSB;
-    float *tbuf = reinterpret_cast<float *>(ws + l.t);
     float *dinv_all = reinterpret_cast<float *>(ws + l.dinv);
     uint32_t *hist = reinterpret_cast<uint32_t *>(ws + l.hist);
     SweepState *state = reinterpret_cast<SweepState *>(ws + l.state);
@@ -408,12 +457,9 @@ int sweep_run(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld_w, in
         const int64_t ld_sal = saliency ? cols : kSB;
         if (mode == 1 || saliency) {
             // the weights of the block as the published sweep holds them when the block starts: W + G inv(R_bb)
-            int st = launch_gemm_f32<kBKN>(static_cast<int>(rows), width, width, 1.f, g + c0, cols,
-                                           dinv_all + (b - first_block) * (kSB * kSB), kSB, 0.f, tbuf, kSB, false, stream);
-            if (st != PRUNE_OK) return st;
             const uint32_t k32 = static_cast<uint32_t>(mode == 1 ? k : 1);
-            hipLaunchKernelGGL(saliency_first_pass<T>, dim3(row_tiles), dim3(256), 0, stream, w, ld_w, r, ld_r, dead, tbuf,
-                               rows, c0, width, sal, ld_sal, hist);
+            hipLaunchKernelGGL(saliency_first_pass<T>, dim3(row_tiles), dim3(256), 0, stream, w, ld_w, r, ld_r, dead, g, cols,
+                               dinv_all + (b - first_block) * (kSB * kSB), rows, c0, width, sal, ld_sal, hist);
             hipLaunchKernelGGL(select_locate<0>, dim3(1), dim3(1024), 0, stream, state, hist, k32);
         }
         if (mode == 1) {
