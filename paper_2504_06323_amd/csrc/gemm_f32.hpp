@@ -3,8 +3,8 @@
 // A [M, K] row-major; op(B) = B for B [K, N] row-major (kBKN) or B^T for B [N, K] row-major (kBNK);
 // C [M, N] row-major.  K and every leading dimension are multiples of 4 and all bases 16-byte aligned
 // (checked by the callers), M and N are arbitrary.  A block of four waves owns a 128 x 128 tile of C
-// (64 x 64 per wave, four 32 x 32 x 2 MFMA accumulators), K is walked 32 at a time through LDS with both
-// operands stored k-major so that a wave reads 32 consecutive floats per MFMA operand.  One owner per
+// (64 x 64 per wave, four 32 x 32 x 2 MFMA accumulators), K is walked 32 at a time through a two-stage LDS buffer
+// with both operands stored k-major so that a wave reads 32 consecutive floats per MFMA operand.  One owner per
 // output element and a fixed order over K: results are reproducible.  C may be the same memory as A when N <= 128
 // (a block then reads all of its rows of A before it writes them).
 #pragma once
@@ -25,9 +25,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, floa
                                                        const float *B, int64_t ldb, float beta, float *C,
                                                        int64_t ldc,
                                                        int upper_from) {
-    __shared__ __attribute__((aligned(16))) float smem[2][kTileK][kPitch];
-    float (&sa)[kTileK][kPitch] = smem[0];
-    float (&sb)[kTileK][kPitch] = smem[1];
+    // two stages of both operand slices: a slice is parked in one stage while the matrix cores read the other
+    __shared__ __attribute__((aligned(16))) float smem[2][2][kTileK][kPitch];
     const int m0 = blockIdx.y * kTileMN, n0 = blockIdx.x * kTileMN;
     // upper_from >= 0: column j of C is column upper_from + j of a square matrix whose row i is row i of C, and
     // tiles strictly below that matrix's diagonal are not needed
@@ -70,7 +69,9 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, floa
             }
         }
     };
-    auto park = [&]() {
+    auto park = [&](int stage) {
+        float (&sa)[kTileK][kPitch] = smem[stage][0];
+        float (&sb)[kTileK][kPitch] = smem[stage][1];
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const int r = (tid >> 3) + 32 * p, kk = (tid & 7) * 4;
@@ -86,11 +87,14 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, floa
         }
     };
     fetch(0);
-    park();
+    park(0);
     __syncthreads();
-    for (int k0 = 0; k0 < K; k0 += kTileK) {
+    int stage = 0;
+    for (int k0 = 0; k0 < K; k0 += kTileK, stage ^= 1) {
         const bool more = k0 + kTileK < K;
         if (more) fetch(k0 + kTileK);
+        float (&sa)[kTileK][kPitch] = smem[stage][0];
+        float (&sb)[kTileK][kPitch] = smem[stage][1];
 #pragma unroll
         for (int kk = 0; kk < kTileK; kk += 2) {
             const int k = kk + (lane >> 5), c = lane & 31;
@@ -105,11 +109,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, floa
 #pragma unroll
                 for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
         }
+        // the other stage was last read before the barrier that ended the previous step: it can be written now,
+        // while the matrix cores still work on this one
+        if (more) park(stage ^ 1);
         __syncthreads();
-        if (more) {
-            park();
-            __syncthreads();
-        }
     }
     // Accumulator element v of lane l: row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32 of its 32 x 32 tile.
     // When C allows 16-byte accesses, a wave passes its tile through LDS eight rows at a time (the operand
@@ -118,7 +121,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, floa
     const bool wide = (ldc % 4 == 0) && (reinterpret_cast<uintptr_t>(C) % 16 == 0);
     if (wide) {
         constexpr int kEpPitch = 64 + 4;
-        float *ep = &smem[0][0][0] + wave * (8 * kEpPitch);
+        float *ep = &smem[0][0][0][0] + wave * (8 * kEpPitch);
         static_assert(4 * 8 * kEpPitch <= 2 * kTileK * kPitch, "the epilogue buffer fits in the operand slices");
 #pragma unroll
         for (int i = 0; i < 2; ++i)
