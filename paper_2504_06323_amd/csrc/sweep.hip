@@ -252,11 +252,14 @@ __device__ __forceinline__ float lane_value(float x, int lane) {
 }
 
 // A wave walks the columns of the block in order for NR rows at once (the rows are independent chains of
-// dependent operations, so they hide each other's latency; fewer rows per wave when there are few rows, so that
-// every SIMD still gets two waves).  mode: 0 nothing is pruned, 1 by the searched
+// dependent operations, so they hide each other's latency).  mode: 0 nothing is pruned, 1 by the searched
 // threshold, 2 everything.  Lane l owns columns l and l + 64 of the block.
+// Eight waves share a block's copy of R in LDS (two blocks fit a compute unit: four waves per SIMD); two rows per
+// wave measured best for every row count of the model shapes.
+constexpr int kSweepThreads = 512, kSweepWaves = kSweepThreads / 64, kSweepRows = 2;
+
 template <typename T, int NR>
-__global__ __launch_bounds__(256) void sweep_block(const T *w, int64_t ld_w, T *w_out, int64_t ld_out,
+__global__ __launch_bounds__(kSweepThreads) void sweep_block(const T *w, int64_t ld_w, T *w_out, int64_t ld_out,
                                                    const float *__restrict__ r, int64_t ld_r,
                                                    const uint8_t *__restrict__ dead, const float *__restrict__ g, int64_t ldg,
                                                    const float *__restrict__ sal, int64_t ld_sal, int64_t rows,
@@ -269,7 +272,7 @@ __global__ __launch_bounds__(256) void sweep_block(const T *w, int64_t ld_w, T *
     __shared__ float rb[kSB][kSBPitch];
     __shared__ float rinv[kSB];
     const int tid = threadIdx.x, lane = tid & 63;
-    for (int e = tid; e < kSB * kSB; e += 256) {
+    for (int e = tid; e < kSB * kSB; e += kSweepThreads) {
         const int i = e >> 7, k = e & (kSB - 1);
         rb[i][k] = (i <= k && k < width) ? r[(c0 + i) * ld_r + c0 + k] : 0.f;
     }
@@ -287,8 +290,8 @@ __global__ __launch_bounds__(256) void sweep_block(const T *w, int64_t ld_w, T *
     const int n0 = width < 64 ? width : 64;
     const float rd0 = valid0 ? rb[lane][lane] : 0.f, rd1 = valid1 ? rb[lane + 64][lane + 64] : 0.f;
     const unsigned long long live0 = __ballot(valid0), live1 = __ballot(valid1);
-    for (int64_t base = (static_cast<int64_t>(blockIdx.x) * 4 + (tid >> 6)) * NR; base < rows;
-         base += static_cast<int64_t>(gridDim.x) * 4 * NR) {
+    for (int64_t base = (static_cast<int64_t>(blockIdx.x) * kSweepWaves + (tid >> 6)) * NR; base < rows;
+         base += static_cast<int64_t>(gridDim.x) * kSweepWaves * NR) {
         float v0[NR], v1[NR], w0[NR], w1[NR], o0[NR], o1[NR], d0[NR], d1[NR];
         unsigned long long pm0[NR], pm1[NR];  // which columns of the row are pruned (uniform over the wave)
 #pragma unroll
@@ -444,8 +447,8 @@ int sweep_run(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld_w, in
     if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
     const unsigned row_tiles = static_cast<unsigned>(ceil_div(rows, 16));
     const unsigned row_quads = static_cast<unsigned>(ceil_div(rows, 4) < 512 ? ceil_div(rows, 4) : 512);
-    const int rows_per_wave = rows <= 8192 ? 2 : 4;
-    const unsigned row_groups = static_cast<unsigned>(ceil_div(rows, 4 * rows_per_wave) < 1024 ? ceil_div(rows, 4 * rows_per_wave) : 1024);
+    const unsigned row_groups = static_cast<unsigned>(ceil_div(rows, kSweepWaves * kSweepRows) < 1024
+                                                          ? ceil_div(rows, kSweepWaves * kSweepRows) : 1024);
     for (int64_t b = first_block; b < first_block + n_blocks; ++b) {
         const int64_t c0 = b * kSB;
         const int width = static_cast<int>(cols - c0 < kSB ? cols - c0 : kSB);
@@ -479,14 +482,9 @@ int sweep_run(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld_w, in
         const int64_t group0 = (b - slot) * kSB;
         const int64_t group_end = group0 + ld_d < cols ? group0 + ld_d : cols;
         float *dblk = dgroup + slot * kSB;
-        if (rows_per_wave == 2)
-            hipLaunchKernelGGL((sweep_block<T, 2>), dim3(row_groups), dim3(256), 0, stream, w, ld_w, w_out, ld_out, r, ld_r,
-                               dead, g, cols, sal, ld_sal, rows, c0, width, mode, state, row_before, dblk, ld_d, mask_bits,
-                               words, cols);
-        else
-            hipLaunchKernelGGL((sweep_block<T, 4>), dim3(row_groups), dim3(256), 0, stream, w, ld_w, w_out, ld_out, r, ld_r,
-                               dead, g, cols, sal, ld_sal, rows, c0, width, mode, state, row_before, dblk, ld_d, mask_bits,
-                               words, cols);
+        hipLaunchKernelGGL((sweep_block<T, kSweepRows>), dim3(row_groups), dim3(kSweepThreads), 0, stream, w, ld_w, w_out,
+                           ld_out, r, ld_r, dead, g, cols, sal, ld_sal, rows, c0, width, mode, state, row_before, dblk, ld_d,
+                           mask_bits, words, cols);
         if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
         const int64_t c1 = c0 + width;
         if (c1 < group_end) {
