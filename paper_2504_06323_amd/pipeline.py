@@ -284,7 +284,7 @@ def obs_prune_layer(st: LayerState, ob: ObsState, sparsities: Sequence[float], i
 
 
 def obs_layer(st: LayerState, ob: ObsState, acts: Dict[str, torch.Tensor], sparsities: Sequence[float],
-              damp: float = 0.01, in_place: bool = False, on_big=None, big: str = "") -> None:
+              damp: float = 0.01, in_place: bool = False, on_big=None, big: str = "", widest_first: bool = True) -> None:
     """hessian_layer and obs_prune_layer as one schedule.  The Hessians are accumulated on the calling stream one
     after the other (each fills the chip), the narrow ones first; as soon as one is there, its factorisation and
     then the sweeps of the projections that read it are queued on the side streams, where they run beside the
@@ -293,7 +293,7 @@ def obs_layer(st: LayerState, ob: ObsState, acts: Dict[str, torch.Tensor], spars
     columns times rows).  The calling stream waits for all of them at the end."""
     main = torch.cuda.current_stream()
     wait_factored(ob, main)
-    names = sorted(acts, key=lambda a: acts[a].shape[1])
+    names = sorted(acts, key=lambda a: -acts[a].shape[1] if widest_first else acts[a].shape[1])
     load = [0.0] * len(ob.streams)
     used = set()
 
