@@ -71,14 +71,25 @@ struct Const {
 __global__ __launch_bounds__(256, 2) void attention_tiles_bf16(const bf16_t *__restrict__ q, const bf16_t *__restrict__ k,
                                                             const bf16_t *__restrict__ v, bf16_t *__restrict__ o,
                                                             int seq_len, int heads, int kv_heads, int64_t ld_q,
-                                                            int64_t ld_k, int64_t ld_v, int64_t ld_o, float scale_log2e) {
+                                                            int64_t ld_k, int64_t ld_v, int64_t ld_o, float scale_log2e, int n_units) {
     __shared__ __attribute__((aligned(1024))) unsigned char ring[2][2][kTileBytes];  // [stage][K, V]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int q_tiles = (seq_len + kQueriesPerBlock - 1) / kQueriesPerBlock;
-    // the blocks with the most keys go first
-    const int qt = q_tiles - 1 - static_cast<int>(blockIdx.x % q_tiles);
-    const int head = static_cast<int>((blockIdx.x / q_tiles) % heads);
-    const int64_t seq = blockIdx.x / (static_cast<int64_t>(q_tiles) * heads);
+    // Workgroups go to the chip's eight dies round robin by their index, and a query tile's work grows with its
+    // position in the sequence: were tile j of every (sequence, head) simply block j of its group of q_tiles, a die
+    // would see the same few tile positions for the whole launch -- the heavy ones on some dies, the light ones on
+    // others -- and the launch would end with most dies idle (measured: 1.3 to 1.6 times slower).  So a die takes
+    // whole units -- a sequence's query heads that share one K / V head -- every eighth one: all positions, the
+    // heaviest first, the heads of a unit side by side, and everything that reads the same K and V shares that
+    // die's L2.
+    const int per_kv = heads / kv_heads, unit_blocks = per_kv * q_tiles;
+    const int die = static_cast<int>(blockIdx.x % kXcds), slot = static_cast<int>(blockIdx.x / kXcds);
+    const int unit = (slot / unit_blocks) * kXcds + die;
+    if (unit >= n_units) return;  // the whole block, before any barrier: padding of the last round of units
+    const int r = slot % unit_blocks;
+    const int qt = q_tiles - 1 - r / per_kv;
+    const int head = (unit % kv_heads) * per_kv + r % per_kv;
+    const int64_t seq = unit / kv_heads;
     const int kv_head = head / (heads / kv_heads);
     const int64_t t0 = seq * seq_len;
     const int q0 = qt * kQueriesPerBlock + 32 * wave;  // first query of this wave
@@ -246,7 +257,8 @@ bool launch_attention_tiles(const void *q, const void *k, const void *v, void *o
                             int64_t seq_len, int64_t heads, int64_t kv_heads, int64_t head_dim, int64_t ld_q,
                             int64_t ld_k, int64_t ld_v, int64_t ld_o, hipStream_t stream) {
     const int64_t q_tiles = ceil_div(seq_len, kQueriesPerBlock);
-    const int64_t blocks = n_seqs * heads * q_tiles;
+    const int64_t n_units = n_seqs * kv_heads;
+    const int64_t blocks = ceil_div(n_units, kXcds) * kXcds * (heads / kv_heads) * q_tiles;
     if (dtype != PRUNE_BF16 || head_dim != kHeadDim || seq_len > (1 << 24) || blocks >= (int64_t(1) << 31) ||
         ld_q % 8 != 0 || ld_k % 8 != 0 || ld_v % 8 != 0 || ld_o % 8 != 0 || !aligned_to(q, 16) || !aligned_to(k, 16) ||
         !aligned_to(v, 16) || !aligned_to(o, 16))
@@ -255,7 +267,7 @@ bool launch_attention_tiles(const void *q, const void *k, const void *v, void *o
     hipLaunchKernelGGL(attention_tiles_bf16, dim3(static_cast<unsigned>(blocks)), dim3(256), 0, stream,
                        static_cast<const bf16_t *>(q), static_cast<const bf16_t *>(k), static_cast<const bf16_t *>(v),
                        static_cast<bf16_t *>(o), static_cast<int>(seq_len), static_cast<int>(heads),
-                       static_cast<int>(kv_heads), ld_q, ld_k, ld_v, ld_o, scale_log2e);
+                       static_cast<int>(kv_heads), ld_q, ld_k, ld_v, ld_o, scale_log2e, static_cast<int>(n_units));
     return true;
 }
 
