@@ -63,6 +63,11 @@ __device__ __forceinline__ void pair_of(int p, int n_tiles, int &mt, int &nt) {
 constexpr int kRing = 4;
 constexpr int kSlabBytes = kStep * kTile * 2;
 
+template <int V>
+struct Whole {
+    static constexpr int value = V;
+};
+
 __device__ __forceinline__ bf16x8 operand_from_ring(const unsigned char *slab, int k16, int group, int i, int lane) {
     const int s = lane & 15, g = lane >> 4;
     const int row = k16 + 8 * (g >> 1) + (s >> 2);
@@ -107,26 +112,34 @@ __global__ __launch_bounds__(kGramBlock, 1) void gram_tiles_bf16(const bf16_t *_
         offa[p] = static_cast<uint32_t>((drow[p] * ld + cha) * 2);
         offb[p] = static_cast<uint32_t>((drow[p] * ld + chb) * 2);
     }
-    const char *xb = reinterpret_cast<const char *>(x);
-    auto issue_part = [&](int64_t stage_index, int p) {  // load instruction p (one for each slab) of a stage
+    // The address of a load is a uniform base, formed with scalar arithmetic, plus a per-lane byte offset that
+    // never changes (offa / offb): no vector instruction per load.  (Per-lane 64-bit addresses advanced or formed
+    // per stage cost 130 of a stage's 1600 cycles: the 64-bit vector additions run at a quarter of the rate and sit
+    // between four matrix instructions.)  Only a stage that reaches past the last token needs per-lane addresses;
+    // WHOLE says that the caller knows the stage to be whole, which keeps that code out of the steady-state loop.
+    const char *const xb = reinterpret_cast<const char *>(x) + t_begin * ld * 2;
+    const int64_t stage_bytes = static_cast<int64_t>(kStep) * ld * 2;
+    auto issue_part = [&](int64_t stage_index, int p, auto whole_c) {  // load instruction p (one for each slab) of a stage
+        constexpr bool kWhole = decltype(whole_c)::value != 0;
         // LDS byte address of this wave's first window in the stage's A slab (uniform over the wave)
         const uint32_t dst = __builtin_amdgcn_readfirstlane(
             static_cast<uint32_t>(reinterpret_cast<uintptr_t>((lds_byte *)&ring[stage_index & (kRing - 1)][0][0])) +
             static_cast<uint32_t>(wave) * 1024u);
-        const char *from;
-        if (stage_index < n_whole) {  // uniform: every token row of the stage exists
-            from = xb + (t_begin + stage_index * kStep) * ld * 2;
+        if (kWhole || stage_index < n_whole) {  // uniform: every token row of the stage exists
+            const char *from = xb + stage_index * stage_bytes;
+            load_to_lds(from, offa[p], dst + 4096u * p);
+            load_to_lds(from, offb[p], dst + kSlabBytes + 4096u * p);
         } else {  // rows past the last token re-read the last one (zeroed after landing, or never used)
             int64_t t = t_begin + stage_index * kStep + drow[p];
             t = t < n_tokens ? t : n_tokens - 1;
-            from = xb + t * ld * 2 - static_cast<int64_t>(drow[p]) * ld * 2;
+            const char *from = reinterpret_cast<const char *>(x) + t * ld * 2 - static_cast<int64_t>(drow[p]) * ld * 2;
+            load_to_lds(from + offa[p], dst + 4096u * p);
+            load_to_lds(from + offb[p], dst + kSlabBytes + 4096u * p);
         }
-        load_to_lds(from + offa[p], dst + 4096u * p);
-        load_to_lds(from + offb[p], dst + kSlabBytes + 4096u * p);
     };
     auto issue = [&](int64_t stage_index) {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) issue_part(stage_index, p);
+        for (int p = 0; p < 4; ++p) issue_part(stage_index, p, Whole<0>{});
     };
     // token rows past the end of a ragged last stage must count as zeros
     auto blank_tail = [&](int64_t stage_index) {
@@ -174,7 +187,7 @@ __global__ __launch_bounds__(kGramBlock, 1) void gram_tiles_bf16(const bf16_t *_
     auto mfma_one = [&](int set, int i, int j) {
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[set][i], b[set][j], acc[i][j], 0, 0, 0);
     };
-    for (int64_t s = 0; s < n_stages; ++s) {
+    auto trip = [&](int64_t s, auto whole_c) {  // stage s; whole_c: stage s + 4, whose loads are issued here, is known to be whole
         // first 12 MFMAs of the stage's first 16 tokens, interleaved with the 16 reads of its last 16 tokens
         __builtin_amdgcn_sched_barrier(0);
         read_a(1, s, 16);
@@ -193,13 +206,13 @@ __global__ __launch_bounds__(kGramBlock, 1) void gram_tiles_bf16(const bf16_t *_
         __syncthreads();    // ... and everyone's; and every wave has read all it needs of stage s from LDS:
         // its buffer takes the stage four ahead; the eight load instructions go between the next four MFMAs
         mfma_one(0, 3, 0);
-        issue_part(s + 4, 0);
+        issue_part(s + 4, 0, whole_c);
         mfma_one(0, 3, 1);
-        issue_part(s + 4, 1);
+        issue_part(s + 4, 1, whole_c);
         mfma_one(0, 3, 2);
-        issue_part(s + 4, 2);
+        issue_part(s + 4, 2, whole_c);
         mfma_one(0, 3, 3);
-        issue_part(s + 4, 3);
+        issue_part(s + 4, 3, whole_c);
         if (s + 1 == n_stages - 1 && n_whole < n_stages) blank_tail(s + 1);  // uniform
         // the 16 MFMAs of the last 16 tokens, interleaved with the 16 reads of the next stage's first 16 tokens
         __builtin_amdgcn_sched_barrier(0);
@@ -215,7 +228,10 @@ __global__ __launch_bounds__(kGramBlock, 1) void gram_tiles_bf16(const bf16_t *_
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
-    }
+    };
+    int64_t s = 0;
+    for (; s + 4 < n_whole && s < n_stages; ++s) trip(s, Whole<1>{});  // the steady state
+    for (; s < n_stages; ++s) trip(s, Whole<0>{});                     // the last few trips issue stages that may be ragged or absent
     MP_WAIT_VMCNT(0);  // nothing may still be landing in this block's LDS when it ends
 
     float *out = partials + (static_cast<int64_t>(split) * n_pairs + pair) * (kTile * kTile);

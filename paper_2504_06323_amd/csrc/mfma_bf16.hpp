@@ -25,6 +25,17 @@ __device__ __forceinline__ void load_to_lds(const void *src, uint32_t lds_addr) 
                  : "memory", "m0");
 }
 
+// The same with the address as a uniform 64-bit base (in scalar registers) plus a 32-bit byte offset per lane.  A
+// wave that has its SIMD to itself pays for every vector instruction between two matrix instructions, and 64-bit
+// vector additions run at a quarter of the rate: a caller whose per-lane part does not change from call to call
+// advances the base with scalar arithmetic and spends no vector instruction per load.
+__device__ __forceinline__ void load_to_lds(const void *base, uint32_t lane_offset, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :
+                 : "s"(lds_addr), "v"(lane_offset), "s"(base)
+                 : "memory", "m0");
+}
+
 // s_waitcnt with only the vector-memory counter set (6 bits: [3:0] and [15:14]); the others left at "no wait"
 #define MP_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt((((n) & 15) | (((n) >> 4) << 14)) | 0x0F70)
 

@@ -73,21 +73,28 @@ __global__ __launch_bounds__(kLinBlock, 1) void linear_tiles_bf16(const bf16_t *
     // Load instruction p of this wave fills LDS window 4 p + wave (16 rows of 64 bytes) of a slab: row
     // 16 (4 p + wave) + lane / 4, position lane % 4, i.e. packet (lane % 4) ^ ((row / 4) % 4).  Rows past the edge
     // of a matrix are clamped to its last row: they only feed outputs that are never stored.
-    const char *pa[4], *pb[4];
+    // The address of a load is a uniform base (the block's first row of x, or of the weight matrix the rows of load
+    // p come from, plus the stage's offset along K: scalar arithmetic) plus a per-lane byte offset that never
+    // changes -- no vector instruction per load (64-bit vector additions between the matrix instructions cost a wave
+    // that has its SIMD to itself a tenth of the kernel's time).
+    uint32_t offa[4], offb[4];
+    const char *base_b[4];
+    const char *const base_a = reinterpret_cast<const char *>(x + static_cast<int64_t>(m0) * ld_x);
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
         const int row = 16 * (4 * p + wave) + (lane >> 2);
         const int c = (lane & 3) ^ ((row >> 2) & 3);
-        const int xr = m0 + row < M ? m0 + row : M - 1;
-        pa[p] = reinterpret_cast<const char *>(x + static_cast<int64_t>(xr) * ld_x + 8 * c);
+        const int xr = m0 + row < M ? row : M - 1 - m0;  // relative to m0
+        offa[p] = static_cast<uint32_t>((static_cast<int64_t>(xr) * ld_x + 8 * c) * 2);
         const bf16_t *wsrc = w0;
-        int wr = n0 + row;
+        int wr = row;
         if (DUAL) {  // slab rows 0..127: gate channels n0 .. n0 + 127, rows 128..255: the same channels of up
-            wsrc = row < 128 ? w0 : w1;
-            wr = n0 + (row & 127);
+            wsrc = p < 2 ? w0 : w1;  // (rows 16 (4 p + wave) ... + 15: below 128 exactly for p = 0, 1)
+            wr = row & 127;
         }
-        wr = wr < N ? wr : N - 1;
-        pb[p] = reinterpret_cast<const char *>(wsrc + static_cast<int64_t>(wr) * ld_w + 8 * c);
+        wr = n0 + wr < N ? wr : N - 1 - n0;  // relative to n0
+        offb[p] = static_cast<uint32_t>((static_cast<int64_t>(wr) * ld_w + 8 * c) * 2);
+        base_b[p] = reinterpret_cast<const char *>(wsrc + static_cast<int64_t>(n0) * ld_w);
     }
     auto issue_part = [&](int stage_index, int p) {
         const uint32_t dst = __builtin_amdgcn_readfirstlane(
@@ -95,8 +102,8 @@ __global__ __launch_bounds__(kLinBlock, 1) void linear_tiles_bf16(const bf16_t *
             static_cast<uint32_t>(wave) * 1024u);
         // stages past the end re-read the last one (into a buffer nobody reads any more)
         const int64_t koff = static_cast<int64_t>(stage_index < n_stages ? stage_index : n_stages - 1) * (kLinStep * 2);
-        load_to_lds(pa[p] + koff, dst + 4096u * p);
-        load_to_lds(pb[p] + koff, dst + kLinSlabBytes + 4096u * p);
+        load_to_lds(base_a + koff, offa[p], dst + 4096u * p);
+        load_to_lds(base_b[p] + koff, offb[p], dst + kLinSlabBytes + 4096u * p);
     };
     auto issue = [&](int stage_index) {
 #pragma unroll
