@@ -204,30 +204,75 @@ __global__ __launch_bounds__(kGramBlock, 1) void gram_tiles_bf16(const bf16_t *_
         __builtin_amdgcn_sched_barrier(0);
         MP_WAIT_VMCNT(16);  // this thread's loads of stage s + 1 have landed (stages s + 2, s + 3 may be in flight)
         __syncthreads();    // ... and everyone's; and every wave has read all it needs of stage s from LDS:
-        // its buffer takes the stage four ahead; the eight load instructions go between the next four MFMAs
-        mfma_one(0, 3, 0);
-        issue_part(s + 4, 0, whole_c);
-        mfma_one(0, 3, 1);
-        issue_part(s + 4, 1, whole_c);
-        mfma_one(0, 3, 2);
-        issue_part(s + 4, 2, whole_c);
-        mfma_one(0, 3, 3);
-        issue_part(s + 4, 3, whole_c);
+        // its buffer takes the stage four ahead.
         if (s + 1 == n_stages - 1 && n_whole < n_stages) blank_tail(s + 1);  // uniform
-        // the 16 MFMAs of the last 16 tokens, interleaved with the 16 reads of the next stage's first 16 tokens
-        __builtin_amdgcn_sched_barrier(0);
-        read_a(0, s + 1, 0);
-        read_b(0, s + 1, 0);
+        // The remaining 20 MFMAs of the trip (the last four of the first 16 tokens, the 16 of the last 16 tokens) go
+        // in four groups of five, each behind two of the eight load instructions and interleaved with four of the 16
+        // reads of the next stage's first 16 tokens: a load instruction holds the wave for some 40 cycles, and the
+        // matrix cores only have the one instruction in flight to work on meanwhile.
+        {
+            const unsigned char *slab_a = &ring[(s + 1) & (kRing - 1)][0][0], *slab_b = &ring[(s + 1) & (kRing - 1)][1][0];
+            issue_part(s + 4, 0, whole_c);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_one(0, 3, 0);
+            mfma_one(0, 3, 1);
+            mfma_one(0, 3, 2);
+            mfma_one(0, 3, 3);
+            mfma_one(1, 0, 0);
+            a[0][0] = operand_from_ring(slab_a, 0, wm, 0, lane);
+            a[0][1] = operand_from_ring(slab_a, 0, wm, 1, lane);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+            for (int g = 0; g < 5; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            issue_part(s + 4, 1, whole_c);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_one(1, 0, 1);
+            mfma_one(1, 0, 2);
+            mfma_one(1, 0, 3);
+            mfma_one(1, 1, 0);
+            mfma_one(1, 1, 1);
+            a[0][2] = operand_from_ring(slab_a, 0, wm, 2, lane);
+            a[0][3] = operand_from_ring(slab_a, 0, wm, 3, lane);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) mfma_one(1, i, j);
+            for (int g = 0; g < 5; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            issue_part(s + 4, 2, whole_c);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_one(1, 1, 2);
+            mfma_one(1, 1, 3);
+            mfma_one(1, 2, 0);
+            mfma_one(1, 2, 1);
+            mfma_one(1, 2, 2);
+            b[0][0] = operand_from_ring(slab_b, 0, wn, 0, lane);
+            b[0][1] = operand_from_ring(slab_b, 0, wn, 1, lane);
 #pragma unroll
-        for (int g = 0; g < 16; ++g) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            for (int g = 0; g < 5; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            issue_part(s + 4, 3, whole_c);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_one(1, 2, 3);
+            mfma_one(1, 3, 0);
+            mfma_one(1, 3, 1);
+            mfma_one(1, 3, 2);
+            mfma_one(1, 3, 3);
+            b[0][2] = operand_from_ring(slab_b, 0, wn, 2, lane);
+            b[0][3] = operand_from_ring(slab_b, 0, wn, 3, lane);
+#pragma unroll
+            for (int g = 0; g < 5; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_barrier(0);
     };
     int64_t s = 0;
     for (; s + 4 < n_whole && s < n_stages; ++s) trip(s, Whole<1>{});  // the steady state

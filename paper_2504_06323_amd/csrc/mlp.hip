@@ -162,27 +162,73 @@ __global__ __launch_bounds__(kLinBlock, 1) void linear_tiles_bf16(const bf16_t *
         __builtin_amdgcn_sched_barrier(0);
         MP_WAIT_VMCNT(16);
         __syncthreads();
-        mfma_one(0, 3, 0);
-        issue_part(s + 4, 0);
-        mfma_one(0, 3, 1);
-        issue_part(s + 4, 1);
-        mfma_one(0, 3, 2);
-        issue_part(s + 4, 2);
-        mfma_one(0, 3, 3);
-        issue_part(s + 4, 3);
-        __builtin_amdgcn_sched_barrier(0);
-        read_a(0, s + 1, 0);
-        read_b(0, s + 1, 0);
+        // The remaining 20 MFMAs of the trip go in four groups of five, each behind two of the eight load
+        // instructions and interleaved with the reads of two of the next stage's eight operands (a load
+        // instruction holds the wave for some 40 cycles: spread out, less of that falls on idle matrix cores).
+        {
+            const unsigned char *slab_a = &ring[(s + 1) & (kLinRing - 1)][0][0], *slab_b = &ring[(s + 1) & (kLinRing - 1)][1][0];
+            auto b_base = [&](int j) { return DUAL ? (j >> 1) * 128 + wn * 64 + 32 * (j & 1) : wn * 128 + 32 * j; };
+            issue_part(s + 4, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_one(0, 3, 0);
+            mfma_one(0, 3, 1);
+            mfma_one(0, 3, 2);
+            mfma_one(0, 3, 3);
+            mfma_one(1, 0, 0);
+            a[0][0] = operand_rows(slab_a, wm * 128, 0, lane);
+            a[0][1] = operand_rows(slab_a, wm * 128 + 32, 0, lane);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+            for (int g = 0; g < 5; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            issue_part(s + 4, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_one(1, 0, 1);
+            mfma_one(1, 0, 2);
+            mfma_one(1, 0, 3);
+            mfma_one(1, 1, 0);
+            mfma_one(1, 1, 1);
+            a[0][2] = operand_rows(slab_a, wm * 128 + 64, 0, lane);
+            a[0][3] = operand_rows(slab_a, wm * 128 + 96, 0, lane);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) mfma_one(1, i, j);
+            for (int g = 0; g < 5; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            issue_part(s + 4, 2);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_one(1, 1, 2);
+            mfma_one(1, 1, 3);
+            mfma_one(1, 2, 0);
+            mfma_one(1, 2, 1);
+            mfma_one(1, 2, 2);
+            b[0][0] = operand_rows(slab_b, b_base(0), 0, lane);
+            b[0][1] = operand_rows(slab_b, b_base(1), 0, lane);
 #pragma unroll
-        for (int g = 0; g < 16; ++g) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            for (int g = 0; g < 5; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            issue_part(s + 4, 3);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_one(1, 2, 3);
+            mfma_one(1, 3, 0);
+            mfma_one(1, 3, 1);
+            mfma_one(1, 3, 2);
+            mfma_one(1, 3, 3);
+            b[0][2] = operand_rows(slab_b, b_base(2), 0, lane);
+            b[0][3] = operand_rows(slab_b, b_base(3), 0, lane);
+#pragma unroll
+            for (int g = 0; g < 5; ++g) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_barrier(0);
     }
     MP_WAIT_VMCNT(0);  // nothing may still be landing in this block's LDS when it ends
 
