@@ -162,7 +162,7 @@ __device__ __forceinline__ void select_one_row(const T *wrow, T *orow, uint32_t 
 }
 
 template <typename T, int BLOCK, int NCHUNK, bool FROM_SCORES>
-__global__ __launch_bounds__(BLOCK, (BLOCK == 64 ? 4 : NCHUNK <= 3 ? 8 : 6)) void select_rows_vec(const T *w, T *w_out, uint32_t cols, int64_t ld,
+__global__ __launch_bounds__(BLOCK, (BLOCK == 64 ? 4 : NCHUNK <= 3 ? 8 : NCHUNK == 4 ? 6 : 4)) void select_rows_vec(const T *w, T *w_out, uint32_t cols, int64_t ld,
                                                             int64_t ld_out, const float *__restrict__ norms,
                                                             const float *__restrict__ scores, uint32_t k,
                                                             int idx_bits, uint8_t *__restrict__ mask_bytes,
@@ -197,7 +197,7 @@ struct SelectArgs {
 };
 
 template <typename T, int BLOCK, int NCHUNK>
-__global__ __launch_bounds__(BLOCK, (BLOCK == 64 ? 4 : NCHUNK <= 3 ? 8 : 6)) void select_rows_batch(const SelectArgs args) {
+__global__ __launch_bounds__(BLOCK, (BLOCK == 64 ? 4 : NCHUNK <= 3 ? 8 : NCHUNK == 4 ? 6 : 4)) void select_rows_batch(const SelectArgs args) {
     __shared__ SelectSmem<BLOCK> sm;
     int p = 0;
     for (int i = 1; i < args.n; ++i)
@@ -209,7 +209,9 @@ __global__ __launch_bounds__(BLOCK, (BLOCK == 64 ? 4 : NCHUNK <= 3 ? 8 : 6)) voi
                                             static_cast<T *>(it.w_out) + row * it.ld_out, it.cols, it.norms, nullptr,
                                             k, it.idx_bits,
                                             it.mask_bytes ? it.mask_bytes + row * it.mask_row_bytes : nullptr,
-                                            it.mask_row_bytes, sm, it.row_sumsq ? it.row_sumsq + row : nullptr);
+                                            it.mask_row_bytes, sm,
+                                            // (the host never pairs row sums with more than 4 packets per thread)
+                                            NCHUNK > 4 ? nullptr : it.row_sumsq ? it.row_sumsq + row : nullptr);
 }
 
 // any width / pitch / alignment; keys are recomputed from memory on every digit pass
@@ -301,11 +303,23 @@ int launch_rows_sumsq_plain(const void *w, int64_t rows, int64_t cols, int64_t l
     return launch_status();
 }
 
-// waves per row grow with the row width so that a thread holds at most 4 packets (32 keys)
-inline void select_variant(int64_t cols, int &block, int &nchunk) {
+// Waves per row grow with the row width so that a thread holds at most 4 packets (32 keys).  Rows of more than
+// 1024 packets take eight waves, unless four waves with up to 7 packets per thread leave fewer thread slots
+// without a packet (14336 columns are 7 x 256 packets exactly but only 3.5 x 512): idle slots cost registers and
+// lanes, which is worth more here than the shorter per-thread chains of the wider block.  (Not when the row's sum
+// of squares is wanted as well: with that the seven-packet form no longer fits its registers.)
+inline void select_variant(int64_t cols, int elem_bytes, bool row_sums, int &block, int &nchunk) {
     const int64_t packets = cols / 8;
     block = packets <= 128 ? 64 : packets <= 256 ? 128 : packets <= 1024 ? 256 : 512;
     nchunk = static_cast<int>(ceil_div(packets, block));
+    if (block == 512 && !row_sums) {
+        const int64_t n256 = ceil_div(packets, 256);
+        // (n256 is 5 or 7 then; seven packets of 4-byte elements and their keys do not fit a thread's registers)
+        if (n256 <= (elem_bytes == 2 ? 7 : 5) && 256 * n256 < 512 * static_cast<int64_t>(nchunk)) {
+            block = 256;
+            nchunk = static_cast<int>(n256);
+        }
+    }
 }
 
 inline bool select_packets_ok(const void *w, const void *w_out, int64_t cols, int64_t ld, int64_t ld_out,
@@ -327,6 +341,8 @@ int launch_select_batch(const SelectArgs &args, int total_rows, int block, int n
     }
     if (block == 64) { MP_BATCH_BLOCK(64) }
     else if (block == 128) { MP_BATCH_BLOCK(128) }
+    else if (block == 256 && nchunk == 5) { MP_BATCH_CASE(256, 5); }
+    else if (block == 256 && nchunk == 7) { MP_BATCH_CASE(256, 7); }
     else if (block == 256) { MP_BATCH_BLOCK(256) }
     else { MP_BATCH_BLOCK(512) }
 #undef MP_BATCH_BLOCK
@@ -355,7 +371,7 @@ int launch_select(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld, 
                        static_cast<uint32_t>(cols), ld, ld_out, norms, scores, k, idx_bits, mb,                   \
                        static_cast<uint32_t>(mrb))
     int block, nchunk;
-    select_variant(cols, block, nchunk);
+    select_variant(cols, static_cast<int>(sizeof(T)), false, block, nchunk);
 #define MP_SELECT_BLOCK(BLOCK)                   \
     switch (nchunk) {                            \
         case 1: MP_SELECT_CASE(BLOCK, 1); break; \
@@ -365,6 +381,8 @@ int launch_select(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld, 
     }
     if (block == 64) { MP_SELECT_BLOCK(64) }
     else if (block == 128) { MP_SELECT_BLOCK(128) }
+    else if (block == 256 && nchunk == 5) { MP_SELECT_CASE(256, 5); }
+    else if (block == 256 && nchunk == 7) { MP_SELECT_CASE(256, 7); }
     else if (block == 256) { MP_SELECT_BLOCK(256) }
     else { MP_SELECT_BLOCK(512) }
 #undef MP_SELECT_BLOCK
@@ -491,7 +509,7 @@ extern "C" int prune_select_mask_batch(const prune_select_item *items, int n_ite
             continue;
         }
         int block, nchunk;
-        select_variant(q.cols, block, nchunk);
+        select_variant(q.cols, dtype == PRUNE_BF16 ? 2 : 4, q.row_sumsq != nullptr, block, nchunk);
         SelectArgs args;
         args.n = 0;
         int64_t total_rows = 0;
@@ -509,7 +527,7 @@ extern "C" int prune_select_mask_batch(const prune_select_item *items, int n_ite
             const prune_select_item &r = items[j];
             if (!batchable_item(r)) continue;
             int b2, c2;
-            select_variant(r.cols, b2, c2);
+            select_variant(r.cols, dtype == PRUNE_BF16 ? 2 : 4, r.row_sumsq != nullptr, b2, c2);
             if (b2 != block || c2 != nchunk) continue;
             if (args.n == kMaxSelectBatch || total_rows + r.rows > 0x7fffffff) {
                 const int st = flush();

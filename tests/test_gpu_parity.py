@@ -201,7 +201,8 @@ def _check_select(w, norms, k, scores=None, in_place=False):
 
 @pytest.mark.parametrize("dtype", DTYPES)
 @pytest.mark.parametrize("shape", [(256, 256), (688, 256), (256, 688), (19, 2056), (11, 4104), (9, 11008),
-                                   (7, 14336), (5, 16384), (6, 16392), (50, 7), (33, 130), (3, 8), (4, 1000)])
+                                   (7, 14336), (5, 16384), (6, 16392), (50, 7), (33, 130), (3, 8), (4, 1000),
+                                   (10, 8200), (6, 10240), (5, 13824), (5, 12296)])
 def test_select_vs_oracle(lib, dtype, shape):
     rows, cols = shape
     w, x = _rank_inputs(rows, cols, dtype, seed=rows * 13 + cols)
@@ -216,7 +217,7 @@ def test_select_vs_oracle(lib, dtype, shape):
 
 
 @pytest.mark.parametrize("dtype", DTYPES)
-@pytest.mark.parametrize("cols", [64, 688, 4096, 1001])
+@pytest.mark.parametrize("cols", [64, 688, 4096, 1001, 8200, 14336])
 def test_select_ties(lib, dtype, cols):
     """Many equal metrics: zeros, constant rows, few distinct values -- the index decides."""
     rows = 12
@@ -370,7 +371,7 @@ def test_toy_layer_end_to_end(lib):
 
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
-@pytest.mark.parametrize("shape,k", [((96, 4096), 2048), ((40, 5120), 3000), ((33, 1000), 400), ((64, 14336), 7000),
+@pytest.mark.parametrize("shape,k", [((96, 4096), 2048), ((40, 5120), 3000), ((33, 1000), 400), ((64, 14336), 7000), ((30, 8200), 4100),
                                      ((50, 256), 0), ((20, 77), 30), ((9, 4096), 4096)])
 def test_select_row_sums_of_squares(lib, dtype, shape, k):
     """The masking pass also hands out the sum of squares of every masked row (the row terms of the structured
