@@ -36,6 +36,9 @@ Parity status of each function:
                                    formula for normalize() or for the planner's scaling;
                                    pinned only by the invariants it states (mean = p,
                                    more outliers => pruned less, equal ranks => uniform p)
+  layer_ratios / plan_sparsity_layerwise
+                                   the pooled ratio is pinned (hand example, brute force); the spread inherits
+                                   plan_sparsity's status (PARITY UNPINNED against the paper, same invariants)
   select_smallest_per_row          pinned (brute-force sort, library top-k special case)
   group_magnitude / struct_rank    PARITY UNPINNED against the paper (no formula given for
                                    "lowest-magnitude" groups); pinned by brute force and
@@ -162,6 +165,34 @@ def plan_sparsity(ratios, p: float, lam: float, scope: str = "global", cols=None
     else:
         raise ValueError(scope)
 
+    clamped = False
+    if cols is not None:
+        upper = 1.0 - 1.0 / _f64(cols)
+        t = np.minimum(np.maximum(s, 0.0), upper)
+        clamped = bool(np.any(t != s))
+        s = t
+    return s, clamped
+
+
+def layer_ratios(counts, numels) -> np.ndarray:
+    """R_n = 100 * (outliers of layer n) / (parameters of layer n), from the N x M tables of per-projection
+    outlier counts and sizes: Algorithm 1's ratio taken over a whole layer, which is what the layer outlier
+    distribution compares between layers (Eq. 3, Eq. 4).  The counts are meant to be those against the
+    layer's mean (layer_outlier_stats)."""
+    c = np.asarray(counts, dtype=np.int64)
+    e = np.asarray(numels, dtype=np.int64)
+    assert c.ndim == 2 and c.shape == e.shape
+    return 100.0 * _f64(c.sum(axis=1)) / _f64(e.sum(axis=1))
+
+
+def plan_sparsity_layerwise(counts, numels, p: float, lam: float, cols=None):
+    """Layer pruning (Section 4.1.3, Pruning Methods, item 2; Section 3.1, layer / block-wise pruning):
+    one target p_n per layer, derived from the N layer ratios by the same normalise-and-spread rule as the
+    projection targets, and every projection of layer n is pruned by p_n.  The unweighted mean of p_n over
+    the layers is p (Eq. 1).  Returns (s [N, M], clamped_flag) like plan_sparsity."""
+    c = np.asarray(counts, dtype=np.int64)
+    s_layer, _ = plan_sparsity(layer_ratios(counts, numels)[:, None], p, lam, "global")
+    s = np.repeat(s_layer, c.shape[1], axis=1)
     clamped = False
     if cols is not None:
         upper = 1.0 - 1.0 / _f64(cols)

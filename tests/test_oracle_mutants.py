@@ -83,6 +83,10 @@ MUTANTS = {
     # planner
     "planner_more_outliers_pruned_more": ("plan_sparsity", lambda r, p, lam, scope="global", cols=None:
                                           (lambda s: (2 * p - s[0], s[1]))(_ORIG["plan_sparsity"](r, p, lam, scope, cols))),
+    "layer_ratio_is_mean_of_projection_ratios": ("layer_ratios", lambda c, e: (100.0 * _f64(c) / _f64(e)).mean(axis=1)),
+    "layer_ratio_not_in_percent_of_layer": ("layer_ratios", lambda c, e: 100.0 * _f64(c).sum(axis=1) / _f64(e)[:, 0]),
+    "layer_plan_not_shared_within_layer": ("plan_sparsity_layerwise", lambda c, e, p, lam, cols=None:
+                                           _ORIG["plan_sparsity"](100.0 * _f64(c) / _f64(e), p, lam, "global", cols)),
     "planner_no_recentering": ("plan_sparsity", lambda r, p, lam, scope="global", cols=None:
                                (p - 2 * lam * (_f64(r) - _f64(r).min()) / max(np.ptp(_f64(r)), 1e-300), False)),
     # structured

@@ -248,6 +248,42 @@ def test_planner_clamp_reports():
     assert orc.zeros_per_row(0.5, 688) == 344 and orc.zeros_per_row(0.4999, 256) == 127
 
 
+def test_hand_layer_planner(golden):
+    ex = golden["layer_planner"]
+    np.testing.assert_allclose(orc.layer_ratios(ex["counts"], ex["numels"]), ex["R_layer"], rtol=1e-14)
+    s, clamped = orc.plan_sparsity_layerwise(ex["counts"], ex["numels"], ex["p"], ex["lam"])
+    np.testing.assert_allclose(s, np.repeat(np.array(ex["s_layer"])[:, None], 2, axis=1), rtol=1e-14)
+    assert not clamped
+
+
+@pytest.mark.parametrize("p", [0.3, 0.7])
+def test_layer_planner_invariants(p):
+    rng = np.random.default_rng(12)
+    numels = rng.integers(1000, 100000, size=(32, 7))
+    counts = (numels * rng.uniform(0, 0.05, size=numels.shape)).astype(np.int64)
+    lam = 0.08
+    s, clamped = orc.plan_sparsity_layerwise(counts, numels, p, lam)
+    assert not clamped and s.shape == (32, 7)
+    assert (s == s[:, :1]).all()                                        # one target per layer
+    assert s[:, 0].mean() == pytest.approx(p, abs=1e-12)                # Eq. 1
+    assert s[:, 0].max() - s[:, 0].min() == pytest.approx(2 * lam, rel=1e-12)
+    # the layer ratio pools the layer's parameters: brute force over explicit outlier flags
+    pooled = [100.0 * sum(int(c) for c in counts[n]) / sum(int(e) for e in numels[n]) for n in range(32)]
+    np.testing.assert_allclose(orc.layer_ratios(counts, numels), pooled, rtol=1e-14)
+    order = np.argsort(pooled)
+    assert (np.diff(s[order, 0]) <= 1e-15).all()                        # more outliers => pruned less
+    # one projection per layer: layer pruning and projection pruning are the same plan
+    one, _ = orc.plan_sparsity_layerwise(counts[:, :1], numels[:, :1], p, lam)
+    want, _ = orc.plan_sparsity(100.0 * counts[:, :1] / numels[:, :1], p, lam)
+    np.testing.assert_allclose(one, want, rtol=0, atol=1e-15)
+    # equal layer ratios: global (uniform) pruning
+    flat, _ = orc.plan_sparsity_layerwise(np.full((4, 7), 5), np.full((4, 7), 100), p, lam)
+    np.testing.assert_array_equal(flat, np.full((4, 7), p))
+    # clamp by each projection's own width
+    cl, flag = orc.plan_sparsity_layerwise([[0, 0], [9, 9]], [[10, 10], [10, 10]], 0.9, 0.2, cols=[[4, 100], [4, 100]])
+    assert flag and cl[0, 0] == 0.75 and cl[0, 1] == pytest.approx(0.99) and cl[1, 0] == pytest.approx(0.7)
+
+
 # ----------------------------------------------------------------- row selection
 
 def _brute_select(row, k):
