@@ -62,7 +62,11 @@ typedef enum {
     PRUNE_OP_BATCH = 5    /* prune_score_outlier_batch: a constant, rows and cols are ignored (pass 1, 1) */
 } prune_op;
 
-typedef enum { PRUNE_SCOPE_GLOBAL = 0, PRUNE_SCOPE_CATEGORY = 1 } prune_scope;
+/* Which entries of the table of outlier ratios are compared with one another when targets are
+ * planned: all of them, those of one projection category across the layers, or -- layer pruning
+ * (Section 4.1.3, Pruning Methods, item 2) -- whole layers, each with one target for all its
+ * projections. */
+typedef enum { PRUNE_SCOPE_GLOBAL = 0, PRUNE_SCOPE_CATEGORY = 1, PRUNE_SCOPE_LAYER = 2 } prune_scope;
 
 /* Which mean an outlier is measured against: that of its own projection (Eq. 6, projection
  * outlier distribution) or that of all projections handed over together, i.e. of the layer
@@ -188,6 +192,11 @@ int prune_score_outlier_batch(const prune_projection *projs, int n_proj, int dty
  *   R = 100 * counts / numels;  within a scope (all entries, or one projection
  *   category across layers) r_hat = (R - min) / (max - min) and
  *   s = p + 2 * lambda * (mean(r_hat) - r_hat);  s = p when max == min.
+ * scope == PRUNE_SCOPE_LAYER (layer pruning, Section 4.1.3 Pruning Methods item
+ * 2; Section 3.1): the ratio is taken per layer, R_n = 100 * (sum of the layer's
+ * counts) / (sum of its numels) -- the counts then being those against the
+ * layer's mean (PRUNE_OUTLIERS_PER_LAYER) --, the n_layers ratios are normalised
+ * and spread by the same rule, and every projection of layer n gets s_n.
  * The unweighted mean of s is p, more outliers give a smaller s.  If cols is
  * non-NULL each s is clamped to [0, 1 - 1 / cols] and *clamped_out (optional)
  * is set to 1 when any clamp changed a value; zeros_per_row_out (optional,

@@ -75,7 +75,7 @@ extern "C" int prune_plan_sparsity(const unsigned long long *counts, const unsig
     if (!counts || !numels || !sparsity_out || (zeros_per_row_out && !cols)) return PRUNE_ERR_NULL;
     if (n_layers <= 0 || n_proj <= 0) return PRUNE_ERR_SHAPE;
     if (!(p >= 0.0 && p < 1.0) || !(lambda >= 0.0)) return PRUNE_ERR_RANGE;
-    if (scope != PRUNE_SCOPE_GLOBAL && scope != PRUNE_SCOPE_CATEGORY) return PRUNE_ERR_RANGE;
+    if (scope != PRUNE_SCOPE_GLOBAL && scope != PRUNE_SCOPE_CATEGORY && scope != PRUNE_SCOPE_LAYER) return PRUNE_ERR_RANGE;
     const int n = n_layers * n_proj;
     std::vector<double> ratio(n);
     for (int i = 0; i < n; ++i) {
@@ -86,12 +86,26 @@ extern "C" int prune_plan_sparsity(const unsigned long long *counts, const unsig
     if (scope == PRUNE_SCOPE_GLOBAL) {
         for (int i = 0; i < n; ++i) idx.push_back(i);
         spread(ratio, idx, p, lambda, sparsity_out);
-    } else {
+    } else if (scope == PRUNE_SCOPE_CATEGORY) {
         for (int m = 0; m < n_proj; ++m) {
             idx.clear();
             for (int l = 0; l < n_layers; ++l) idx.push_back(l * n_proj + m);
             spread(ratio, idx, p, lambda, sparsity_out);
         }
+    } else {
+        // one ratio per layer from the layer's pooled counts, held in the slot of its first projection, spread over
+        // the layers, then handed to the layer's other projections
+        for (int l = 0; l < n_layers; ++l) {
+            unsigned long long c = 0, e = 0;
+            for (int m = 0; m < n_proj; ++m) {
+                c += counts[l * n_proj + m];
+                e += numels[l * n_proj + m];
+            }
+            ratio[l * n_proj] = 100.0 * static_cast<double>(c) / static_cast<double>(e);
+            idx.push_back(l * n_proj);
+        }
+        spread(ratio, idx, p, lambda, sparsity_out);
+        for (int i = 0; i < n; ++i) sparsity_out[i] = sparsity_out[i - i % n_proj];
     }
     int clamped = 0;
     if (cols) {

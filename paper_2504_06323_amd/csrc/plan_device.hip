@@ -31,11 +31,14 @@ __device__ __forceinline__ double block_min_max(double v, bool take_max, double 
 }
 
 // One block.  Groups are the sets over which the ratios are normalised: all entries (n_groups == 1),
-// or, per projection type m, the entries l * n_proj + m (n_groups == n_proj).
+// or, per projection type m, the entries l * n_proj + m (n_groups == n_proj).  by_layer (layer pruning; n_groups
+// == n_proj then): the ratio of a layer's pooled counts sits in the slot of the layer's first projection, only
+// group 0 -- those slots -- is normalised and spread, and the layer's other projections copy the result.
 __global__ __launch_bounds__(kPlanBlock) void plan_kernel(const unsigned long long *__restrict__ counts,
                                                           const unsigned long long *__restrict__ numels,
                                                           const int64_t *__restrict__ cols, int n, int n_groups,
-                                                          double p, double lambda, double *__restrict__ sparsity,
+                                                          int by_layer, double p, double lambda,
+                                                          double *__restrict__ sparsity,
                                                           uint32_t *__restrict__ zeros_per_row,
                                                           int *__restrict__ flags) {
     __shared__ double scratch[kPlanBlock];
@@ -56,7 +59,18 @@ __global__ __launch_bounds__(kPlanBlock) void plan_kernel(const unsigned long lo
     }
     __syncthreads();
     const int per_group = n / n_groups;
-    for (int g = 0; g < n_groups; ++g) {
+    if (by_layer) {
+        for (int l = tid; l < per_group; l += kPlanBlock) {
+            unsigned long long c = 0, e = 0;
+            for (int m = 0; m < n_groups; ++m) {
+                c += counts[l * n_groups + m];
+                e += numels[l * n_groups + m];
+            }
+            sparsity[l * n_groups] = e ? 100.0 * static_cast<double>(c) / static_cast<double>(e) : 0.0;
+        }
+        __syncthreads();
+    }
+    for (int g = 0; g < (by_layer ? 1 : n_groups); ++g) {
         // entry j of group g sits at g + j * n_groups (n_groups == 1: all entries in order)
         double lo = INFINITY, hi = -INFINITY;
         for (int j = tid; j < per_group; j += kPlanBlock) {
@@ -106,6 +120,11 @@ __global__ __launch_bounds__(kPlanBlock) void plan_kernel(const unsigned long lo
         }
         __syncthreads();
     }
+    if (by_layer) {  // (the sources, slots l * n_groups, are not written here)
+        for (int i = tid; i < n; i += kPlanBlock)
+            if (i % n_groups) sparsity[i] = sparsity[i - i % n_groups];
+        __syncthreads();
+    }
     for (int i = tid; i < n; i += kPlanBlock) {
         const double width = static_cast<double>(cols[i] > 0 ? cols[i] : 1);
         const double hi = 1.0 - 1.0 / width;
@@ -136,13 +155,14 @@ extern "C" int prune_plan_sparsity_device(const unsigned long long *counts, cons
     if (!counts || !numels || !cols || !sparsity_out || !zeros_per_row_out || !flags_out) return PRUNE_ERR_NULL;
     if (n_layers <= 0 || n_proj <= 0 || static_cast<int64_t>(n_layers) * n_proj > (1 << 20)) return PRUNE_ERR_SHAPE;
     if (!(p >= 0.0 && p < 1.0) || !(lambda >= 0.0)) return PRUNE_ERR_RANGE;
-    if (scope != PRUNE_SCOPE_GLOBAL && scope != PRUNE_SCOPE_CATEGORY) return PRUNE_ERR_RANGE;
+    if (scope != PRUNE_SCOPE_GLOBAL && scope != PRUNE_SCOPE_CATEGORY && scope != PRUNE_SCOPE_LAYER) return PRUNE_ERR_RANGE;
     if (!aligned_to(counts, 8) || !aligned_to(numels, 8) || !aligned_to(cols, 8) || !aligned_to(sparsity_out, 8) ||
         !aligned_to(zeros_per_row_out, 4) || !aligned_to(flags_out, 4))
         return PRUNE_ERR_ALIGNMENT;
     const int n = n_layers * n_proj;
     const int n_groups = scope == PRUNE_SCOPE_GLOBAL ? 1 : n_proj;
     hipLaunchKernelGGL(plan_kernel, dim3(1), dim3(kPlanBlock), 0, static_cast<hipStream_t>(stream_), counts, numels,
-                       cols, n, n_groups, p, lambda, sparsity_out, zeros_per_row_out, flags_out);
+                       cols, n, n_groups, scope == PRUNE_SCOPE_LAYER ? 1 : 0, p, lambda, sparsity_out, zeros_per_row_out,
+                       flags_out);
     return launch_status();
 }

@@ -21,7 +21,7 @@ _lib = None
 
 F32, BF16 = 0, 1
 OP_STATS, OP_SCORE, OP_OUTLIER, OP_SELECT, OP_STRUCT, OP_BATCH = range(6)
-SCOPE_GLOBAL, SCOPE_CATEGORY = 0, 1
+SCOPE_GLOBAL, SCOPE_CATEGORY, SCOPE_LAYER = 0, 1, 2
 OUTLIERS_PER_PROJECTION, OUTLIERS_PER_LAYER = 0, 1
 
 _c = ctypes

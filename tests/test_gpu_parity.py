@@ -426,8 +426,8 @@ def test_struct_with_row_sums_from_the_masking_pass(lib, dtype):
 
 # ----------------------------------------------------------------- planner on the device
 
-@pytest.mark.parametrize("scope", ["global", "category"])
-@pytest.mark.parametrize("n_layers,n_proj", [(1, 7), (32, 7), (3, 300), (40, 7)])
+@pytest.mark.parametrize("scope", ["global", "category", "layer"])
+@pytest.mark.parametrize("n_layers,n_proj", [(1, 7), (32, 7), (3, 300), (40, 7), (300, 3)])
 def test_plan_device_vs_host_and_oracle(lib, scope, n_layers, n_proj):
     """Same bits as the host planner, same plan as the oracle; clamping, equal ratios and bad input flagged."""
     rng = np.random.default_rng(n_layers * 1000 + n_proj)
@@ -435,7 +435,7 @@ def test_plan_device_vs_host_and_oracle(lib, scope, n_layers, n_proj):
     cols = rng.choice([256, 688, 4096, 11008, 14336], size=n).astype(np.int64)
     numels = cols * rng.integers(8, 4096, size=n)
     counts = (numels * rng.uniform(0.001, 0.06, size=n)).astype(np.int64)
-    code = prune.SCOPE_GLOBAL if scope == "global" else prune.SCOPE_CATEGORY
+    code = {"global": prune.SCOPE_GLOBAL, "category": prune.SCOPE_CATEGORY, "layer": prune.SCOPE_LAYER}[scope]
     dev = lambda a, dt: torch.tensor(np.asarray(a), dtype=dt, device=DEV)
     for p, lam, cnt in ((0.5, 0.08, counts), (0.7, 0.08, counts), (0.05, 0.6, counts),      # the third clamps at 0
                         (0.5, 0.08, numels // 16)):                                          # equal ratios: s == p
@@ -450,12 +450,18 @@ def test_plan_device_vs_host_and_oracle(lib, scope, n_layers, n_proj):
         assert np.array_equal(to_np(s_dev).view(np.uint64), np.array(s_host).view(np.uint64))
         assert k_dev.tolist() == k_host and flags.tolist() == [int(clamped), 0]
         ratios = (100.0 * cnt / numels).reshape(n_layers, n_proj)
-        want, want_clamped = orc.plan_sparsity(ratios, p, lam, scope, cols=cols.reshape(n_layers, n_proj))
+        if scope == "layer":
+            want, want_clamped = orc.plan_sparsity_layerwise(cnt.reshape(n_layers, n_proj),
+                                                             numels.reshape(n_layers, n_proj), p, lam,
+                                                             cols=cols.reshape(n_layers, n_proj))
+        else:
+            want, want_clamped = orc.plan_sparsity(ratios, p, lam, scope, cols=cols.reshape(n_layers, n_proj))
         assert np.allclose(to_np(s_dev), want.reshape(-1), atol=1e-12) and bool(want_clamped) == clamped
         exact = [orc.zeros_per_row(v, c) for v, c in zip(want.reshape(-1), cols)]
         near_integer = np.abs(want.reshape(-1) * cols - np.round(want.reshape(-1) * cols)) < 1e-6
         assert all(a == b or t for a, b, t in zip(k_dev.tolist(), exact, near_integer))
-    assert np.all(to_np(s_dev) == 0.5)                                   # the last case: every ratio is 6.25
+    # the last case: every ratio is 6.25 (cols divide numels, so a layer's pooled ratio is 6.25 too)
+    assert np.all(to_np(s_dev) == 0.5)
     bad = counts.copy()
     bad[n // 2] = numels[n // 2] + 1
     prune.plan_sparsity_device(dev(bad, torch.int64), dev(numels, torch.int64), dev(cols, torch.int64), n_layers,
@@ -571,6 +577,58 @@ def test_layer_scope_outliers_vs_oracle(lib, dtype, aligned):
     prune.score_outlier_batch(ws_, norms, alpha, sums, per, outlier_scope=prune.OUTLIERS_PER_PROJECTION)
     _sync()
     assert per.tolist() != counts.tolist()                                     # the two rules really differ here
+
+
+def test_layer_pruning_ranked_planned_and_masked_on_the_device(lib):
+    """Layer pruning (Section 4.1.3, Pruning Methods, item 2) without a host round trip: outliers against each
+    layer's mean, one target per layer from the pooled layer ratios, every projection of a layer masked to it."""
+    shapes = [(256, 256), (64, 256), (688, 256), (256, 688)]
+    n_layers, n_proj, alpha, p, lam = 3, len(shapes), 4.0, 0.5, 0.08
+    n = n_layers * n_proj
+    counts = torch.zeros(n, dtype=torch.int64, device=DEV)
+    sums = torch.zeros(n, dtype=torch.float64, device=DEV)
+    layers = []
+    for l in range(n_layers):
+        ws_, norms = [], []
+        for i, (rows, cols) in enumerate(shapes):
+            w, x = _rank_inputs(rows, cols, torch.bfloat16, seed=4000 + 10 * l + i)
+            x[:, : 3 * (l + 1)] *= 12.0                  # more planted outlier channels in later layers
+            ws_.append(w)
+            norms.append(gpu_norms(x)[1])
+        layers.append((ws_, norms))
+        prune.score_outlier_batch(ws_, norms, alpha, sums[l * n_proj:(l + 1) * n_proj],
+                                  counts[l * n_proj:(l + 1) * n_proj], outlier_scope=prune.OUTLIERS_PER_LAYER)
+    numels = torch.tensor([r * c for r, c in shapes] * n_layers, dtype=torch.int64, device=DEV)
+    cols = torch.tensor([c for _, c in shapes] * n_layers, dtype=torch.int64, device=DEV)
+    s_dev = torch.empty(n, dtype=torch.float64, device=DEV)
+    k_dev = torch.empty(n, dtype=torch.int32, device=DEV)
+    flags = torch.empty(2, dtype=torch.int32, device=DEV)
+    prune.plan_sparsity_device(counts, numels, cols, n_layers, n_proj, p, lam, s_dev, k_dev, flags,
+                               scope=prune.SCOPE_LAYER)
+    outs = []
+    for l, (ws_, norms) in enumerate(layers):
+        o = [torch.empty_like(w) for w in ws_]
+        prune.select_mask_batch(ws_, norms, None, w_outs=o, ks_dev=k_dev[l * n_proj:(l + 1) * n_proj])
+        outs.append(o)
+    _sync()
+    assert flags.tolist() == [0, 0]
+    c2 = to_np(counts).reshape(n_layers, n_proj)
+    want, _ = orc.plan_sparsity_layerwise(c2, to_np(numels).reshape(n_layers, n_proj), p, lam,
+                                          cols=to_np(cols).reshape(n_layers, n_proj))
+    got = to_np(s_dev).reshape(n_layers, n_proj)
+    assert np.allclose(got, want, atol=1e-13) and (got == got[:, :1]).all()
+    assert got[:, 0].mean() == pytest.approx(p, abs=1e-12) and len(set(got[:, 0])) == n_layers
+    ratios = orc.layer_ratios(c2, to_np(numels).reshape(n_layers, n_proj))
+    assert (np.diff(got[np.argsort(ratios), 0]) < 0).all()                   # more outliers => pruned less
+    ks = k_dev.tolist()
+    for l in range(n_layers):
+        for i, (rows, cols_i) in enumerate(shapes):
+            k = ks[l * n_proj + i]
+            assert k == orc.zeros_per_row(got[l, i], cols_i)
+            w_in, w_out = to_np(layers[l][0][i]), to_np(outs[l][i])
+            omega = host_metric_f32(layers[l][0][i], layers[l][1][i])
+            pruned = orc.select_smallest_per_row(omega, k)
+            assert np.array_equal(w_out, orc.apply_mask(w_in, pruned))
 
 
 # ----------------------------------------------------------------- coupled groups (attention heads, grouped queries)

@@ -244,6 +244,40 @@ def test_planner_matches_hand_example(lib):
     assert k == [60, 40, 50, 50] and not clamped
 
 
+def test_layer_planner_matches_hand_example(lib):
+    ex = json.load(open(os.path.join(ROOT, "tests", "golden", "hand_examples.json")))["layer_planner"]
+    counts = [c for row in ex["counts"] for c in row]
+    numels = [e for row in ex["numels"] for e in row]
+    s, k, clamped = prune.plan_sparsity(counts, numels, 3, 2, ex["p"], ex["lam"], prune.SCOPE_LAYER, cols=[100] * 6)
+    np.testing.assert_allclose(np.array(s).reshape(3, 2), np.repeat(np.array(ex["s_layer"])[:, None], 2, axis=1),
+                               rtol=1e-14)
+    assert k == [60, 60, 40, 40, 50, 50] and not clamped
+
+
+@pytest.mark.parametrize("p", [0.3, 0.5, 0.7])
+def test_layer_planner_matches_oracle(lib, p):
+    rng = np.random.default_rng(22)
+    n_layers, n_proj = 32, 7
+    numels = rng.integers(1 << 20, 1 << 26, size=(n_layers, n_proj))
+    counts = (numels * rng.uniform(0, 0.05, size=numels.shape)).astype(np.int64)
+    cols = rng.choice([4096, 11008, 14336], size=numels.shape)
+    s, k, clamped = prune.plan_sparsity(counts.reshape(-1).tolist(), numels.reshape(-1).tolist(), n_layers, n_proj, p,
+                                        0.08, prune.SCOPE_LAYER, cols=cols.reshape(-1).tolist())
+    want, want_clamped = orc.plan_sparsity_layerwise(counts, numels, p, 0.08, cols=cols)
+    np.testing.assert_allclose(np.array(s).reshape(n_layers, n_proj), want, rtol=0, atol=1e-13)
+    assert clamped == want_clamped
+    assert k == [orc.zeros_per_row(v, c) for v, c in zip(np.array(s), cols.reshape(-1))]
+    # the three pruning methods side by side (Section 4.1.3): one target, one per layer, one per projection
+    uniform, _, _ = prune.plan_sparsity(counts.reshape(-1).tolist(), numels.reshape(-1).tolist(), n_layers, n_proj, p,
+                                        0.0, prune.SCOPE_GLOBAL)
+    per_proj, _, _ = prune.plan_sparsity(counts.reshape(-1).tolist(), numels.reshape(-1).tolist(), n_layers, n_proj, p,
+                                         0.08, prune.SCOPE_GLOBAL)
+    assert uniform == [p] * (n_layers * n_proj)
+    assert len(set(np.array(s).round(15))) == n_layers and len(set(per_proj)) == n_layers * n_proj
+    for plan in (uniform, s, per_proj):
+        assert np.mean(plan) == pytest.approx(p, abs=1e-12)
+
+
 @pytest.mark.parametrize("scope", [prune.SCOPE_GLOBAL, prune.SCOPE_CATEGORY])
 @pytest.mark.parametrize("p", [0.3, 0.5, 0.7])
 def test_planner_matches_oracle(lib, scope, p):
