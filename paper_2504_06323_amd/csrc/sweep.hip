@@ -15,8 +15,8 @@
 // one small product per block.
 // Per block of 128 columns: (1) T = G_block inv(R_bb), saliency ((w + T) R_jj)^2, in one kernel; (2) the
 // floor(s * rows * width) smallest saliencies of the block are found exactly by a radix search over all rows
-// together (ties by row-major position); (3) one wave walks the 128 columns in order for four rows at a time, the
-// block of R in LDS; (4) fp32 matrix-core products add D R[finished, later] to G: after every block for the rest
+// together (ties by row-major position); (3) the 128 columns are walked in order, a lane per row with the block of
+// R in LDS (or, for ragged blocks, a wave per two rows); (4) fp32 matrix-core products add D R[finished, later] to G: after every block for the rest
 // of its group of four blocks, after every group for everything beyond it.
 #include "gemm_f32.hpp"
 #include "tri_inverse.hpp"
@@ -424,6 +424,241 @@ SweepLayout sweep_layout(int64_t rows, int64_t cols, bool own_v) {
     return l;
 }
 
+// eight consecutive entries of a row (16-byte aligned), widened to fp32 / narrowed from it
+__device__ __forceinline__ void load_row_run(const bf16_t *p, float (&out)[8]) {
+    const u32x4 raw = *reinterpret_cast<const u32x4 *>(p);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        out[2 * e] = __uint_as_float(raw[e] << 16);
+        out[2 * e + 1] = __uint_as_float(raw[e] & 0xffff0000u);
+    }
+}
+__device__ __forceinline__ void load_row_run(const float *p, float (&out)[8]) {
+    const f32x4 a = *reinterpret_cast<const f32x4 *>(p), b = *reinterpret_cast<const f32x4 *>(p + 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        out[e] = a[e];
+        out[4 + e] = b[e];
+    }
+}
+__device__ __forceinline__ void store_row_run(bf16_t *p, const float *v) {
+    u32x4 raw;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        raw[e] = static_cast<uint32_t>(narrow_bf16(v[2 * e])) | (static_cast<uint32_t>(narrow_bf16(v[2 * e + 1])) << 16);
+    *reinterpret_cast<u32x4 *>(p) = raw;
+}
+__device__ __forceinline__ void store_row_run(float *p, const float *v) {
+    f32x4 a, b;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        a[e] = v[e];
+        b[e] = v[4 + e];
+    }
+    *reinterpret_cast<f32x4 *>(p) = a;
+    *reinterpret_cast<f32x4 *>(p + 4) = b;
+}
+
+// The same walk with a lane per row, for full blocks whose rows allow 16-byte accesses.  A workgroup of four waves
+// takes 64 rows; the block's 16 runs of eight columns are dealt to the waves round robin (wave x owns runs x, x + 4,
+// x + 8, x + 12), a lane holds its row's entries of its wave's 32 columns in registers.  The owner of a run walks
+// its eight columns (a multiplication, a subtraction and the updates inside the run per column) and publishes the
+// eight changes d of every row through LDS; after the one barrier per run, every wave adds d R[run, later] to the
+// later columns it owns, the entries of R being uniform over the wave (one LDS address per read, no conflicts).  The owner of the next run
+// brings that run up to date first, walks and publishes it, and only then updates its other columns, so that the
+// chain run -> barrier -> next run is as short as the arithmetic allows.  Every column receives its updates in
+// ascending order of the source column, as in the wave-per-two-rows form: the results are the same bits.
+constexpr int kRowLanes = 64, kRunCols = 8, kRuns = kSB / kRunCols, kRunsPerWave = kRuns / 4;
+
+template <typename T>
+__global__ __launch_bounds__(256) void sweep_block_rows(const T *__restrict__ w, int64_t ld_w, T *__restrict__ w_out,
+                                                        int64_t ld_out, const float *__restrict__ r, int64_t ld_r,
+                                                        const uint8_t *__restrict__ dead, const float *__restrict__ g,
+                                                        int64_t ldg, const float *__restrict__ sal, int64_t ld_sal,
+                                                        int64_t rows, int64_t c0, int mode,
+                                                        const SweepState *__restrict__ state,
+                                                        const uint32_t *__restrict__ row_before,
+                                                        float *__restrict__ dblk, int64_t ld_d,
+                                                        uint8_t *__restrict__ mask_bytes, int64_t words_per_row) {
+    __shared__ __attribute__((aligned(16))) float rs[kSB][kSB];  // the block of R (read with one address per wave)
+    __shared__ float rinv[kSB];
+    __shared__ float xch[2][kRunCols][kRowLanes];
+    __shared__ uint32_t eq_bits[4][kRowLanes];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const float *__restrict__ rb = r + c0 * ld_r + c0;  // the block of R: entry (i, k) at rb[i * ld_r + k]
+    if (tid < kSB) rinv[tid] = 1.f / rb[tid * ld_r + tid];
+    for (int e = tid; e < kSB * kSB / 4; e += 256) {
+        const int i = e >> 5, k4 = (e & 31) * 4;
+        *reinterpret_cast<f32x4 *>(&rs[i][k4]) = *reinterpret_cast<const f32x4 *>(rb + i * ld_r + k4);
+    }
+    const int64_t row_raw = static_cast<int64_t>(blockIdx.x) * kRowLanes + lane;
+    const bool live = row_raw < rows;
+    const int64_t row = live ? row_raw : rows - 1;  // lanes past the end compute on the last row and store nothing
+
+    // this lane's entries: register q = 8 i + jj holds column 8 (wv + 4 i) + jj of the block
+    float wq[32], vq[32];
+    uint32_t pruned = mode == 2 ? 0xffffffffu : 0u, equal = 0u;
+    uint32_t skey = 0u, need_eq = 0u;
+    bool all_eq = true;
+    if (mode == 1) {
+        skey = state->key;
+        need_eq = state->need_eq;
+        all_eq = need_eq == state->count_eq;
+    }
+#pragma unroll
+    for (int i = 0; i < kRunsPerWave; ++i) {
+        const int col = kRunCols * (wv + 4 * i);
+        float wf[8], gf[8];
+        load_row_run(w + row * ld_w + c0 + col, wf);
+        const f32x4 g0 = *reinterpret_cast<const f32x4 *>(g + row * ldg + c0 + col);
+        const f32x4 g1 = *reinterpret_cast<const f32x4 *>(g + row * ldg + c0 + col + 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            gf[e] = g0[e];
+            gf[4 + e] = g1[e];
+        }
+        if (mode == 1) {
+            const f32x4 s0 = *reinterpret_cast<const f32x4 *>(sal + row * ld_sal + col);
+            const f32x4 s1 = *reinterpret_cast<const f32x4 *>(sal + row * ld_sal + col + 4);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t key = saliency_key(e < 4 ? s0[e] : s1[e - 4]);
+                pruned |= (key < skey || (all_eq && key == skey) ? 1u : 0u) << (8 * i + e);
+                equal |= (key == skey ? 1u : 0u) << (8 * i + e);
+            }
+        }
+        // (the flags of the run's eight columns in one uniform load)
+        const uint64_t dead8 = dead ? *reinterpret_cast<const uint64_t *>(dead + c0 + col) : 0ull;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const bool is_dead = ((dead8 >> (8 * e)) & 0xffull) != 0ull;
+            wq[8 * i + e] = is_dead ? 0.f : wf[e];
+            vq[8 * i + e] = fmaf(wq[8 * i + e], rb[(col + e) * ld_r + col + e], gf[e]);  // (uniform address)
+        }
+    }
+    if (mode == 1 && !all_eq) {
+        // Of the entries with the threshold key, the first need_eq in row-major order go.  The waves exchange
+        // which of their columns hold that key; word k of a row's 128 flags is made of byte k of each wave's 32.
+        eq_bits[wv][lane] = equal;
+        __syncthreads();
+        uint32_t word[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            word[k] = 0u;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) word[k] |= ((eq_bits[x][lane] >> (8 * k)) & 0xffu) << (8 * x);
+        }
+        const uint32_t before = row_before[row];
+#pragma unroll
+        for (int i = 0; i < kRunsPerWave; ++i) {
+            uint32_t ahead = before;  // equal keys of this row in earlier words, then in this word before the run
+#pragma unroll
+            for (int k = 0; k < 4; ++k) ahead += k < i ? __popc(word[k]) : 0u;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int bit = 8 * wv + e;  // position of the column inside word i
+                const uint32_t rank = ahead + __popc(word[i] & ((1u << bit) - 1u));
+                const bool goes = ((equal >> (8 * i + e)) & 1u) && rank < need_eq;
+                pruned |= (goes ? 1u : 0u) << (8 * i + e);
+            }
+        }
+    }
+    __syncthreads();  // rinv, rs
+
+    // Eight rows of R (those of run `run`) at eight columns from `col`: fetched in one batch, so that a single LDS
+    // round trip is waited for and not one per row
+    struct RowRun {
+        f32x4 lo[kRunCols], hi[kRunCols];
+        __device__ __forceinline__ float at(int jj, int e) const { return e < 4 ? lo[jj][e] : hi[jj][e - 4]; }
+    };
+    auto fetch = [&](int run, int col, RowRun &rr) {
+#pragma unroll
+        for (int jj = 0; jj < kRunCols; ++jj) {
+            rr.lo[jj] = *reinterpret_cast<const f32x4 *>(&rs[kRunCols * run + jj][col]);
+            rr.hi[jj] = *reinterpret_cast<const f32x4 *>(&rs[kRunCols * run + jj][col + 4]);
+        }
+    };
+    // columns of run `run` (owned by this wave, registers 8 i ...): walk them and publish the changes; rw holds the
+    // run's own rows of R at its own columns, ri the reciprocals of its diagonal
+    auto walk = [&](int run, int i, const RowRun &rw, const float (&ri)[kRunCols]) {
+#pragma unroll
+        for (int jj = 0; jj < kRunCols; ++jj) {
+            const int q = 8 * i + jj;
+            const float prod = __fmul_rn(vq[q], ri[jj]);
+            const float wnew = ((pruned >> q) & 1u) ? 0.f : prod;
+            const float dj = wq[q] - wnew;
+            vq[q] = wnew;  // from here on the register holds the column's new weight ...
+            wq[q] = dj;    // ... and this one its change
+            xch[run & 1][jj][lane] = dj;
+#pragma unroll
+            for (int j2 = jj + 1; j2 < kRunCols; ++j2) vq[8 * i + j2] = fmaf(dj, rw.at(jj, j2), vq[8 * i + j2]);
+        }
+    };
+    // add d R[run, columns of own run i] for the eight changes d of a run, rr holding those rows of R
+    auto apply = [&](int i, const float (&d)[kRunCols], const RowRun &rr) {
+#pragma unroll
+        for (int jj = 0; jj < kRunCols; ++jj)
+#pragma unroll
+            for (int e = 0; e < kRunCols; ++e) vq[8 * i + e] = fmaf(d[jj], rr.at(jj, e), vq[8 * i + e]);
+    };
+    if (wv == 0) {
+        RowRun rw;
+        float ri[kRunCols];
+        fetch(0, 0, rw);
+#pragma unroll
+        for (int jj = 0; jj < kRunCols; ++jj) ri[jj] = rinv[jj];
+        walk(0, 0, rw, ri);
+    }
+#pragma clang loop unroll(full)
+    for (int run = 0; run + 1 < kRuns; ++run) {
+        const int next = run + 1, next_i = next >> 2;
+        const bool owner_of_next = wv == (next & 3);  // uniform
+        __builtin_amdgcn_sched_barrier(0);  // (reads of R are not to be moved up across trips: they would pile up in registers)
+        __syncthreads();  // the changes of `run` are in xch[run & 1]
+        float d[kRunCols];
+#pragma unroll
+        for (int jj = 0; jj < kRunCols; ++jj) d[jj] = xch[run & 1][jj][lane];
+        if (owner_of_next) {
+            RowRun ra, rw;
+            float ri[kRunCols];
+            fetch(run, kRunCols * next, ra);
+            fetch(next, kRunCols * next, rw);
+#pragma unroll
+            for (int jj = 0; jj < kRunCols; ++jj) ri[jj] = rinv[kRunCols * next + jj];
+            apply(next_i, d, ra);
+            walk(next, next_i, rw, ri);
+        }
+#pragma unroll
+        for (int i = 0; i < kRunsPerWave; ++i) {
+            // own run wv + 4 i lies after `run`, and is not the one just brought up to date
+            if (wv + 4 * i > run && !(owner_of_next && i == next_i)) {
+                RowRun rr;
+                __builtin_amdgcn_sched_barrier(0);
+                fetch(run, kRunCols * (wv + 4 * i), rr);
+                apply(i, d, rr);
+            }
+        }
+    }
+
+    if (!live) return;
+#pragma unroll
+    for (int i = 0; i < kRunsPerWave; ++i) {
+        const int col = kRunCols * (wv + 4 * i);
+        store_row_run(w_out + row * ld_out + c0 + col, &vq[8 * i]);
+        f32x4 d0, d1;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            d0[e] = wq[8 * i + e];
+            d1[e] = wq[8 * i + 4 + e];
+        }
+        *reinterpret_cast<f32x4 *>(dblk + row * ld_d + col) = d0;
+        *reinterpret_cast<f32x4 *>(dblk + row * ld_d + col + 4) = d1;
+        // keep-bits (bit set = kept): byte wv of word c0 / 32 + i of the row
+        if (mask_bytes) mask_bytes[(row * words_per_row + c0 / 32 + i) * 4 + wv] = static_cast<uint8_t>(~(pruned >> (8 * i)) & 0xffu);
+    }
+}
+
 template <typename T>
 int sweep_run(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld_w, int64_t ld_out, const float *r,
               int64_t ld_r, const uint8_t *dead, double sparsity, int64_t first_block, int64_t n_blocks, float *g,
@@ -482,9 +717,20 @@ int sweep_run(const T *w, T *w_out, int64_t rows, int64_t cols, int64_t ld_w, in
         const int64_t group0 = (b - slot) * kSB;
         const int64_t group_end = group0 + ld_d < cols ? group0 + ld_d : cols;
         float *dblk = dgroup + slot * kSB;
-        hipLaunchKernelGGL((sweep_block<T, kSweepRows>), dim3(row_groups), dim3(kSweepThreads), 0, stream, w, ld_w, w_out,
-                           ld_out, r, ld_r, dead, g, cols, sal, ld_sal, rows, c0, width, mode, state, row_before, dblk, ld_d,
-                           mask_bits, words, cols);
+        // full blocks whose rows can be read and written 16 bytes at a time take the lane-per-row form
+        const bool by_rows = width == kSB && aligned_to(w + c0, 16) && aligned_to(w_out + c0, 16) &&
+                             (ld_w * sizeof(T)) % 16 == 0 && (ld_out * sizeof(T)) % 16 == 0 && aligned_to(g + c0, 16) &&
+                             cols % 4 == 0 && aligned_to(sal, 16) && ld_sal % 4 == 0 && aligned_to(dblk, 16) &&
+                             (!dead || aligned_to(dead + c0, 8));
+        if (by_rows) {
+            hipLaunchKernelGGL(sweep_block_rows<T>, dim3(static_cast<unsigned>(ceil_div(rows, kRowLanes))), dim3(256), 0,
+                               stream, w, ld_w, w_out, ld_out, r, ld_r, dead, g, cols, sal, ld_sal, rows, c0, mode, state,
+                               row_before, dblk, ld_d, reinterpret_cast<uint8_t *>(mask_bits), words);
+        } else {
+            hipLaunchKernelGGL((sweep_block<T, kSweepRows>), dim3(row_groups), dim3(kSweepThreads), 0, stream, w, ld_w,
+                               w_out, ld_out, r, ld_r, dead, g, cols, sal, ld_sal, rows, c0, width, mode, state, row_before,
+                               dblk, ld_d, mask_bits, words, cols);
+        }
         if (launch_status() != PRUNE_OK) return PRUNE_ERR_DEVICE;
         const int64_t c1 = c0 + width;
         if (c1 < group_end) {

@@ -253,6 +253,9 @@ def test_sweep_ties_dead_channels_and_compensation(lib):
     plain = np.where(got_w == 0, 0.0, w0)
     assert obs.reconstruction_error(w0, got_w, h) < 0.97 * obs.reconstruction_error(w0, plain, h)   # (nearly independent channels: a few percent)
     assert obs.reconstruction_error(w0, got_w, h) <= 1.001 * obs.reconstruction_error(w0, want_w, h)
+    # the same splitting of equal saliencies in bf16 storage, with more rows than one workgroup of the walk takes
+    w0, got_w, _, _ = _sweep_case(70, 256, 1200, torch.bfloat16, 0.5, seed=79, zero_frac=0.6, dead_cols=(5,))
+    assert (got_w[:, 5] == 0).all() and (got_w[:, :128][w0[:, :128] != 0] != 0).all()
 
 
 def test_sweep_resumed_with_a_fresh_workspace_at_a_group_boundary(lib):
