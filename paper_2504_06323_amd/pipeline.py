@@ -284,25 +284,30 @@ def obs_prune_layer(st: LayerState, ob: ObsState, sparsities: Sequence[float], i
 
 
 def obs_layer(st: LayerState, ob: ObsState, acts: Dict[str, torch.Tensor], sparsities: Sequence[float],
-              damp: float = 0.01, in_place: bool = False, on_big=None, big: str = "", widest_first: bool = True) -> None:
+              damp: float = 0.01, in_place: bool = False, on_big=None, big: str = "") -> None:
     """hessian_layer and obs_prune_layer as one schedule.  The Hessians are accumulated on the calling stream one
-    after the other (each fills the chip), the narrow ones first; as soon as one is there, its factorisation and
-    then the sweeps of the projections that read it are queued on the side streams, where they run beside the
-    Hessians still to come: a factorisation and a sweep are long chains of short kernels that leave most of the chip
-    idle.  Each task goes to the side stream with the least work queued so far (by a rough cost: panels of 128
-    columns times rows).  The calling stream waits for all of them at the end."""
+    after the other; an accumulation fills the chip and next to nothing else runs beside it, so what matters is
+    what waits behind the last one.  The widest Hessian comes first (its factorisation and sweep are the longest
+    chain of the layer and get the head start), the others in the order of the sweep work that waits for them.
+    Each factorisation is queued on a side stream of its own as soon as its Hessian is there, all of them before any
+    sweep, so that no factorisation waits behind a sweep of another input.  The largest sweep of an input follows
+    its factorisation on the same stream; the others go, largest first, to the stream with the least work queued
+    (by a rough cost: panels of 128 columns times a factor for the rows).  The calling stream waits for all side
+    streams at the end."""
     main = torch.cuda.current_stream()
     wait_factored(ob, main)
-    names = sorted(acts, key=lambda a: -acts[a].shape[1] if widest_first else acts[a].shape[1])
-    load = [0.0] * len(ob.streams)
-    used = set()
+    n_side = len(ob.streams)
 
-    def pick() -> int:
-        i = min(range(len(load)), key=lambda j: load[j])
-        used.add(i)
-        return i
+    def sweep_cost(name: str) -> float:
+        w = st.weights[name]
+        return (w.shape[1] / 128.0) * (1.0 + w.shape[0] / 8192.0)
 
-    for idx_a, a in enumerate(names):
+    readers = {a: sorted((n for n in st.names if st.proj_inputs[n] == a), key=lambda n: -sweep_cost(n)) for a in acts}
+    widest = max(acts, key=lambda a: acts[a].shape[1])
+    names = [widest] + sorted((a for a in acts if a != widest), key=lambda a: -sum(sweep_cost(n) for n in readers[a]))
+    load = [0.0] * n_side
+    slot_of, done = {}, {}
+    for i, a in enumerate(names):
         x = acts[a]
         ch = x.shape[1]
         ob.hessian[a].zero_()
@@ -316,28 +321,34 @@ def obs_layer(st: LayerState, ob: ObsState, acts: Dict[str, torch.Tensor], spars
             on_big((e0, e1))
         ready = torch.cuda.Event()
         ready.record(main)
-        slot = pick()
+        slot = i % n_side if i < n_side else min(range(n_side), key=lambda j: load[j])
         side = ob.streams[slot]
         side.wait_event(ready)
         i_info = list(acts).index(a)
         prune.hessian_factor(ob.hessian[a], damp, dead=ob.dead[a], info=ob.info[i_info:i_info + 1], ws=ob.ws[slot],
                              stream=side)
-        done = torch.cuda.Event()
-        done.record(side)
-        ob.factored[a] = done
+        done[a] = torch.cuda.Event()
+        done[a].record(side)
+        ob.factored[a] = done[a]
+        slot_of[a] = slot
         load[slot] += (ch / 128.0) * 1.6 * (ch / 4096.0) ** 0.5
-        readers = sorted((n for n in st.names if st.proj_inputs[n] == a), key=lambda n: -st.weights[n].numel())
-        for k, name in enumerate(readers):
-            w = st.weights[name]
-            slot_s = slot if k == 0 else pick()        # the first sweep follows its factor on the same stream
-            side_s = ob.streams[slot_s]
-            if slot_s != slot:
-                side_s.wait_event(done)
-            prune.obs_sweep(w, ob.hessian[a], float(sparsities[st.names.index(name)]),
-                            w_out=None if in_place else st.pruned[name], dead=ob.dead[a],
-                            mask_bits=st.mask_bits.get(name), ws=ob.ws[slot_s], stream=side_s)
-            load[slot_s] += (w.shape[1] / 128.0) * (1.0 + w.shape[0] / 8192.0)
-    for i in sorted(used):
+
+    def sweep_on(name: str, a: str, slot: int) -> None:
+        side = ob.streams[slot]
+        if slot != slot_of[a]:
+            side.wait_event(done[a])
+        prune.obs_sweep(st.weights[name], ob.hessian[a], float(sparsities[st.names.index(name)]),
+                        w_out=None if in_place else st.pruned[name], dead=ob.dead[a],
+                        mask_bits=st.mask_bits.get(name), ws=ob.ws[slot], stream=side)
+        load[slot] += sweep_cost(name)
+
+    for a in names:                                   # the largest reader of an input stays with its factorisation
+        if readers[a]:
+            sweep_on(readers[a][0], a, slot_of[a])
+    rest = sorted(((n, a) for a in names for n in readers[a][1:]), key=lambda na: -sweep_cost(na[0]))
+    for name, a in rest:
+        sweep_on(name, a, min(range(n_side), key=lambda j: load[j]))
+    for i in range(n_side):
         fin = torch.cuda.Event()
         fin.record(ob.streams[i])
         main.wait_event(fin)
