@@ -95,7 +95,7 @@ __global__ __launch_bounds__(256) void factor_diagonal_block(float *__restrict__
             // lane i holds row i of the block; last column first: r_jj = sqrt(d_jj), R[i][j] = d[i][j] / r_jj (i < j),
             // d[i][k] -= R[i][j] R[k][j] (i <= k < j).  Entries below the diagonal are carried along and never read.
             const int lane = tid;
-            float r[kG], w[kG];
+            float r[kG], w[kG], rinv_of[kG];  // rinv_of[j] = 1 / r_jj (uniform over the lanes)
 #pragma unroll
             for (int q = 0; q < kG; q += 4) {
                 const f32x4 v = *reinterpret_cast<const f32x4 *>(&blk[lane][q]);
@@ -108,8 +108,14 @@ __global__ __launch_bounds__(256) void factor_diagonal_block(float *__restrict__
             for (int j = kG - 1; j >= 0; --j) {
                 const float pivot = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, r[j]), j));
                 if (!(pivot > 0.f) && info && lane == 0) atomicMax(info, static_cast<int>(c0) + 16 * jb + j + 1);
-                const float rjj = sqrtf(pivot);
-                r[j] = lane < j ? r[j] / rjj : lane == j ? rjj : 0.f;
+                // 1 / sqrt(pivot) from the hardware approximation and one Newton step (a relative error of a few
+                // 2^-24, like a correctly rounded square root followed by a division, in a fifth of the dependent
+                // instructions: this chain of 16 steps per group is what the whole block waits for); a pivot that is
+                // not positive gives NaN here as it would there
+                const float y0 = __builtin_amdgcn_rsqf(pivot);
+                const float y1 = fmaf(0.5f * y0, fmaf(-pivot * y0, y0, 1.f), y0);
+                rinv_of[j] = y1;
+                r[j] = lane < j ? r[j] * y1 : lane == j ? pivot * y1 : 0.f;
 #pragma unroll
                 for (int k = 0; k < j; ++k) {
                     const float rkj = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, r[j]), k));
@@ -126,8 +132,7 @@ __global__ __launch_bounds__(256) void factor_diagonal_block(float *__restrict__
                     const float rmk = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, r[k]), m));
                     acc = fmaf(-w[m], rmk, acc);
                 }
-                const float rkk = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, r[k]), k));
-                w[k] = acc / rkk;
+                w[k] = acc * rinv_of[k];
             }
 #pragma unroll
             for (int q = 0; q < kG; q += 4) {
