@@ -3,7 +3,8 @@
 // A [M, K] row-major; op(B) = B for B [K, N] row-major (kBKN) or B^T for B [N, K] row-major (kBNK);
 // C [M, N] row-major.  K and every leading dimension are multiples of 4 and all bases 16-byte aligned
 // (checked by the callers), M and N are arbitrary.  A block of four waves owns a 128 x 128 tile of C
-// (64 x 64 per wave, four 32 x 32 x 2 MFMA accumulators), K is walked 32 at a time through a two-stage LDS buffer
+// (64 x 64 per wave, four 32 x 32 x 2 MFMA accumulators) or, for small products, a 64 x 128 tile (32 x 64 per
+// wave); K is walked 32 at a time through a two-stage LDS buffer
 // with both operands stored k-major so that a wave reads 32 consecutive floats per MFMA operand.  One owner per
 // output element and a fixed order over K: results are reproducible.  C may be the same memory as A when N <= 128
 // (a block then reads all of its rows of A before it writes them).
@@ -20,21 +21,23 @@ namespace gemm_detail {
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 constexpr int kTileMN = 128, kTileK = 32, kPitch = kTileMN + 4;
 
-template <int BL>
+template <int BL, int TM>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, float alpha, const float *A, int64_t lda,
                                                        const float *B, int64_t ldb, float beta, float *C,
                                                        int64_t ldc,
                                                        int upper_from) {
     // two stages of both operand slices: a slice is parked in one stage while the matrix cores read the other
     __shared__ __attribute__((aligned(16))) float smem[2][2][kTileK][kPitch];
-    const int m0 = blockIdx.y * kTileMN, n0 = blockIdx.x * kTileMN;
+    static_assert(TM == 128 || TM == 64, "rows of C per block");
+    constexpr int TI = TM / 64;  // 32-row tiles of a wave
+    const int m0 = blockIdx.y * TM, n0 = blockIdx.x * kTileMN;
     // upper_from >= 0: column j of C is column upper_from + j of a square matrix whose row i is row i of C, and
     // tiles strictly below that matrix's diagonal are not needed
     if (upper_from >= 0 && upper_from + n0 + kTileMN <= m0) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
-    f32x16 acc[2][2];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, wm = (wave >> 1) * (TM / 2), wn = (wave & 1) * 64;
+    f32x16 acc[TI][2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TI; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -48,7 +51,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, floa
         for (int p = 0; p < 4; ++p) {
             const int r = (tid >> 3) + 32 * p, kk = (tid & 7) * 4;
             const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-            ra[p] = (m0 + r < M && k0 + kk < K) ? *reinterpret_cast<const f32x4 *>(A + (m0 + r) * lda + k0 + kk) : zero;
+            if (p < TM / 32)
+                ra[p] = (m0 + r < M && k0 + kk < K) ? *reinterpret_cast<const f32x4 *>(A + (m0 + r) * lda + k0 + kk) : zero;
             if (BL == kBNK) {
                 rbv[p] = (n0 + r < N && k0 + kk < K) ? *reinterpret_cast<const f32x4 *>(B + (n0 + r) * ldb + k0 + kk)
                                                      : zero;
@@ -75,8 +79,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, floa
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const int r = (tid >> 3) + 32 * p, kk = (tid & 7) * 4;
+            if (p < TM / 32) {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) sa[kk + e][r] = ra[p][e];
+                for (int e = 0; e < 4; ++e) sa[kk + e][r] = ra[p][e];
+            }
             if (BL == kBNK) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) sb[kk + e][r] = rbv[p][e];
@@ -98,14 +104,13 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, floa
 #pragma unroll
         for (int kk = 0; kk < kTileK; kk += 2) {
             const int k = kk + (lane >> 5), c = lane & 31;
-            float a[2], b[2];
+            float a[TI], b[2];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                a[i] = sa[k][wm + 32 * i + c];
-                b[i] = sb[k][wn + 32 * i + c];
-            }
+            for (int i = 0; i < TI; ++i) a[i] = sa[k][wm + 32 * i + c];
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int j = 0; j < 2; ++j) b[j] = sb[k][wn + 32 * j + c];
+#pragma unroll
+            for (int i = 0; i < TI; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
         }
@@ -124,7 +129,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, floa
         float *ep = &smem[0][0][0][0] + wave * (8 * kEpPitch);
         static_assert(4 * 8 * kEpPitch <= 2 * kTileK * kPitch, "the epilogue buffer fits in the operand slices");
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < TI; ++i)
 #pragma unroll
             for (int vq = 0; vq < 4; ++vq) {
 #pragma unroll
@@ -162,7 +167,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(int M, int N, int K, floa
         return;
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < TI; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -192,11 +197,18 @@ inline int launch_gemm_f32(int M, int N, int K, float alpha, const float *A, int
                            float beta, float *C, int64_t ldc, bool upper_tiles_only, hipStream_t stream,
                            int upper_col0 = 0) {
     if (M <= 0 || N <= 0) return PRUNE_OK;
-    const dim3 grid(static_cast<unsigned>(ceil_div(N, gemm_detail::kTileMN)),
-                    static_cast<unsigned>(ceil_div(M, gemm_detail::kTileMN)));
+    const int64_t tiles_n = ceil_div(N, gemm_detail::kTileMN), tiles_m = ceil_div(M, gemm_detail::kTileMN);
+    // A product with fewer 128-row tiles than the chip has compute units is a link in a chain of short kernels:
+    // 64-row tiles halve the time of each block and double their number (same operations on every element).
+    const bool small = tiles_n * tiles_m <= 256;
+    const dim3 grid(static_cast<unsigned>(tiles_n), static_cast<unsigned>(small ? ceil_div(M, 64) : tiles_m));
     if (grid.y > 65535) return PRUNE_ERR_SHAPE;
-    hipLaunchKernelGGL(gemm_detail::gemm_f32_kernel<BL>, grid, dim3(256), 0, stream, M, N, K, alpha, A, lda, B, ldb,
-                       beta, C, ldc, upper_tiles_only ? upper_col0 : -1);
+    if (small)
+        hipLaunchKernelGGL((gemm_detail::gemm_f32_kernel<BL, 64>), grid, dim3(256), 0, stream, M, N, K, alpha, A, lda, B,
+                           ldb, beta, C, ldc, upper_tiles_only ? upper_col0 : -1);
+    else
+        hipLaunchKernelGGL((gemm_detail::gemm_f32_kernel<BL, 128>), grid, dim3(256), 0, stream, M, N, K, alpha, A, lda,
+                           B, ldb, beta, C, ldc, upper_tiles_only ? upper_col0 : -1);
     return launch_status();
 }
 
