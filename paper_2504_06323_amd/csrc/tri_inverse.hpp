@@ -36,7 +36,9 @@ __device__ __forceinline__ void invert_upper_triangle(float (&d)[kTriN][kTriPitc
         }
         __syncthreads();
     }
-    for (int s = 16, ls = 4; s < kNB; s *= 2, ++ls) {
+    // The first merge (16 -> 32: sixteen-wide products, 64 threads) runs on the vector units below; the merges to 64
+    // and to 128 are products of 32 x 32 tiles on the matrix cores, one tile per wave.
+    for (int s = 16, ls = 4; s < 32; s *= 2, ++ls) {
         // Every pair of this level is an s x s product, cut into 4 x 4 micro-tiles: (kNB / 2s) (s / 4)^2 = 8 s
         // micro-tiles, one per thread (s = 64 uses all 256).  Zeros below the diagonals of inv(A) and inv(D)
         // make the plain products right.
@@ -93,6 +95,56 @@ __device__ __forceinline__ void invert_upper_triangle(float (&d)[kTriN][kTriPitc
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int jj = 0; jj < 4; ++jj) u[p + r0 + i][p + s + cc0 + jj] = -acc[i][jj];
+        }
+        __syncthreads();
+    }
+    typedef __attribute__((ext_vector_type(16))) float tri_f32x16;
+    const int lane = tid & 63, wave = tid >> 6;
+    for (int s = 32; s < kNB; s *= 2) {
+        const int tpd = s / 32;                                   // 32-wide tiles along a side of a pair's product
+        const bool active = wave < (kNB / (2 * s)) * tpd * tpd;   // two tiles at s = 32, four at s = 64
+        const int pair = wave / (tpd * tpd), tr = (wave / tpd) % tpd, tc = wave % tpd;
+        const int p = 2 * s * pair, hl = lane >> 5, ll = lane & 31;
+        // T = B * inv(D); inv(D) is upper triangular: column tile tc needs the inner indices below 32 (tc + 1)
+        if (active) {
+            tri_f32x16 acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+            const int k_end = 32 * (tc + 1);
+            for (int kc = 0; kc < k_end; kc += 32) {  // 32 inner indices at a time: all operands asked for at once
+                float a[16], b[16];
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    a[q] = d[p + 32 * tr + ll][p + s + kc + 2 * q + hl];
+                    b[q] = u[p + s + kc + 2 * q + hl][p + s + 32 * tc + ll];
+                }
+#pragma unroll
+                for (int q = 0; q < 16; ++q) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q], b[q], acc, 0, 0, 0);
+            }
+            // accumulator element v of lane l: row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32 of the tile
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                d[p + s + 32 * tr + 8 * (v >> 2) + 4 * hl + (v & 3)][p + 32 * tc + ll] = acc[v];
+        }
+        __syncthreads();
+        // inv(B-part) = -inv(A) * T; inv(A) is upper triangular: row tile tr needs the inner indices from 32 tr on
+        if (active) {
+            tri_f32x16 acc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+            for (int kc = 32 * tr; kc < s; kc += 32) {
+                float a[16], b[16];
+#pragma unroll
+                for (int q = 0; q < 16; ++q) {
+                    a[q] = u[p + 32 * tr + ll][p + kc + 2 * q + hl];
+                    b[q] = d[p + s + kc + 2 * q + hl][p + 32 * tc + ll];
+                }
+#pragma unroll
+                for (int q = 0; q < 16; ++q) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q], b[q], acc, 0, 0, 0);
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                u[p + 32 * tr + 8 * (v >> 2) + 4 * hl + (v & 3)][p + s + 32 * tc + ll] = -acc[v];
         }
         __syncthreads();
     }
