@@ -690,6 +690,21 @@ def run_prune_stage(args):
     torch.cuda.synchronize()
     ceilings = measure_ceilings(torch, prune, dev)
 
+    # The timed region above is a few tens of milliseconds.  The same steps are run once more for a couple of seconds
+    # (not part of `value`), so that the rate can be cross-checked against a clock or a utilisation sampler outside
+    # this process.
+    sustained = None
+    if args.sustain_seconds > 0:
+        n_sus = max(args.steps, int(1e3 * args.sustain_seconds / ms_per_step))
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for i in range(n_sus):
+            step(i, False)
+        torch.cuda.synchronize()
+        sus = time.perf_counter() - t1
+        sustained = {"steps": n_sus, "seconds": round(sus, 3), "ms_per_step": round(1e3 * sus / n_sus, 4),
+                     "value": numel * n_sus / sus}
+
     spans = [a.elapsed_time(b) / len(names) for a, b in stats_events]
     avg_ms, sd_ms = mean_sigma(spans)
     avg_bytes = stats_bytes / len(names)
@@ -767,6 +782,8 @@ def run_prune_stage(args):
         "passes": passes,
         "ceilings": ceilings,
     }
+    if sustained:
+        out["sustained"] = sustained
     if not args.no_cpu_baseline:
         layer0, st0, acts0 = ring[0]
         out["cpu_baseline"] = cpu_baseline(st0.weights, acts0)
@@ -794,6 +811,9 @@ def main():
     ap.add_argument("--struct-frac", type=float, default=0.2,
                     help="fraction of MLP channels removed structurally when the workload itself names none")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sustain-seconds", type=float, default=2.0,
+                    help="default stage: after the timed steps, run the same steps for about this long and report "
+                         "their rate as `sustained` (0: skip)")
     ap.add_argument("--obs-two-phases", action="store_true",
                     help="obs stage: all Hessians and factors, then all sweeps (two timed segments) instead of one "
                          "schedule in which the sweeps of a projection input start as soon as its factor is there")
